@@ -1,0 +1,221 @@
+/*
+ * kvq.h -- C ABI of the MI355X (gfx950) library for adaptive mixed-precision KV-cache decoding.
+ *
+ * The four hot-path calls follow the four stages of the paper's pipeline (Sec. 3.4 "Framework
+ * Overview"): token-level saliency features (Sec. 3.5), the controller that turns them into a
+ * bit width per token (Sec. 3.6), quantize-and-append of the token's K/V at that width
+ * (Sec. 3.7; Concat update of Sec. 3.2), and single-query decode attention over the resulting
+ * heterogeneous-precision cache (Sec. 3.2, a = Softmax(q K^T / sqrt(d_k)) V).
+ *
+ * Conventions shared by every call
+ *   - Return value: one of the KVQ_* status codes.  Nothing throws or aborts across this boundary;
+ *     kvq_last_error() returns a thread-local description of the last failure on this thread.
+ *   - Arguments are checked on the host before anything is launched: a call that returns an error
+ *     has launched nothing and changed no state.
+ *   - Pointers marked "device" are device memory owned by the caller and must stay valid until the
+ *     work enqueued by the call has run.  Pointers marked "host" are read before the call returns.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the default stream).
+ *     No call synchronizes unless its comment says so, and none of the four hot-path calls
+ *     allocates or frees device memory.
+ *   - Conditions that only the device can see (a page pool that runs dry, a sequence that would
+ *     outgrow max_context, a bit width that is not 2/4/8/16) never fault: the offending tokens are
+ *     dropped or stored as FP16, a sticky flag is raised in the cache, and kvq_cache_status()
+ *     reports it.
+ *   - Inputs must be finite.  NaN/Inf inputs give unspecified values, never a fault.
+ *   - head_dim is 64.  fp16 means IEEE binary16; "bits" are always 2, 4, 8 or 16 (16 = FP16 storage).
+ */
+#ifndef KVQ_H
+#define KVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVQ_HEAD_DIM 64
+#define KVQ_EXPORT_REC 128   /* bytes per packed vector in the canonical export */
+
+typedef enum {
+    KVQ_OK = 0,
+    KVQ_ERR_INVALID_ARG = 1,   /* null pointer, bad shape, bad layer index, ... */
+    KVQ_ERR_CAPACITY = 2,      /* request cannot fit the cache as configured */
+    KVQ_ERR_UNSUPPORTED = 3,   /* head_dim != 64, MLP wider than supported, ... */
+    KVQ_ERR_DEVICE = 4,        /* a HIP call failed */
+    KVQ_ERR_OOM = 5            /* arena too small / allocation failed */
+} kvq_status;
+
+/* sticky device-side flags reported by kvq_cache_status() */
+#define KVQ_FLAG_POOL_EXHAUSTED 1u   /* a class page pool ran dry; tokens went to a sink page */
+#define KVQ_FLAG_CONTEXT_FULL   2u   /* an append would exceed max_context; that sequence was skipped */
+#define KVQ_FLAG_BAD_BITS       4u   /* a bit width other than 2/4/8/16 was seen; stored as FP16 */
+
+typedef struct kvq_cache kvq_cache;   /* opaque */
+
+typedef struct {
+    int32_t n_layers;
+    int32_t max_seqs;        /* sequence slots 0 .. max_seqs-1 */
+    int32_t n_q_heads;       /* Hq, a multiple of n_kv_heads */
+    int32_t n_kv_heads;      /* Hkv; query head h reads kv-head h / (Hq/Hkv) */
+    int32_t head_dim;        /* must be 64 */
+    int32_t page_tokens;     /* tokens per page, a multiple of 256; 0 selects 256 */
+    int64_t max_context;     /* largest number of tokens one sequence may hold */
+    int64_t pool_pages[4];   /* pages available to the 2/4/8/16-bit classes; 0 = enough for every
+                                sequence to put max_context tokens into that class */
+    void *arena;             /* device memory for the whole cache, 256-byte aligned, or NULL to let
+                                kvq_cache_create allocate it with hipMalloc */
+    size_t arena_bytes;      /* size of `arena` (ignored when arena is NULL) */
+} kvq_cache_desc;
+
+/* Controller MLP (Sec. 3.6): n_linear linear layers dims[0] -> dims[1] -> ... -> dims[n_linear],
+ * ReLU after every layer but the last.  dims[0] = 4 (the feature vector), dims[n_linear] = 4 (one
+ * logit per precision class), hidden widths at most 256.  W[l] is row-major [dims[l+1]][dims[l]],
+ * b[l] is [dims[l+1]]; both fp32, device. */
+typedef struct {
+    int32_t n_linear;        /* 2 or 3 */
+    int32_t dims[5];
+    const float *W[4];
+    const float *b[4];
+} kvq_mlp;
+
+const char *kvq_version(void);
+const char *kvq_last_error(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Cache object: the heterogeneous-precision KV cache of Sec. 3.4 / 3.7.  Tokens of one sequence
+ * are kept in four precision buckets (2/4/8-bit codes with an fp16 scale and fp16 minimum per
+ * 64-vector, or raw fp16); attention is a sum over tokens, so bucket order does not change it.
+ * The device layout is private; kvq_cache_export() gives a layout-independent dump.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Bytes of device memory kvq_cache_create needs for `desc` (0 on an invalid descriptor). */
+size_t kvq_cache_arena_bytes(const kvq_cache_desc *desc);
+
+/* Creates a cache.  Synchronizes the device once (it clears the arena).  `*out` is owned by the
+ * caller until kvq_cache_destroy.  With desc->arena == NULL the arena is hipMalloc'd and freed on
+ * destroy; otherwise the caller keeps ownership of the arena. */
+int kvq_cache_create(const kvq_cache_desc *desc, kvq_cache **out);
+int kvq_cache_destroy(kvq_cache *cache);
+
+/* Empties every sequence and returns all pages to the pools; clears the sticky flags. */
+int kvq_cache_reset(kvq_cache *cache, void *stream);
+
+/* Empties the listed sequences and returns their pages.  seq_ids: device int32[n_seq], distinct. */
+int kvq_cache_free_seqs(kvq_cache *cache, const int32_t *seq_ids, int32_t n_seq, void *stream);
+
+/* Synchronizes `stream` and reports the sticky flags (KVQ_FLAG_*) and, if free_pages != NULL, the
+ * number of free pages left in each class (host int64[4]). */
+int kvq_cache_status(kvq_cache *cache, uint32_t *flags, int64_t *free_pages, void *stream);
+
+/* Synchronizes `stream` and copies per-sequence token counts to the host:
+ * counts is host int32[max_seqs][5] = tokens in the 2/4/8/16-bit classes and the total length. */
+int kvq_cache_counts(kvq_cache *cache, int32_t *counts, void *stream);
+
+/* Canonical dump of one (layer, sequence), in TOKEN order, for parity checks and save/restore.
+ *   bits_out  device uint8 [max_tokens]                      the width b of each token
+ *   codes_out device uint8 [max_tokens][Hkv][2][128]         index 0 = K, 1 = V.  b in {2,4,8}: element i
+ *                                                            occupies bits [i*b, i*b+b) of the byte
+ *                                                            stream (little-endian bit order), rest 0;
+ *                                                            b = 16: the 64 fp16 patterns, little-endian
+ *   meta_out  device uint16[max_tokens][Hkv][2][2]           fp16 bit patterns (scale, minimum); 0 for b = 16
+ * Only the first len(seq) tokens are written; max_tokens bounds the buffers (tokens beyond it are
+ * not written).  Read the length with kvq_cache_counts. */
+int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t seq, uint8_t *bits_out, uint8_t *codes_out,
+                     uint16_t *meta_out, int64_t max_tokens, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 1 -- token-level saliency features s_t = [H_t, R_t, V_t, C_t]  (Sec. 3.5)
+ *   H_t = -sum_v p(v) ln p(v), p = Softmax(logits row)          (entropy equation)
+ *   R_t = -ln((c(x_t)+1) / (N + |V_obs| + 1))                   (rarity equation)
+ *   V_t = mean over query heads of the population variance of the token's final-layer attention
+ *         probability row                                        (attention-variance equation)
+ *   C_t = max_v p(v)                                            (the "confidence term"; the paper
+ *         names it without a formula: this is the reading taken here)
+ *
+ *   logits     device fp32 [n][vocab], row-major
+ *   token_ids  device int32 [n], each in [0, vocab)
+ *   counts     device int64 [vocab]   running counts c(.)
+ *   totals     device int64 [2]       {N, |V_obs|}
+ *   update_counts  0: tables are read only.  1: after all n rows have been scored against the tables
+ *              as passed in, every token is counted (c[id] += 1, N += n, |V_obs| += number of distinct
+ *              ids whose count was 0); the result does not depend on thread order.
+ *   Attention variance takes exactly one of two sources:
+ *     attn_probs device fp32 [n][n_q_heads][ld]: the probability rows themselves, of which the first
+ *                attn_len[t] entries are used, or
+ *     sum_p2     device fp32 [n][n_q_heads]: sum_j p_j^2 of each row as emitted by kvq_decode_attn
+ *                (then Var = sum_p2/l - 1/l^2, because the row sums to one).
+ *   attn_len   device int32 [n], each >= 1
+ *   workspace  device, at least kvq_features_workspace(n, vocab) bytes, 256-byte aligned
+ *   feats_out  device fp32 [n][4] = H, R, V, C
+ * ------------------------------------------------------------------------------------------- */
+size_t kvq_features_workspace(int64_t n, int64_t vocab);
+int kvq_features(const float *logits, int64_t n, int64_t vocab, const int32_t *token_ids,
+                 int64_t *counts, int64_t *totals, int32_t update_counts,
+                 const float *attn_probs, const float *sum_p2, const int32_t *attn_len,
+                 int32_t n_q_heads, int64_t ld, float *feats_out,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 2 -- controller (Sec. 3.6): h1 = ReLU(W1 s + b1), h2 = ReLU(W2 h1 + b2), o = W3 h2 + b3,
+ * class = argmax_k o_k (the softmax of the paper is monotone and is skipped; the first maximum wins
+ * a tie), bits = {2,4,8,16}[class] (label mapping of Algorithm 1).
+ *   feats       device fp32 [n][4]
+ *   mlp         host struct; its W/b pointers are device memory
+ *   bits_out    device uint8 [n]
+ *   logits_out  device fp32 [n][4] or NULL
+ * ------------------------------------------------------------------------------------------- */
+int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp, uint8_t *bits_out,
+                   float *logits_out, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 3 -- quantize and append (Sec. 3.7: k^ = Q_b(k), v^ = Q_b(v); Sec. 3.2: K <- Concat(K, k)).
+ * Q_b for b in {2,4,8}, per (token, kv-head) vector x of 64 fp16 values, every step in IEEE binary32
+ * round-to-nearest-even:  levels = 2^b - 1;  scale = fp16((max x - min x) / levels);  the stored
+ * minimum is min x (a zero of either sign is stored as +0);  code_i = clamp(rint((x_i - min x) /
+ * fp32(scale)), 0, levels), all codes 0 when scale == 0;  x^_i = min + code_i * scale.  b = 16 stores
+ * x itself.  K and V are quantized independently with the same b; one b per token serves every
+ * layer and kv-head.
+ *
+ *   layer   0 .. n_layers-1, or -1 for all layers in one call
+ *   k, v    device fp16 [n_seq][T][Hkv][64]   (layer == -1: [n_layers][n_seq][T][Hkv][64])
+ *   bits    device uint8 [n_seq][T]; read only by the call that does the bookkeeping (below)
+ *   seq_ids device int32 [n_seq], distinct, or NULL for 0 .. n_seq-1
+ * Bookkeeping rule: the bucket slots, page allocation and bit-width log of the T new tokens are
+ * shared by all layers and are advanced by the call with layer == 0 (or layer == -1).  Calls with
+ * layer >= 1 write the K/V of the tokens appended by the latest layer-0 call on those sequences and
+ * must use the same n_seq, T and seq_ids; they ignore `bits`.
+ * ------------------------------------------------------------------------------------------- */
+int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const void *v, const uint8_t *bits,
+               const int32_t *seq_ids, int32_t n_seq, int32_t T, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 4 -- decode attention (Sec. 3.2): for every listed sequence and query head h,
+ *   s_j = (q_h . k^_j) / sqrt(64),  p = Softmax(s) over all cached tokens j (the newest included, in
+ *   its stored precision),  out_h = sum_j p_j v^_j,  with k^, v^ of kv-head h / (Hq/Hkv) dequantized
+ *   in registers.  fp32 accumulation.
+ *   q           device fp16 [n_seq][Hq][64]
+ *   seq_ids     device int32 [n_seq] or NULL for 0 .. n_seq-1
+ *   out         device fp32 [n_seq][Hq][64]; zeros for an empty sequence
+ *   lse_out     device fp32 [n_seq][Hq] or NULL: ln sum_j exp(s_j)  (-inf for an empty sequence)
+ *   sum_p2_out  device fp32 [n_seq][Hq] or NULL: sum_j p_j^2, the input of the attention-variance feature
+ *   workspace   device, at least kvq_decode_attn_workspace(cache, n_seq) bytes, 256-byte aligned
+ * ------------------------------------------------------------------------------------------- */
+size_t kvq_decode_attn_workspace(const kvq_cache *cache, int32_t n_seq);
+int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void *q, const int32_t *seq_ids,
+                    int32_t n_seq, float *out, float *lse_out, float *sum_p2_out,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Measurement helpers (not part of the method): a streaming read-reduce and a plain copy of `bytes`
+ * bytes (a multiple of 16), used to measure the attainable HBM rate next to the kernels above and to
+ * calibrate hardware byte counters against a transfer of known size.
+ *   src, dst  device, 16-byte aligned;  sink device uint32[1]
+ * ------------------------------------------------------------------------------------------- */
+int kvq_probe_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+int kvq_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQ_H */

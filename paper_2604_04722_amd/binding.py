@@ -1,0 +1,258 @@
+"""Thin ctypes binding of ``libkvq.so``: same names as the C ABI, argument marshalling only.
+
+Every step of the hot path runs in the library's HIP kernels.  PyTorch appears here only as the owner
+of device memory (``tensor.data_ptr()``) and of the stream the work is enqueued on.  There is no
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvq.so")
+
+KVQ_OK = 0
+FLAG_POOL_EXHAUSTED = 1
+FLAG_CONTEXT_FULL = 2
+FLAG_BAD_BITS = 4
+EXPORT_REC = 128
+
+EXPORTED_SYMBOLS = (
+    "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
+    "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_export",
+    "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_append", "kvq_decode_attn_workspace",
+    "kvq_decode_attn", "kvq_probe_read", "kvq_probe_copy",
+)
+
+
+class KvqError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("kvq status %d: %s" % (code, msg))
+        self.code = code
+
+
+class CacheDesc(ctypes.Structure):
+    _fields_ = [
+        ("n_layers", ctypes.c_int32), ("max_seqs", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("page_tokens", ctypes.c_int32),
+        ("max_context", ctypes.c_int64), ("pool_pages", ctypes.c_int64 * 4),
+        ("arena", ctypes.c_void_p), ("arena_bytes", ctypes.c_size_t),
+    ]
+
+
+class Mlp(ctypes.Structure):
+    _fields_ = [("n_linear", ctypes.c_int32), ("dims", ctypes.c_int32 * 5),
+                ("W", ctypes.c_void_p * 4), ("b", ctypes.c_void_p * 4)]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library.  Raises if it has not been built: there is no other path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    lib.kvq_version.restype = ctypes.c_char_p
+    lib.kvq_last_error.restype = ctypes.c_char_p
+    lib.kvq_cache_arena_bytes.restype = sz
+    lib.kvq_cache_arena_bytes.argtypes = [ctypes.POINTER(CacheDesc)]
+    lib.kvq_cache_create.argtypes = [ctypes.POINTER(CacheDesc), ctypes.POINTER(vp)]
+    lib.kvq_cache_destroy.argtypes = [vp]
+    lib.kvq_cache_reset.argtypes = [vp, vp]
+    lib.kvq_cache_free_seqs.argtypes = [vp, vp, i32, vp]
+    lib.kvq_cache_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(i64), vp]
+    lib.kvq_cache_counts.argtypes = [vp, vp, vp]
+    lib.kvq_cache_export.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp]
+    lib.kvq_features_workspace.restype = sz
+    lib.kvq_features_workspace.argtypes = [i64, i64]
+    lib.kvq_features.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp, sz, vp]
+    lib.kvq_controller.argtypes = [vp, i64, ctypes.POINTER(Mlp), vp, vp, vp]
+    lib.kvq_append.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, vp]
+    lib.kvq_decode_attn_workspace.restype = sz
+    lib.kvq_decode_attn_workspace.argtypes = [vp, i32]
+    lib.kvq_decode_attn.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.kvq_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.kvq_probe_copy.argtypes = [vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != KVQ_OK:
+        raise KvqError(rc, load_library().kvq_last_error().decode())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, name: str = "tensor") -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    return t.data_ptr()
+
+
+def kvq_version() -> str:
+    return load_library().kvq_version().decode()
+
+
+class Cache:
+    """Owner of one ``kvq_cache`` handle."""
+
+    def __init__(self, n_layers: int, max_seqs: int, n_q_heads: int, n_kv_heads: int, max_context: int,
+                 page_tokens: int = 0, pool_pages: Sequence[int] = (0, 0, 0, 0), head_dim: int = 64,
+                 arena: Optional[torch.Tensor] = None):
+        lib = load_library()
+        self.desc = CacheDesc()
+        self.desc.n_layers, self.desc.max_seqs = n_layers, max_seqs
+        self.desc.n_q_heads, self.desc.n_kv_heads, self.desc.head_dim = n_q_heads, n_kv_heads, head_dim
+        self.desc.page_tokens, self.desc.max_context = page_tokens, max_context
+        for c in range(4):
+            self.desc.pool_pages[c] = int(pool_pages[c])
+        self._arena = arena
+        if arena is not None:
+            self.desc.arena = _ptr(arena, torch.uint8, "arena")
+            self.desc.arena_bytes = arena.numel()
+        self.handle = ctypes.c_void_p(None)
+        _check(lib.kvq_cache_create(ctypes.byref(self.desc), ctypes.byref(self.handle)))
+        self.n_layers, self.max_seqs, self.Hq, self.Hkv, self.max_context = n_layers, max_seqs, n_q_heads, n_kv_heads, max_context
+
+    @staticmethod
+    def arena_bytes(n_layers, max_seqs, n_q_heads, n_kv_heads, max_context, page_tokens=0, pool_pages=(0, 0, 0, 0)) -> int:
+        d = CacheDesc()
+        d.n_layers, d.max_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim = n_layers, max_seqs, n_q_heads, n_kv_heads, 64
+        d.page_tokens, d.max_context = page_tokens, max_context
+        for c in range(4):
+            d.pool_pages[c] = int(pool_pages[c])
+        return int(load_library().kvq_cache_arena_bytes(ctypes.byref(d)))
+
+    def destroy(self) -> None:
+        if self.handle:
+            _check(load_library().kvq_cache_destroy(self.handle))
+            self.handle = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def reset(self, stream=None) -> None:
+        _check(load_library().kvq_cache_reset(self.handle, _stream(stream)))
+
+    def free_seqs(self, seq_ids: Optional[torch.Tensor], n_seq: int, stream=None) -> None:
+        _check(load_library().kvq_cache_free_seqs(self.handle, _ptr(seq_ids, torch.int32, "seq_ids"), n_seq, _stream(stream)))
+
+    def status(self, stream=None):
+        flags = ctypes.c_uint32(0)
+        free = (ctypes.c_int64 * 4)()
+        _check(load_library().kvq_cache_status(self.handle, ctypes.byref(flags), free, _stream(stream)))
+        return int(flags.value), [int(x) for x in free]
+
+    def counts(self, stream=None) -> torch.Tensor:
+        """int32 [max_seqs, 5] on the host: tokens per class and total length."""
+        out = torch.zeros((self.max_seqs, 5), dtype=torch.int32)
+        _check(load_library().kvq_cache_counts(self.handle, out.data_ptr(), _stream(stream)))
+        return out
+
+    def export(self, layer: int, seq: int, max_tokens: int, stream=None):
+        dev = torch.device("cuda")
+        bits = torch.zeros(max_tokens, dtype=torch.uint8, device=dev)
+        codes = torch.zeros((max_tokens, self.Hkv, 2, EXPORT_REC), dtype=torch.uint8, device=dev)
+        meta = torch.zeros((max_tokens, self.Hkv, 2, 2), dtype=torch.int16, device=dev)
+        _check(load_library().kvq_cache_export(self.handle, layer, seq, bits.data_ptr(), codes.data_ptr(),
+                                               meta.data_ptr(), max_tokens, _stream(stream)))
+        return bits, codes, meta
+
+
+def kvq_features_workspace(n: int, vocab: int) -> int:
+    return int(load_library().kvq_features_workspace(n, vocab))
+
+
+def kvq_features(logits: torch.Tensor, token_ids: torch.Tensor, counts: torch.Tensor, totals: torch.Tensor,
+                 update_counts: bool, attn_len: torch.Tensor, n_q_heads: int, feats_out: torch.Tensor,
+                 workspace: torch.Tensor, attn_probs: Optional[torch.Tensor] = None,
+                 sum_p2: Optional[torch.Tensor] = None, stream=None) -> None:
+    n, vocab = logits.shape
+    ld = attn_probs.shape[-1] if attn_probs is not None else 0
+    _check(load_library().kvq_features(
+        _ptr(logits, torch.float32, "logits"), n, vocab, _ptr(token_ids, torch.int32, "token_ids"),
+        _ptr(counts, torch.int64, "counts"), _ptr(totals, torch.int64, "totals"), int(bool(update_counts)),
+        _ptr(attn_probs, torch.float32, "attn_probs"), _ptr(sum_p2, torch.float32, "sum_p2"),
+        _ptr(attn_len, torch.int32, "attn_len"), n_q_heads, ld, _ptr(feats_out, torch.float32, "feats_out"),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+class MlpWeights:
+    """Device weights of the controller plus the C struct that points at them."""
+
+    def __init__(self, weights: Sequence[torch.Tensor], biases: Sequence[torch.Tensor]):
+        assert len(weights) == len(biases) and 2 <= len(weights) <= 3
+        self.W = [w.contiguous() for w in weights]
+        self.b = [b.contiguous() for b in biases]
+        self.c = Mlp()
+        self.c.n_linear = len(self.W)
+        self.c.dims[0] = self.W[0].shape[1]
+        for l, (w, b) in enumerate(zip(self.W, self.b)):
+            assert w.dtype == torch.float32 and b.dtype == torch.float32 and w.is_cuda and b.is_cuda
+            assert w.shape[1] == self.c.dims[l] and b.shape == (w.shape[0],)
+            self.c.dims[l + 1] = w.shape[0]
+            self.c.W[l] = w.data_ptr()
+            self.c.b[l] = b.data_ptr()
+
+
+def kvq_controller(feats: torch.Tensor, mlp: MlpWeights, bits_out: torch.Tensor,
+                   logits_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    n = feats.shape[0]
+    _check(load_library().kvq_controller(_ptr(feats, torch.float32, "feats"), n, ctypes.byref(mlp.c),
+                                         _ptr(bits_out, torch.uint8, "bits_out"),
+                                         _ptr(logits_out, torch.float32, "logits_out"), _stream(stream)))
+
+
+def kvq_append(cache: Cache, layer: int, k: torch.Tensor, v: torch.Tensor, bits: Optional[torch.Tensor],
+               seq_ids: Optional[torch.Tensor], n_seq: int, T: int, stream=None) -> None:
+    _check(load_library().kvq_append(cache.handle, layer, _ptr(k, torch.float16, "k"), _ptr(v, torch.float16, "v"),
+                                     _ptr(bits, torch.uint8, "bits"), _ptr(seq_ids, torch.int32, "seq_ids"),
+                                     n_seq, T, _stream(stream)))
+
+
+def kvq_decode_attn_workspace(cache: Cache, n_seq: int) -> int:
+    return int(load_library().kvq_decode_attn_workspace(cache.handle, n_seq))
+
+
+def kvq_decode_attn(cache: Cache, layer: int, q: torch.Tensor, seq_ids: Optional[torch.Tensor], n_seq: int,
+                    out: torch.Tensor, workspace: torch.Tensor, lse_out: Optional[torch.Tensor] = None,
+                    sum_p2_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(load_library().kvq_decode_attn(cache.handle, layer, _ptr(q, torch.float16, "q"),
+                                          _ptr(seq_ids, torch.int32, "seq_ids"), n_seq,
+                                          _ptr(out, torch.float32, "out"), _ptr(lse_out, torch.float32, "lse_out"),
+                                          _ptr(sum_p2_out, torch.float32, "sum_p2_out"),
+                                          _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+def kvq_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    _check(load_library().kvq_probe_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream(stream)))
+
+
+def kvq_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    _check(load_library().kvq_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), _stream(stream)))

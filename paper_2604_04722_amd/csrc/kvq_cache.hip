@@ -1,0 +1,500 @@
+// Cache object, bucket bookkeeping, quantize-and-append (paper Sec. 3.7 + the Concat update of Sec. 3.2)
+// and the canonical export.
+#include "kvq_internal.h"
+
+#include <hip/hip_fp16.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+namespace kvq {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int check_hip(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return KVQ_OK;
+    set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+    return e == hipErrorOutOfMemory ? KVQ_ERR_OOM : KVQ_ERR_DEVICE;
+}
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Everything the arena holds, in order.  Returns the total size; fills `v` when base != nullptr.
+static size_t plan_arena(const kvq_cache_desc &d, CacheView *v, uint8_t *base)
+{
+    const int P = d.page_tokens ? d.page_tokens : 256;
+    const int bpp = P / kBlockTokens;
+    const int64_t mpps = (d.max_context + P - 1) / P;
+    size_t off = 0;
+    CacheView cv;
+    memset(&cv, 0, sizeof(cv));
+    cv.n_layers = d.n_layers;
+    cv.max_seqs = d.max_seqs;
+    cv.Hq = d.n_q_heads;
+    cv.Hkv = d.n_kv_heads;
+    cv.page_tokens = P;
+    cv.blocks_per_page = bpp;
+    cv.max_pages_per_seq = (int32_t)mpps;
+    cv.max_context = (int32_t)d.max_context;
+    for (int c = 0; c < kClasses; ++c) {
+        int64_t np = d.pool_pages[c] > 0 ? d.pool_pages[c] : (int64_t)d.max_seqs * mpps;
+        cv.n_pages[c] = (int32_t)np;
+        const size_t page_bytes = (size_t)bpp * class_block_bytes(c);
+        cv.layer_stride[c] = (size_t)(np + 1) * d.n_kv_heads * page_bytes;     // +1: the sink page
+        cv.pool[c] = base + off;
+        off = align256(off + cv.layer_stride[c] * d.n_layers);
+    }
+    cv.page_table = (int32_t *)(base + off);
+    off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs * kClasses * mpps);
+    cv.counts = (int32_t *)(base + off);
+    off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs * 5);
+    cv.last_T = (int32_t *)(base + off);
+    off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs);
+    cv.bits_log = base + off;
+    off = align256(off + (size_t)d.max_seqs * d.max_context);
+    cv.slot_log = (int32_t *)(base + off);
+    off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs * d.max_context);
+    for (int c = 0; c < kClasses; ++c) {
+        cv.free_stack[c] = (int32_t *)(base + off);
+        off = align256(off + sizeof(int32_t) * (size_t)cv.n_pages[c]);
+    }
+    cv.free_top = (int32_t *)(base + off);
+    off = align256(off + sizeof(int32_t) * kClasses);
+    cv.flags = (uint32_t *)(base + off);
+    off = align256(off + sizeof(uint32_t));
+    if (v) *v = cv;
+    return off;
+}
+
+static bool valid_desc(const kvq_cache_desc *d)
+{
+    if (!d) { set_error("descriptor is NULL"); return false; }
+    if (d->head_dim != kD) { set_error("head_dim must be 64 (got %d)", d->head_dim); return false; }
+    if (d->n_layers < 1 || d->max_seqs < 1 || d->n_kv_heads < 1 || d->n_q_heads < 1) {
+        set_error("n_layers, max_seqs, n_q_heads, n_kv_heads must be positive"); return false;
+    }
+    if (d->n_q_heads % d->n_kv_heads != 0) {
+        set_error("n_q_heads (%d) must be a multiple of n_kv_heads (%d)", d->n_q_heads, d->n_kv_heads); return false;
+    }
+    const int P = d->page_tokens ? d->page_tokens : 256;
+    if (P < 256 || P % 256 != 0 || P > (1 << 20)) { set_error("page_tokens must be a multiple of 256"); return false; }
+    if (d->max_context < 1 || d->max_context > (int64_t)0x7fff0000) { set_error("max_context out of range"); return false; }
+    const int64_t mpps = (d->max_context + P - 1) / P;
+    for (int c = 0; c < kClasses; ++c) {
+        if (d->pool_pages[c] < 0 || d->pool_pages[c] > 0x7ffffff0) { set_error("pool_pages[%d] out of range", c); return false; }
+        if (d->pool_pages[c] == 0 && (int64_t)d->max_seqs * mpps > 0x7ffffff0) { set_error("default pool too large"); return false; }
+    }
+    return true;
+}
+
+// ---------------------------------------------------------------------------------------------
+// kernels
+// ---------------------------------------------------------------------------------------------
+
+__global__ void k_reset(CacheView cv)
+{
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int c = 0; c < kClasses; ++c) {
+        const int n = cv.n_pages[c];
+        // stack popped from the top: hand out low page ids first
+        for (int64_t i = tid; i < n; i += stride) cv.free_stack[c][i] = (int32_t)(n - 1 - i);
+    }
+    for (int64_t i = tid; i < (int64_t)cv.max_seqs * 5; i += stride) cv.counts[i] = 0;
+    for (int64_t i = tid; i < cv.max_seqs; i += stride) cv.last_T[i] = 0;
+    if (tid < kClasses) cv.free_top[tid] = cv.n_pages[tid];
+    if (tid == 0) *cv.flags = 0;
+}
+
+__global__ void k_free_seqs(CacheView cv, const int32_t *seq_ids, int n_seq)
+{
+    const int si = blockIdx.x;
+    if (si >= n_seq) return;
+    const int seq = seq_ids ? seq_ids[si] : si;
+    if (seq < 0 || seq >= cv.max_seqs) return;
+    int32_t *cnt = cv.counts + (size_t)seq * 5;
+    for (int c = 0; c < kClasses; ++c) {
+        const int np = (cnt[c] + cv.page_tokens - 1) / cv.page_tokens;
+        const int32_t *pt = cv.page_table + ((size_t)seq * kClasses + c) * cv.max_pages_per_seq;
+        for (int i = threadIdx.x; i < np; i += blockDim.x) {
+            const int page = pt[i];
+            if (page >= 0 && page < cv.n_pages[c]) {               // never the sink page
+                const int idx = atomicAdd(&cv.free_top[c], 1);
+                if (idx >= 0 && idx < cv.n_pages[c]) cv.free_stack[c][idx] = page;
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 5) cnt[threadIdx.x] = 0;
+    if (threadIdx.x == 0) cv.last_T[seq] = 0;
+}
+
+// Bucket bookkeeping for T new tokens of each listed sequence: one wavefront per sequence walks the
+// tokens 64 at a time; a ballot per class gives every token its rank inside its class.
+__global__ __launch_bounds__(64) void k_advance(CacheView cv, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T)
+{
+    const int si = blockIdx.x;
+    if (si >= n_seq) return;
+    const int lane = threadIdx.x;
+    const int seq = seq_ids ? seq_ids[si] : si;
+    if (seq < 0 || seq >= cv.max_seqs) {
+        if (lane == 0) atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL);
+        return;
+    }
+    int32_t *cnt = cv.counts + (size_t)seq * 5;
+    const int len = cnt[4];
+    if ((int64_t)len + T > (int64_t)cv.max_context) {
+        if (lane == 0) {
+            atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL);
+            cv.last_T[seq] = 0;
+        }
+        return;
+    }
+    int cc[kClasses] = {cnt[0], cnt[1], cnt[2], cnt[3]};
+    bool bad = false;
+    for (int t0 = 0; t0 < T; t0 += 64) {
+        const int t = t0 + lane;
+        const bool valid = t < T;
+        int b = valid ? (int)bits[(size_t)si * T + t] : 0;
+        if (valid && b != 2 && b != 4 && b != 8 && b != 16) { bad = true; b = 16; }
+        const int cls = bits_to_class(b);
+#pragma unroll
+        for (int c = 0; c < kClasses; ++c) {
+            const bool mine = valid && cls == c;
+            const unsigned long long mask = __ballot(mine);
+            if (mine) {
+                const int rank = __popcll(mask & ((1ull << lane) - 1ull));
+                const int slot = cc[c] + rank;
+                if (slot % cv.page_tokens == 0) {
+                    int page;
+                    const int idx = atomicSub(&cv.free_top[c], 1) - 1;
+                    if (idx < 0) {
+                        atomicAdd(&cv.free_top[c], 1);
+                        atomicOr(cv.flags, KVQ_FLAG_POOL_EXHAUSTED);
+                        page = cv.n_pages[c];                          // sink page: in bounds, shared, garbage
+                    } else {
+                        page = cv.free_stack[c][idx];
+                    }
+                    cv.page_table[((size_t)seq * kClasses + c) * cv.max_pages_per_seq + slot / cv.page_tokens] = page;
+                }
+                const size_t pos = (size_t)seq * cv.max_context + len + t;
+                cv.bits_log[pos] = (uint8_t)b;
+                cv.slot_log[pos] = slot;
+            }
+            cc[c] += __popcll(mask);
+        }
+    }
+    if (__ballot(bad) != 0ull && lane == 0) atomicOr(cv.flags, KVQ_FLAG_BAD_BITS);
+    if (lane == 0) {
+        cnt[0] = cc[0]; cnt[1] = cc[1]; cnt[2] = cc[2]; cnt[3] = cc[3];
+        cnt[4] = len + T;
+        cv.last_T[seq] = T;
+    }
+}
+
+__device__ __forceinline__ float wave_min_all(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fminf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+__device__ __forceinline__ float wave_max_all(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+// OR of `word` over the aligned group of `per` lanes (per = 2, 4, 8 or 16)
+__device__ __forceinline__ uint32_t group_or(uint32_t word, int per)
+{
+    for (int o = 1; o < per; o <<= 1) word |= (uint32_t)__shfl_xor((int)word, o, 64);
+    return word;
+}
+
+// Q_b of one 64-vector held one element per lane, written into its block.  Every lane passes the same
+// uniform arguments.  `codes` points at the K or V code region of the block, `meta` at the token's
+// (scale, min) pair for this tensor (nullptr for FP16).
+__device__ __forceinline__ void quantize_store(__half xh, int b, int lane, int tok, uint8_t *codes, __half *meta)
+{
+    uint32_t word;
+    int per;
+    if (b == 16) {
+        per = 2;
+        word = (uint32_t)__half_as_ushort(xh) << (16 * (lane & 1));
+    } else {
+        const float x = __half2float(xh);
+        float mn = wave_min_all(x);
+        const float mx = wave_max_all(x);
+        if (mn == 0.0f) mn = 0.0f;                                  // a zero minimum of either sign is stored as +0
+        const float levels = (float)((1 << b) - 1);
+        const float range = mx - mn;
+        const float scale32 = range / levels;                      // IEEE binary32 division
+        const __half sh = __float2half_rn(scale32);                // RNE, subnormals kept
+        const float s = __half2float(sh);
+        float code = 0.0f;
+        if (s != 0.0f) {
+            code = rintf((x - mn) / s);                            // IEEE division, ties to even
+            code = fminf(fmaxf(code, 0.0f), levels);
+        }
+        per = 32 / b;
+        const int r = lane % per;
+        word = (uint32_t)code << (b * (r >> 1) + 16 * (r & 1));
+        if (lane == 0) {
+            meta[0] = sh;
+            meta[1] = __float2half_rn(mn);                         // exact: mn is an fp16 value
+        }
+    }
+    word = group_or(word, per);
+    if (lane % per == 0) {
+        const int w = lane / per;
+        *(uint32_t *)(codes + (size_t)(w >> 2) * (kBlockTokens * 16) + tok * 16 + (w & 3) * 4) = word;
+    }
+}
+
+// One wavefront per (layer, sequence, token, kv-head): quantizes the K vector and the V vector and
+// stores them at the slot the bookkeeping kernel assigned.  Tokens never share a byte, so any number
+// of tokens can be written in parallel.
+__global__ __launch_bounds__(256) void k_append_write(CacheView cv, int layer, const __half *k, const __half *v,
+                                                      const int32_t *seq_ids, int n_seq, int T, long long total_vecs)
+{
+    const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (wave >= total_vecs) return;
+    long long r = wave;
+    const int h = (int)(r % cv.Hkv); r /= cv.Hkv;
+    const int t = (int)(r % T); r /= T;
+    const int si = (int)(r % n_seq);
+    const int li = (int)(r / n_seq);
+    const int L = layer < 0 ? li : layer;
+    const int seq = seq_ids ? seq_ids[si] : si;
+    if (seq < 0 || seq >= cv.max_seqs) return;
+    const int lastT = cv.last_T[seq];
+    if (lastT != T || t >= lastT) return;                          // the bookkeeping call skipped this sequence
+    const int len = cv.counts[(size_t)seq * 5 + 4];
+    const size_t pos = (size_t)seq * cv.max_context + (len - lastT + t);
+    const int b = cv.bits_log[pos];
+    const int slot = cv.slot_log[pos];
+    const int cls = bits_to_class(b);
+    const int page = cv.page_table[((size_t)seq * kClasses + cls) * cv.max_pages_per_seq + slot / cv.page_tokens];
+    const int blk = (slot % cv.page_tokens) / kBlockTokens;
+    const int tok = slot % kBlockTokens;
+    uint8_t *base = cv.pool[cls] + block_offset(cv, cls, L, page, h, blk);
+    const size_t src = ((((size_t)li * n_seq + si) * T + t) * cv.Hkv + h) * kD + lane;
+    const int meta_bytes = class_meta_bytes(cls);
+    const size_t region = (size_t)class_chunks(cls) * kBlockTokens * 16;
+    __half *meta = (__half *)(base + tok * 8);
+    quantize_store(k[src], b, lane, tok, base + meta_bytes, meta);
+    quantize_store(v[src], b, lane, tok, base + meta_bytes + region, meta + 2);
+}
+
+// Canonical dump of one (layer, sequence): one wavefront per (token, kv-head), lane = element.
+__global__ __launch_bounds__(256) void k_export(CacheView cv, int layer, int seq, uint8_t *bits_out, uint8_t *codes_out,
+                                                uint16_t *meta_out, long long max_tokens)
+{
+    const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    const int len = cv.counts[(size_t)seq * 5 + 4];
+    const long long ntok = len < max_tokens ? len : max_tokens;
+    if (wave >= ntok * cv.Hkv) return;
+    const int h = (int)(wave % cv.Hkv);
+    const long long t = wave / cv.Hkv;
+    const size_t pos = (size_t)seq * cv.max_context + t;
+    const int b = cv.bits_log[pos];
+    const int slot = cv.slot_log[pos];
+    const int cls = bits_to_class(b);
+    const int page = cv.page_table[((size_t)seq * kClasses + cls) * cv.max_pages_per_seq + slot / cv.page_tokens];
+    const int blk = (slot % cv.page_tokens) / kBlockTokens;
+    const int tok = slot % kBlockTokens;
+    const uint8_t *base = cv.pool[cls] + block_offset(cv, cls, layer, page, h, blk);
+    const int meta_bytes = class_meta_bytes(cls);
+    const size_t region = (size_t)class_chunks(cls) * kBlockTokens * 16;
+    const int per = 32 / b;
+    const int w = lane / per, r = lane % per;
+    const uint32_t mask = b == 16 ? 0xffffu : ((1u << b) - 1u);
+    for (int which = 0; which < 2; ++which) {
+        const uint8_t *codes = base + meta_bytes + which * region;
+        const uint32_t word = *(const uint32_t *)(codes + (size_t)(w >> 2) * (kBlockTokens * 16) + tok * 16 + (w & 3) * 4);
+        const uint32_t code = (word >> (b * (r >> 1) + 16 * (r & 1))) & mask;
+        const uint32_t canon = group_or(code << (b * r), per);      // element i at bits [i*b, i*b+b)
+        uint32_t *rec = (uint32_t *)(codes_out + (((size_t)t * cv.Hkv + h) * 2 + which) * KVQ_EXPORT_REC);
+        if (r == 0) rec[w] = canon;
+        if (lane >= 2 * b && lane < 32) rec[lane] = 0u;             // words past the 8*b code bytes
+        if (lane == 0) {
+            uint16_t *m = meta_out + (((size_t)t * cv.Hkv + h) * 2 + which) * 2;
+            if (cls == 3) { m[0] = 0; m[1] = 0; }
+            else {
+                const uint16_t *src = (const uint16_t *)(base + tok * 8 + which * 4);
+                m[0] = src[0]; m[1] = src[1];
+            }
+        }
+    }
+    if (h == 0 && lane == 0) bits_out[t] = (uint8_t)b;
+}
+
+}  // namespace kvq
+
+using namespace kvq;
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+
+extern "C" const char *kvq_version(void) { return "kvq 0.1 (gfx950)"; }
+extern "C" const char *kvq_last_error(void) { return g_err; }
+
+extern "C" size_t kvq_cache_arena_bytes(const kvq_cache_desc *desc)
+{
+    if (!valid_desc(desc)) return 0;
+    return plan_arena(*desc, nullptr, nullptr);
+}
+
+extern "C" int kvq_cache_create(const kvq_cache_desc *desc, kvq_cache **out)
+{
+    if (!out) { set_error("out is NULL"); return KVQ_ERR_INVALID_ARG; }
+    *out = nullptr;
+    if (!valid_desc(desc)) return desc && desc->head_dim != kD ? KVQ_ERR_UNSUPPORTED : KVQ_ERR_INVALID_ARG;
+    const size_t need = plan_arena(*desc, nullptr, nullptr);
+    void *arena = desc->arena;
+    bool own = false;
+    if (arena) {
+        if (((uintptr_t)arena & 255) != 0) { set_error("arena must be 256-byte aligned"); return KVQ_ERR_INVALID_ARG; }
+        if (desc->arena_bytes < need) {
+            set_error("arena too small: %zu bytes given, %zu needed", desc->arena_bytes, need);
+            return KVQ_ERR_OOM;
+        }
+    } else {
+        KVQ_HIP(hipMalloc(&arena, need));
+        own = true;
+    }
+    kvq_cache *c = new (std::nothrow) kvq_cache;
+    if (!c) { if (own) (void)hipFree(arena); set_error("host allocation failed"); return KVQ_ERR_OOM; }
+    c->desc = *desc;
+    c->arena = arena;
+    c->arena_bytes = need;
+    c->own_arena = own;
+    c->len_bound = 0;
+    (void)hipGetDevice(&c->device);
+    plan_arena(*desc, &c->view, (uint8_t *)arena);
+    // Pages hold finite data from the start: lanes past the end of a bucket read in-bounds bytes and
+    // weight them by zero, which is only safe if those bytes are never NaN/Inf patterns.
+    hipError_t e = hipMemset(arena, 0, need);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, 0, c->view);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        if (own) (void)hipFree(arena);
+        delete c;
+        return check_hip(e, "kvq_cache_create");
+    }
+    *out = c;
+    return KVQ_OK;
+}
+
+extern "C" int kvq_cache_destroy(kvq_cache *cache)
+{
+    if (!cache) return KVQ_OK;
+    int rc = KVQ_OK;
+    if (cache->own_arena) rc = check_hip(hipFree(cache->arena), "hipFree(arena)");
+    delete cache;
+    return rc;
+}
+
+extern "C" int kvq_cache_reset(kvq_cache *cache, void *stream)
+{
+    if (!cache) { set_error("cache is NULL"); return KVQ_ERR_INVALID_ARG; }
+    hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, (hipStream_t)stream, cache->view);
+    KVQ_HIP(hipGetLastError());
+    cache->len_bound = 0;
+    return KVQ_OK;
+}
+
+extern "C" int kvq_cache_free_seqs(kvq_cache *cache, const int32_t *seq_ids, int32_t n_seq, void *stream)
+{
+    if (!cache) { set_error("cache is NULL"); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq < 0 || n_seq > cache->desc.max_seqs) { set_error("n_seq out of range"); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq == 0) return KVQ_OK;
+    hipLaunchKernelGGL(k_free_seqs, dim3(n_seq), dim3(256), 0, (hipStream_t)stream, cache->view, seq_ids, n_seq);
+    KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+}
+
+extern "C" int kvq_cache_status(kvq_cache *cache, uint32_t *flags, int64_t *free_pages, void *stream)
+{
+    if (!cache || !flags) { set_error("cache or flags is NULL"); return KVQ_ERR_INVALID_ARG; }
+    uint32_t f = 0;
+    int32_t top[kClasses];
+    KVQ_HIP(hipStreamSynchronize((hipStream_t)stream));
+    KVQ_HIP(hipMemcpy(&f, cache->view.flags, sizeof(f), hipMemcpyDeviceToHost));
+    KVQ_HIP(hipMemcpy(top, cache->view.free_top, sizeof(top), hipMemcpyDeviceToHost));
+    *flags = f;
+    if (free_pages) for (int c = 0; c < kClasses; ++c) free_pages[c] = top[c];
+    return KVQ_OK;
+}
+
+extern "C" int kvq_cache_counts(kvq_cache *cache, int32_t *counts, void *stream)
+{
+    if (!cache || !counts) { set_error("cache or counts is NULL"); return KVQ_ERR_INVALID_ARG; }
+    KVQ_HIP(hipStreamSynchronize((hipStream_t)stream));
+    KVQ_HIP(hipMemcpy(counts, cache->view.counts, sizeof(int32_t) * (size_t)cache->desc.max_seqs * 5, hipMemcpyDeviceToHost));
+    return KVQ_OK;
+}
+
+extern "C" int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t seq, uint8_t *bits_out, uint8_t *codes_out,
+                                uint16_t *meta_out, int64_t max_tokens, void *stream)
+{
+    if (!cache || !bits_out || !codes_out || !meta_out) { set_error("NULL argument"); return KVQ_ERR_INVALID_ARG; }
+    if (layer < 0 || layer >= cache->desc.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
+    if (seq < 0 || seq >= cache->desc.max_seqs) { set_error("seq %d out of range", seq); return KVQ_ERR_INVALID_ARG; }
+    if (max_tokens < 0) { set_error("max_tokens negative"); return KVQ_ERR_INVALID_ARG; }
+    if (max_tokens == 0) return KVQ_OK;
+    const int64_t cap = max_tokens < cache->desc.max_context ? max_tokens : cache->desc.max_context;
+    const long long waves = (long long)cap * cache->desc.n_kv_heads;
+    const unsigned grid = (unsigned)((waves + 3) / 4);
+    hipLaunchKernelGGL(k_export, dim3(grid), dim3(256), 0, (hipStream_t)stream, cache->view, layer, seq, bits_out,
+                       codes_out, meta_out, (long long)max_tokens);
+    KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+}
+
+extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const void *v, const uint8_t *bits,
+                          const int32_t *seq_ids, int32_t n_seq, int32_t T, void *stream)
+{
+    if (!cache || !k || !v) { set_error("cache, k or v is NULL"); return KVQ_ERR_INVALID_ARG; }
+    const kvq_cache_desc &d = cache->desc;
+    if (layer < -1 || layer >= d.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
+    if (T < 0) { set_error("T negative"); return KVQ_ERR_INVALID_ARG; }
+    if ((int64_t)T > d.max_context) { set_error("T %d exceeds max_context", T); return KVQ_ERR_CAPACITY; }
+    const bool bookkeeping = layer <= 0;
+    if (bookkeeping && !bits) { set_error("bits is NULL on the bookkeeping call (layer 0 or -1)"); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq == 0 || T == 0) return KVQ_OK;
+    const long long nl = layer < 0 ? d.n_layers : 1;
+    const long long total = nl * n_seq * (long long)T * d.n_kv_heads;
+    if ((total + 3) / 4 > 0x7fffffffLL) { set_error("append too large for one launch"); return KVQ_ERR_CAPACITY; }
+    hipStream_t st = (hipStream_t)stream;
+    if (bookkeeping) {
+        hipLaunchKernelGGL(k_advance, dim3(n_seq), dim3(64), 0, st, cache->view, bits, seq_ids, n_seq, T);
+        KVQ_HIP(hipGetLastError());
+        cache->len_bound += T;
+        if (cache->len_bound > d.max_context) cache->len_bound = d.max_context;
+    }
+    hipLaunchKernelGGL(k_append_write, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, st, cache->view, layer,
+                       (const __half *)k, (const __half *)v, seq_ids, n_seq, T, total);
+    KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+}

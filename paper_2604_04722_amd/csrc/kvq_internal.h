@@ -1,0 +1,96 @@
+// Internal declarations shared by the HIP translation units of libkvq (not installed, not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "kvq.h"
+
+namespace kvq {
+
+// ----------------------------------------------------------------------------------------------
+// Device layout of the precision-bucketed cache.
+//
+// A token's bit width (class 0..3 = 2/4/8/16 bit) is one decision shared by every layer and
+// kv-head (paper Sec. 3.6: one b per token), so the bucket bookkeeping is per (sequence, class):
+//   slot  = rank of the token among the sequence's tokens of its class,
+//   page  = page_table[seq][class][slot / page_tokens]      (allocated from the class's pool)
+//   block = 64 consecutive slots = one wavefront's worth of tokens (lane = token).
+// One page id names memory for every layer and kv-head:
+//   addr = pool[class] + layer*layer_stride[class] + ((page*Hkv + kvh)*blocks_per_page + blk)*block_bytes[class]
+// Inside a block (NCH = 16-byte chunks per vector = 1/2/4/8):
+//   [ meta: 64 tokens x 8 B  (half K scale, half K min, half V scale, half V min) ]   (absent for FP16)
+//   [ K codes: NCH chunks x 64 tokens x 16 B ]   chunk-major: a wave's 16-B-per-lane load is 1 KiB contiguous
+//   [ V codes: NCH chunks x 64 tokens x 16 B ]
+// Inside a token's vector, 32-bit word w holds elements [w*per, (w+1)*per), per = 32/b.  The pair of
+// elements (2m, 2m+1) sits at the same offset of the low and the high 16-bit half of its word:
+// element w*per + r goes to bits  b*(r/2) + 16*(r%2).  One shift + one and-or then yields the pair as
+// two fp16 values, ready for a packed dot with the matching pair of q (or a mixed-precision FMA).
+// ----------------------------------------------------------------------------------------------
+
+constexpr int kD = 64;                 // head_dim
+constexpr int kBlockTokens = 64;       // one block = one wavefront of tokens
+constexpr int kClasses = 4;
+
+__host__ __device__ constexpr int class_bits(int c) { return c == 0 ? 2 : c == 1 ? 4 : c == 2 ? 8 : 16; }
+__host__ __device__ constexpr int class_chunks(int c) { return c == 0 ? 1 : c == 1 ? 2 : c == 2 ? 4 : 8; }
+__host__ __device__ constexpr int class_meta_bytes(int c) { return c == 3 ? 0 : kBlockTokens * 8; }
+__host__ __device__ constexpr int class_block_bytes(int c)
+{
+    return class_meta_bytes(c) + 2 * class_chunks(c) * kBlockTokens * 16;
+}
+// blocks that one loop iteration of the attention kernel treats together (all inside one page)
+__host__ __device__ constexpr int class_unit_blocks(int c) { return c == 0 ? 4 : c == 1 ? 2 : 1; }
+
+struct CacheView {
+    uint8_t *pool[kClasses];
+    size_t layer_stride[kClasses];
+    int32_t *page_table;               // [max_seqs][4][max_pages_per_seq]
+    int32_t *counts;                   // [max_seqs][5]: tokens per class, total length
+    int32_t *last_T;                   // [max_seqs]: tokens accepted by the latest bookkeeping append
+    uint8_t *bits_log;                 // [max_seqs][max_context]
+    int32_t *slot_log;                 // [max_seqs][max_context]
+    int32_t *free_stack[kClasses];     // [n_pages[c]] ids of free pages
+    int32_t *free_top;                 // [4] number of free pages
+    uint32_t *flags;                   // [1] sticky KVQ_FLAG_*
+    int32_t n_pages[kClasses];         // usable pages; page id n_pages[c] is the sink page
+    int32_t n_layers, max_seqs, Hq, Hkv;
+    int32_t page_tokens, blocks_per_page, max_pages_per_seq;
+    int32_t max_context;
+};
+
+}  // namespace kvq
+
+struct kvq_cache {
+    kvq_cache_desc desc;
+    kvq::CacheView view;
+    void *arena;
+    size_t arena_bytes;
+    bool own_arena;
+    int device;
+    int64_t len_bound;                 // host-side upper bound of any sequence's length (split heuristic only)
+};
+
+namespace kvq {
+
+void set_error(const char *fmt, ...);
+int check_hip(hipError_t e, const char *what);
+
+#define KVQ_HIP(call)                                              \
+    do {                                                           \
+        int _rc = ::kvq::check_hip((call), #call);                 \
+        if (_rc != KVQ_OK) return _rc;                             \
+    } while (0)
+
+// ---- small device helpers -------------------------------------------------------------------
+
+__device__ __forceinline__ int bits_to_class(int b) { return b == 2 ? 0 : b == 4 ? 1 : b == 8 ? 2 : 3; }
+
+__device__ __forceinline__ size_t block_offset(const CacheView &cv, int cls, int layer, int page, int kvh, int blk_in_page)
+{
+    return (size_t)layer * cv.layer_stride[cls] +
+           (((size_t)page * cv.Hkv + kvh) * cv.blocks_per_page + blk_in_page) * (size_t)class_block_bytes(cls);
+}
+
+}  // namespace kvq

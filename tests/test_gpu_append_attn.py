@@ -1,0 +1,311 @@
+"""GPU parity: kvq_append / kvq_cache_export bit-exact, kvq_decode_attn within tolerance, against the CPU oracle.
+
+Every test prints what it is about to run (flushed) before touching the GPU.
+"""
+import numpy as np
+import pytest
+import torch
+
+from helpers import (OracleCache, assert_attn_close, assert_export_equals, dev, env, gpu_f16, make_kv, to_bits_u16)
+from paper_2604_04722_amd import binding as kvq
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def build_both(B, T, Hq, Hkv, bits, seed, n_layers=1, max_context=None, chunk=None, kinds=("outlier", "outlier"),
+               page_tokens=0, pool_pages=(0, 0, 0, 0)):
+    """Appends T tokens per sequence (bits[B,T]) to a fresh GPU cache and to an oracle cache, layer by layer."""
+    max_context = max_context or max(T, 1)
+    cache = kvq.Cache(n_layers, B, Hq, Hkv, max_context, page_tokens=page_tokens, pool_pages=pool_pages)
+    ocs = [OracleCache(B, Hkv) for _ in range(n_layers)]
+    chunk = chunk or max(T, 1)
+    for t0 in range(0, T, chunk):
+        tc = min(chunk, T - t0)
+        bt = torch.from_numpy(np.ascontiguousarray(bits[:, t0:t0 + tc])).to(dev())
+        for L in range(n_layers):
+            K = make_kv((B, tc, Hkv, 64), seed + 1000 * L + t0, outlier=kinds[0] == "outlier")
+            V = make_kv((B, tc, Hkv, 64), seed + 1000 * L + t0 + 500, outlier=kinds[1] == "outlier")
+            kvq.kvq_append(cache, L, gpu_f16(K), gpu_f16(V), bt if L == 0 else None, None, B, tc)
+            for b in range(B):
+                ocs[L].append(b, K[b], V[b], bits[b, t0:t0 + tc])
+    torch.cuda.synchronize()
+    return cache, ocs
+
+
+def run_attn(cache, layer, q16, B, Hq, want_aux=True):
+    ws = torch.empty(kvq.kvq_decode_attn_workspace(cache, B), dtype=torch.uint8, device=dev())
+    out = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=dev())
+    lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev()) if want_aux else None
+    p2 = torch.zeros((B, Hq), dtype=torch.float32, device=dev()) if want_aux else None
+    kvq.kvq_decode_attn(cache, layer, gpu_f16(q16), None, B, out, ws, lse, p2)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), (lse.cpu().numpy() if want_aux else None), (p2.cpu().numpy() if want_aux else None)
+
+
+@pytest.mark.parametrize("b", [2, 4, 8, 16])
+@pytest.mark.parametrize("T", [1, 63, 64, 65, 300])
+def test_uniform_width_append_is_bit_exact(b, T):
+    say("append uniform b=%d T=%d" % (b, T))
+    B, Hq, Hkv = 2, 4, 2
+    bits = np.full((B, T), b, np.uint8)
+    cache, ocs = build_both(B, T, Hq, Hkv, bits, seed=b * 100 + T)
+    for s in range(B):
+        assert_export_equals(cache, 0, s, ocs[0])
+    assert cache.status()[0] == 0
+
+
+def test_config1_shape_mixed_append_bit_exact_and_attention_matches():
+    say("config 1 shape: ctx 512, 9q/3kv, uniform random widths, one bulk append")
+    from paper_2604_04722_amd import workloads as wl
+    cfg = wl.CONFIGS[1]
+    bits = wl.uniform_bits(cfg, 1, cfg.context)
+    cache, ocs = build_both(1, cfg.context, cfg.n_q_heads, cfg.n_kv_heads, bits, seed=11)
+    assert_export_equals(cache, 0, 0, ocs[0])
+    q = make_kv((1, cfg.n_q_heads, 64), 12, outlier=False)
+    for splits in (0, 1, 3):
+        with env(KVQ_ATTN_SPLITS=splits):
+            out, lse, p2 = run_attn(cache, 0, q, 1, cfg.n_q_heads)
+        want, want_lse, probs = ocs[0].attn(0, q[0], cfg.n_q_heads, want_probs=True)
+        assert_attn_close(out[0], want, "splits=%d" % splits)
+        np.testing.assert_allclose(lse[0], want_lse, rtol=1e-4, atol=1e-4)
+        np.testing.assert_allclose(p2[0], (probs ** 2).sum(axis=1), rtol=2e-3)
+
+
+def test_token_by_token_decode_appends_match_bulk_and_oracle():
+    say("decode-style appends: 140 steps of T=1 on 3 sequences, 2 layers, mixed widths")
+    B, T, Hq, Hkv = 3, 140, 6, 2
+    bits = np.random.default_rng(5).choice([2, 4, 8, 16], (B, T)).astype(np.uint8)
+    cache, ocs = build_both(B, T, Hq, Hkv, bits, seed=21, n_layers=2, max_context=256, chunk=1)
+    for L in range(2):
+        for s in range(B):
+            assert_export_equals(cache, L, s, ocs[L])
+    q = make_kv((B, Hq, 64), 22, outlier=False)
+    for L in range(2):
+        out, lse, _ = run_attn(cache, L, q, B, Hq)
+        for s in range(B):
+            want, want_lse, _ = ocs[L].attn(s, q[s], Hq)
+            assert_attn_close(out[s], want, "layer %d seq %d" % (L, s))
+            np.testing.assert_allclose(lse[s], want_lse, rtol=1e-4, atol=1e-4)
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 64, 65, 255, 256, 257, 511, 513, 1030])
+@pytest.mark.parametrize("width", [2, 4, 8, 16, 0])
+def test_attention_lengths_around_block_and_page_edges(T, width):
+    say("attention T=%d width=%s" % (T, width or "mixed"))
+    B, Hq, Hkv = 2, 4, 4
+    rng = np.random.default_rng(T * 7 + width)
+    bits = np.full((B, T), width, np.uint8) if width else rng.choice([2, 4, 8, 16], (B, T)).astype(np.uint8)
+    cache, ocs = build_both(B, T, Hq, Hkv, bits, seed=31 + T)
+    q = make_kv((B, Hq, 64), 32 + T, outlier=False)
+    out, lse, p2 = run_attn(cache, 0, q, B, Hq)
+    for s in range(B):
+        want, want_lse, probs = ocs[0].attn(s, q[s], Hq, want_probs=True)
+        assert_attn_close(out[s], want, "seq %d" % s)
+        np.testing.assert_allclose(lse[s], want_lse, rtol=1e-4, atol=1e-4)
+        np.testing.assert_allclose(p2[s], (probs ** 2).sum(axis=1), rtol=2e-3)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(9, 3), (15, 5), (32, 32), (8, 1)])
+@pytest.mark.parametrize("waves", [1, 2, 4, 8])
+def test_attention_head_layouts_wave_counts_and_splits(Hq, Hkv, waves):
+    say("attention Hq=%d Hkv=%d waves=%d" % (Hq, Hkv, waves))
+    B, T = 2, 700
+    bits = np.random.default_rng(Hq + waves).choice([2, 4, 8, 16], (B, T), p=[0.5, 0.25, 0.15, 0.1]).astype(np.uint8)
+    cache, ocs = build_both(B, T, Hq, Hkv, bits, seed=41)
+    q = make_kv((B, Hq, 64), 42, outlier=False)
+    for splits in (1, 2, 5):
+        with env(KVQ_ATTN_SPLITS=splits, KVQ_ATTN_WAVES=waves):
+            out, _, _ = run_attn(cache, 0, q, B, Hq, want_aux=False)
+        for s in range(B):
+            want, _, _ = ocs[0].attn(s, q[s], Hq)
+            assert_attn_close(out[s], want, "splits %d seq %d" % (splits, s))
+
+
+def test_ragged_lengths_empty_sequence_and_seq_ids():
+    say("ragged batch with an empty sequence and a permuted seq_ids list")
+    Hq, Hkv, max_ctx = 6, 3, 512
+    lens = [300, 0, 1, 129]
+    B = len(lens)
+    cache = kvq.Cache(1, B, Hq, Hkv, max_ctx)
+    oc = OracleCache(B, Hkv)
+    rng = np.random.default_rng(9)
+    for s, n in enumerate(lens):
+        if n == 0:
+            continue
+        bits = rng.choice([2, 4, 8, 16], (1, n)).astype(np.uint8)
+        K, V = make_kv((1, n, Hkv, 64), 50 + s), make_kv((1, n, Hkv, 64), 60 + s)
+        ids = torch.tensor([s], dtype=torch.int32, device=dev())
+        kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), ids, 1, n)
+        oc.append(s, K[0], V[0], bits[0])
+    torch.cuda.synchronize()
+    for s in range(B):
+        assert_export_equals(cache, 0, s, oc)
+    order = [3, 1, 0, 2]
+    q = make_kv((B, Hq, 64), 70, outlier=False)
+    ids = torch.tensor(order, dtype=torch.int32, device=dev())
+    ws = torch.empty(kvq.kvq_decode_attn_workspace(cache, B), dtype=torch.uint8, device=dev())
+    out = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=dev())
+    lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
+    kvq.kvq_decode_attn(cache, 0, gpu_f16(q), ids, B, out, ws, lse, None)
+    torch.cuda.synchronize()
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    for i, s in enumerate(order):
+        if lens[s] == 0:
+            assert np.all(out[i] == 0) and np.all(np.isneginf(lse[i]))
+            continue
+        want, want_lse, _ = oc.attn(s, q[i], Hq)
+        assert_attn_close(out[i], want, "slot %d seq %d" % (i, s))
+        np.testing.assert_allclose(lse[i], want_lse, rtol=1e-4, atol=1e-4)
+
+
+def test_degenerate_vectors_constant_tiny_huge_and_signed_zero():
+    say("degenerate vectors: constant, sub-resolution, +-65504, signed zeros")
+    B, T, Hq, Hkv = 1, 8, 2, 2
+    K = make_kv((B, T, Hkv, 64), 80, outlier=False)
+    V = make_kv((B, T, Hkv, 64), 81, outlier=False)
+    K[0, 0] = np.float16(1.5)                                   # constant vector
+    V[0, 0] = np.float16(-0.0)                                  # constant zero, negative sign
+    K[0, 1] = 0.0
+    K[0, 1, :, 3] = np.uint16(1).view(np.float16)               # range of one subnormal step
+    K[0, 2, :, ::2] = np.float16(65504.0)
+    K[0, 2, :, 1::2] = np.float16(-65504.0)                     # widest possible range
+    V[0, 3] = np.abs(V[0, 3])
+    V[0, 3, :, 5] = np.float16(-0.0)                            # minimum is a negative zero
+    V[0, 3, :, 6] = np.float16(0.0)
+    K[0, 4] = (np.random.default_rng(1).standard_normal((Hkv, 64)) * 1e-6).astype(np.float16)   # subnormal range
+    for width in (2, 4, 8, 16):
+        bits = np.full((B, T), width, np.uint8)
+        cache = kvq.Cache(1, B, Hq, Hkv, T)
+        oc = OracleCache(B, Hkv)
+        kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+        oc.append(0, K[0], V[0], bits[0])
+        assert_export_equals(cache, 0, 0, oc)
+
+
+def test_student_t_heavy_tailed_channels_and_long_mixed_context():
+    say("heavy-tailed channels, ctx 3000, mix 40/30/20/10, 15q/5kv")
+    B, T, Hq, Hkv = 2, 3000, 15, 5
+    rng = np.random.default_rng(90)
+    mult = np.clip(np.abs(rng.standard_t(3, size=(Hkv, 64))), 0.1, 50)
+    K = (rng.standard_normal((B, T, Hkv, 64)) * mult).astype(np.float16)
+    V = (rng.standard_normal((B, T, Hkv, 64)) * mult).astype(np.float16)
+    bits = rng.choice([2, 4, 8, 16], (B, T), p=[0.4, 0.3, 0.2, 0.1]).astype(np.uint8)
+    cache = kvq.Cache(1, B, Hq, Hkv, T)
+    oc = OracleCache(B, Hkv)
+    kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+    for s in range(B):
+        oc.append(s, K[s], V[s], bits[s])
+        assert_export_equals(cache, 0, s, oc)
+    q = make_kv((B, Hq, 64), 91, outlier=False)
+    out, lse, _ = run_attn(cache, 0, q, B, Hq)
+    for s in range(B):
+        want, want_lse, _ = oc.attn(s, q[s], Hq)
+        assert_attn_close(out[s], want, "seq %d" % s)
+
+
+def test_peaked_attention_and_large_scores():
+    say("peaked attention: one key aligned with q, scores up to ~+-60")
+    B, T, Hq, Hkv = 1, 500, 4, 4
+    K = make_kv((B, T, Hkv, 64), 100, outlier=False)
+    V = make_kv((B, T, Hkv, 64), 101)
+    q = make_kv((B, Hq, 64), 102, outlier=False, scale=3.0)
+    K[0, 123] = (q[0] * 2.0).astype(np.float16)                 # head h's key 123 is parallel to its query
+    bits = np.random.default_rng(103).choice([2, 4, 8, 16], (B, T)).astype(np.uint8)
+    bits[0, 123] = 16
+    cache = kvq.Cache(1, B, Hq, Hkv, T)
+    oc = OracleCache(B, Hkv)
+    kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+    oc.append(0, K[0], V[0], bits[0])
+    out, lse, p2 = run_attn(cache, 0, q, B, Hq)
+    want, want_lse, probs = oc.attn(0, q[0], Hq, want_probs=True)
+    assert probs.max() > 0.99
+    assert_attn_close(out[0], want)
+    np.testing.assert_allclose(lse[0], want_lse, rtol=1e-4)
+
+
+def test_sticky_flags_context_full_pool_exhausted_bad_bits_never_fault():
+    say("device-side conditions: context full, pool exhausted, invalid width")
+    B, Hq, Hkv = 2, 2, 2
+    cache = kvq.Cache(1, B, Hq, Hkv, 300, pool_pages=(1, 1, 1, 1))
+    K, V = make_kv((B, 256, Hkv, 64), 110), make_kv((B, 256, Hkv, 64), 111)
+    bits = np.full((B, 256), 4, np.uint8)
+    kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, 256)
+    flags, free = cache.status()
+    assert flags & kvq.FLAG_POOL_EXHAUSTED and free[1] == 0      # two sequences, one 4-bit page
+    cache.reset()
+    assert cache.status() == (0, [1, 1, 1, 1])
+    bits[:, 0] = 3                                               # not a width
+    kvq.kvq_append(cache, 0, gpu_f16(K[:1]), gpu_f16(V[:1]), torch.from_numpy(bits[:1]).to(dev()), None, 1, 256)
+    assert cache.status()[0] & kvq.FLAG_BAD_BITS
+    counts = cache.counts()
+    assert int(counts[0, 3]) == 1 and int(counts[0, 1]) == 255   # the bad token went to the FP16 class
+    kvq.kvq_append(cache, 0, gpu_f16(K[:1, :100]), gpu_f16(V[:1, :100]), torch.from_numpy(bits[:1, 1:101].copy()).to(dev()), None, 1, 100)
+    assert cache.status()[0] & kvq.FLAG_CONTEXT_FULL             # 256 + 100 > 300: skipped
+    assert int(cache.counts()[0, 4]) == 256
+
+
+def test_free_seqs_returns_pages_and_sequences_can_be_reused():
+    say("free_seqs / reuse")
+    B, Hq, Hkv, T = 2, 2, 1, 600
+    cache = kvq.Cache(1, B, Hq, Hkv, 1024, pool_pages=(4, 4, 4, 4))
+    rng = np.random.default_rng(120)
+    oc = OracleCache(B, Hkv)
+    bits = rng.choice([2, 4, 8, 16], (B, T)).astype(np.uint8)
+    K, V = make_kv((B, T, Hkv, 64), 121), make_kv((B, T, Hkv, 64), 122)
+    kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+    free_before = cache.status()[1]
+    cache.free_seqs(torch.tensor([0], dtype=torch.int32, device=dev()), 1)
+    free_after = cache.status()[1]
+    assert all(a >= b for a, b in zip(free_after, free_before)) and sum(free_after) > sum(free_before)
+    assert int(cache.counts()[0, 4]) == 0
+    K2, V2 = make_kv((1, T, Hkv, 64), 123), make_kv((1, T, Hkv, 64), 124)
+    ids = torch.tensor([0], dtype=torch.int32, device=dev())
+    kvq.kvq_append(cache, 0, gpu_f16(K2), gpu_f16(V2), torch.from_numpy(bits[1:2].copy()).to(dev()), ids, 1, T)
+    oc.append(0, K2[0], V2[0], bits[1])
+    oc.append(1, K[1], V[1], bits[1])
+    assert_export_equals(cache, 0, 0, oc)
+    assert_export_equals(cache, 0, 1, oc)
+    assert cache.status()[0] == 0
+
+
+def test_host_side_argument_checks_change_nothing():
+    say("host-side argument validation")
+    cache = kvq.Cache(2, 2, 4, 2, 256)
+    K = gpu_f16(make_kv((2, 1, 2, 64), 1))
+    bits = torch.full((2, 1), 4, dtype=torch.uint8, device=dev())
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_append(cache, 2, K, K, bits, None, 2, 1)          # layer out of range
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_append(cache, 0, K, K, None, None, 2, 1)          # bookkeeping call without bits
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_append(cache, 0, K, K, bits, None, 3, 1)          # more sequences than slots
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_append(cache, 0, K, K, bits, None, 2, 257)        # T beyond max_context
+    out = torch.zeros((2, 4, 64), dtype=torch.float32, device=dev())
+    ws = torch.empty(16, dtype=torch.uint8, device=dev())
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_decode_attn(cache, 5, K, None, 2, out, ws)
+    with env(KVQ_ATTN_SPLITS=4):
+        with pytest.raises(kvq.KvqError):
+            kvq.kvq_decode_attn(cache, 0, K, None, 2, out, ws)    # workspace too small for 4 splits
+    assert int(cache.counts()[:, 4].sum()) == 0 and cache.status()[0] == 0
+    with pytest.raises(kvq.KvqError):
+        kvq.Cache(1, 1, 3, 2, 256)                                # Hq not a multiple of Hkv
+    with pytest.raises(kvq.KvqError):
+        kvq.Cache(1, 1, 2, 2, 256, head_dim=128)
+
+
+def test_running_twice_gives_bitwise_identical_attention():
+    say("determinism: two runs, identical bits")
+    B, T, Hq, Hkv = 2, 2000, 8, 8
+    bits = np.random.default_rng(130).choice([2, 4, 8, 16], (B, T)).astype(np.uint8)
+    cache, _ = build_both(B, T, Hq, Hkv, bits, seed=131)
+    q = make_kv((B, Hq, 64), 132, outlier=False)
+    with env(KVQ_ATTN_SPLITS=3):
+        a, _, _ = run_attn(cache, 0, q, B, Hq)
+        b, _, _ = run_attn(cache, 0, q, B, Hq)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))

@@ -1,0 +1,204 @@
+"""GPU parity: kvq_features and kvq_controller against the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import dev
+from paper_2604_04722_amd import binding as kvq
+from paper_2604_04722_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+# Feature tolerances (fp32 kernels vs an fp64 oracle): H, R, C are sums of ~5e4 fp32 terms of one sign, so a
+# relative 2e-5 (plus 1e-6 absolute) leaves two orders of margin; V is a difference of order 1/l^2 taken from
+# numbers of order 1/l, so its absolute floor scales with 1/l^2.
+F_RTOL, F_ATOL = 2e-5, 1e-6
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def run_features(logits, ids, counts, N, Vobs, lens, Hq, probs=None, sum_p2=None, update=False):
+    n, vocab = logits.shape
+    d = dev()
+    t_logits = torch.from_numpy(logits).to(d)
+    t_ids = torch.from_numpy(ids.astype(np.int32)).to(d)
+    t_counts = torch.from_numpy(counts.astype(np.int64)).to(d)
+    t_tot = torch.tensor([N, Vobs], dtype=torch.int64, device=d)
+    t_len = torch.from_numpy(np.asarray(lens, np.int32)).to(d)
+    feats = torch.full((n, 4), float("nan"), dtype=torch.float32, device=d)
+    ws = torch.empty(kvq.kvq_features_workspace(n, vocab), dtype=torch.uint8, device=d)
+    kvq.kvq_features(t_logits, t_ids, t_counts, t_tot, update, t_len, Hq, feats, ws,
+                     attn_probs=None if probs is None else torch.from_numpy(probs.astype(np.float32)).to(d),
+                     sum_p2=None if sum_p2 is None else torch.from_numpy(sum_p2.astype(np.float32)).to(d))
+    torch.cuda.synchronize()
+    return feats.cpu().numpy(), t_counts.cpu().numpy(), t_tot.cpu().numpy()
+
+
+def check_feats(got, want, lens):
+    for col in (0, 1, 3):
+        np.testing.assert_allclose(got[:, col], want[:, col], rtol=F_RTOL, atol=F_ATOL)
+    l = np.asarray(lens, np.float64)
+    assert np.all(np.abs(got[:, 2] - want[:, 2]) <= 1e-4 * np.abs(want[:, 2]) + 2e-6 / l ** 2 + 1e-12)
+
+
+@pytest.mark.parametrize("n,vocab,sigma", [(1, 49152, 1.0), (16, 49152, 2.0), (64, 49152, 2.0), (5, 1000, 3.0), (3, 4099, 0.5), (2, 7, 1.0)])
+def test_features_match_the_oracle(n, vocab, sigma):
+    say("features n=%d vocab=%d sigma=%g" % (n, vocab, sigma))
+    rng = np.random.default_rng(n * 31 + vocab)
+    logits = (rng.standard_normal((n, vocab)) * sigma).astype(np.float32)
+    ids = rng.integers(0, vocab, n).astype(np.int32)
+    counts = rng.integers(0, 50, vocab).astype(np.int64) * (rng.random(vocab) < 0.6)
+    N, Vobs = int(counts.sum()), int((counts > 0).sum())
+    Hq, ld = 9, 700
+    lens = rng.integers(1, ld + 1, n).astype(np.int32)
+    raw = rng.standard_normal((n, Hq, ld)) * 2
+    probs = np.zeros((n, Hq, ld), np.float32)
+    for t in range(n):
+        e = np.exp(raw[t, :, :lens[t]])
+        probs[t, :, :lens[t]] = (e / e.sum(axis=1, keepdims=True)).astype(np.float32)
+        probs[t, :, lens[t]:] = 9.0                               # must be ignored
+    want = oracle.features(logits, ids, counts, N, Vobs, probs.astype(np.float64), lens)
+    got, c2, tot2 = run_features(logits, ids, counts, N, Vobs, lens, Hq, probs=probs)
+    check_feats(got, want, lens)
+    assert np.array_equal(c2, counts) and list(tot2) == [N, Vobs]   # update_counts = 0 leaves the tables alone
+
+
+def test_features_closed_forms_uniform_and_peaked_rows():
+    say("features closed forms")
+    vocab = 49152
+    logits = np.zeros((3, vocab), np.float32)
+    logits[0] = 3.25                                              # uniform: H = ln V, C = 1/V
+    logits[1, 77] = 100.0                                         # peaked: H = 0, C = 1
+    logits[2, :7] = 5.5
+    ids = np.array([0, 1, 2], np.int32)
+    counts = np.zeros(vocab, np.int64)
+    lens = np.array([64, 64, 64], np.int32)
+    probs = np.full((3, 2, 64), 1 / 64, np.float32)
+    got, _, _ = run_features(logits, ids, counts, 0, 0, lens, 2, probs=probs)
+    assert got[0, 0] == pytest.approx(math.log(vocab), rel=2e-6) and got[0, 3] == pytest.approx(1 / vocab, rel=2e-6)
+    assert abs(got[1, 0]) < 1e-6 and got[1, 3] == pytest.approx(1.0, rel=1e-6)
+    Z = 7 * math.exp(5.5) + vocab - 7
+    assert got[2, 0] == pytest.approx(math.log(Z) - 5.5 * 7 * math.exp(5.5) / Z, rel=5e-6)
+    assert np.all(got[:, 1] == 0.0) and np.all(np.abs(got[:, 2]) < 1e-12)
+
+
+def test_features_from_sum_p2_and_count_updates_with_duplicates():
+    say("features: fused sum_p2 input, running counts with duplicate ids in one batch")
+    n, vocab, Hq = 8, 2048, 6
+    rng = np.random.default_rng(3)
+    logits = rng.standard_normal((n, vocab)).astype(np.float32)
+    ids = np.array([5, 5, 9, 1000, 5, 9, 3, 2047], np.int32)
+    counts = np.zeros(vocab, np.int64)
+    counts[9] = 4
+    counts[3] = 1
+    N, Vobs = 5, 2
+    lens = rng.integers(2, 400, n).astype(np.int32)
+    probs = np.zeros((n, Hq, 400))
+    for t in range(n):
+        e = np.exp(rng.standard_normal((Hq, lens[t])) * 3)
+        probs[t, :, :lens[t]] = e / e.sum(axis=1, keepdims=True)
+    p2 = (probs ** 2).sum(axis=2)
+    want = oracle.features(logits, ids, counts, N, Vobs, probs, lens)
+    got, c2, tot2 = run_features(logits, ids, counts, N, Vobs, lens, Hq, sum_p2=p2, update=True)
+    check_feats(got, want, lens)
+    wc, wN, wV = oracle.counts_update(ids, counts, N, Vobs)
+    assert np.array_equal(c2, wc) and list(tot2) == [wN, wV]
+    # a second call sees the updated table
+    want2 = oracle.features(logits, ids, wc, wN, wV, probs, lens)
+    got2, _, _ = run_features(logits, ids, c2, int(tot2[0]), int(tot2[1]), lens, Hq, sum_p2=p2)
+    check_feats(got2, want2, lens)
+    assert np.all(got2[:, 1] != got[:, 1])
+
+
+def gpu_controller(feats, Ws, bs):
+    d = dev()
+    mlp = kvq.MlpWeights([torch.from_numpy(w).to(d) for w in Ws], [torch.from_numpy(b).to(d) for b in bs])
+    n = feats.shape[0]
+    bits = torch.zeros(n, dtype=torch.uint8, device=d)
+    logits = torch.zeros((n, 4), dtype=torch.float32, device=d)
+    kvq.kvq_controller(torch.from_numpy(feats).to(d), mlp, bits, logits)
+    torch.cuda.synchronize()
+    return bits.cpu().numpy(), logits.cpu().numpy()
+
+
+def check_controller(feats, Ws, bs):
+    want_bits, want_logits = oracle.controller(feats, Ws, bs)
+    got_bits, got_logits = gpu_controller(feats, Ws, bs)
+    scale = np.abs(want_logits).max() + 1.0
+    np.testing.assert_allclose(got_logits, want_logits, rtol=0, atol=2e-6 * scale * 8)
+    # precision assignments: identical, except where the oracle's two best logits are within 1e-5
+    srt = np.sort(want_logits, axis=1)
+    gap = srt[:, -1] - srt[:, -2]
+    differ = got_bits != want_bits
+    assert not np.any(differ & (gap > 1e-5)), "assignment differs off a tie at rows %s" % np.where(differ & (gap > 1e-5))[0][:5]
+    top2 = np.argsort(want_logits, axis=1)[:, -2:]
+    for r in np.where(differ)[0]:
+        assert int(np.log2(got_bits[r])) - 1 in top2[r]
+    return got_bits, want_bits
+
+
+@pytest.mark.parametrize("cfg_index", [1, 2, 3, 4])
+@pytest.mark.parametrize("n", [1, 64, 3000, 70000])
+def test_controller_assignments_match_the_oracle(cfg_index, n):
+    say("controller cfg %d n=%d" % (cfg_index, n))
+    cfg = wl.CONFIGS[cfg_index]
+    Ws, bs = wl.calibrated_mlp(cfg) if cfg_index >= 2 else wl.xavier_mlp(cfg)
+    feats = wl.bulk_features(cfg, n, chunk=7)
+    got, want = check_controller(feats, Ws, bs)
+    if n >= 3000 and cfg_index >= 2:
+        mix = np.array([(want == w).mean() for w in (2, 4, 8, 16)])
+        assert np.max(np.abs(mix - np.array(cfg.mix))) < 0.03       # the calibrated mix holds on a fresh draw
+
+
+def test_controller_ties_zero_weights_and_two_layer_network():
+    say("controller ties / hand-built weights")
+    feats = np.random.default_rng(4).standard_normal((10, 4)).astype(np.float32)
+    Ws = [np.zeros((8, 4), np.float32), np.zeros((4, 8), np.float32)]
+    for b3, expect in (([0.5, 0.5, 0.5, 0.5], 2), ([0.1, 0.7, 0.3, 0.2], 4), ([0.1, 0.2, 0.9, 0.9], 8), ([0, 0, 0, 1e-3], 16)):
+        bits, _ = gpu_controller(feats, Ws, [np.zeros(8, np.float32), np.array(b3, np.float32)])
+        assert list(bits) == [expect] * 10
+    W1 = np.zeros((2, 4), np.float32)
+    W1[0, 1], W1[1, 1] = 1.0, -1.0
+    W3 = np.array([[0, 0], [1, -1], [2, -2], [3, -3]], np.float32)
+    b3 = np.array([0, -0.5, -2.0, -4.5], np.float32)
+    f = np.zeros((8, 4), np.float32)
+    f[:, 1] = [-5.0, 0.2, 0.7, 1.4, 1.6, 2.4, 2.6, 9.0]
+    bits, _ = gpu_controller(f, [W1, np.eye(2, dtype=np.float32), W3], [np.zeros(2, np.float32)] * 2 + [b3])
+    assert list(bits) == [2, 2, 4, 4, 8, 8, 16, 16]
+
+
+def test_controller_row_and_bulk_launch_shapes_agree_bitwise():
+    say("controller: per-step and bulk launch shapes give identical logits")
+    cfg = wl.CONFIGS[4]
+    Ws, bs = wl.calibrated_mlp(cfg)
+    feats = wl.bulk_features(cfg, 5000, chunk=3)
+    b_bulk, l_bulk = gpu_controller(feats, Ws, bs)
+    b_row, l_row = gpu_controller(feats[:2048], Ws, bs)
+    assert np.array_equal(l_bulk[:2048].view(np.uint32), l_row.view(np.uint32)) and np.array_equal(b_bulk[:2048], b_row)
+
+
+def test_end_to_end_step_features_controller_append_attention():
+    say("one decode step end to end: features -> controller -> append -> attention (sum_p2 feeds the next step)")
+    cfg = wl.CONFIGS[1]
+    d = dev()
+    B, Hq, Hkv, vocab = 4, cfg.n_q_heads, cfg.n_kv_heads, wl.VOCAB
+    Ws, bs = wl.xavier_mlp(cfg)
+    counts, N, Vobs, probs_tab = wl.zipf_table(cfg)
+    ids = wl.zipf_ids(cfg, probs_tab, 0, B)
+    logits = wl.logits(cfg, 0, B, "cpu").numpy()
+    lens = np.array([7, 7, 7, 7], np.int32)
+    sum_p2 = np.random.default_rng(8).uniform(1 / 7, 1.0, (B, Hq)).astype(np.float32)
+    feats, _, _ = run_features(logits, ids, counts, N, Vobs, lens, Hq, sum_p2=sum_p2)
+    # oracle side: the same sum_p2 corresponds to no explicit row, so compare H, R, C and the closed form of V
+    probs = np.zeros((B, Hq, 7))
+    probs[:, :, 0] = 1.0
+    want = oracle.features(logits, ids, counts, N, Vobs, probs, lens)
+    np.testing.assert_allclose(feats[:, [0, 1, 3]], want[:, [0, 1, 3]], rtol=F_RTOL, atol=F_ATOL)
+    np.testing.assert_allclose(feats[:, 2], (sum_p2.astype(np.float64) / 7 - 1 / 49).mean(axis=1), rtol=1e-4)
+    got_bits, want_bits = check_controller(feats, Ws, bs)
+    assert set(got_bits.tolist()) <= {2, 4, 8, 16}
