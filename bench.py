@@ -1,0 +1,329 @@
+#!/usr/bin/env python3
+"""Benchmark of the adaptive mixed-precision KV-cache hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input, all on one stream with no host
+synchronisation inside: kvq_features (logits -> H, R, V, C) -> kvq_controller (bits for the new token of every
+sequence) -> for every layer: kvq_append (quantize + append the new token's K/V) -> kvq_decode_attn (one query
+per sequence and head over the whole mixed-precision cache).  Inputs are resident in HBM before timing starts.
+
+Prints ONE JSON line.  `value` is microseconds per step (lower is better); the `roofline` object is for the
+dominant kernel (decode attention), timed live with events on the launch stream; `cpu_baseline` times the CPU
+oracle on a bounded sample of the same workload on the host cores of this machine.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (4 = SmolLM-1.7B-shaped, the metric's config)")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (profiling runs only)")
+    ap.add_argument("--no-compare", action="store_true", help="skip the static-4-bit and FP16 caches")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-events", action="store_true", help="do not bracket attention launches with events")
+    ap.add_argument("--cpu-seqs", type=int, default=4, help="sequences of one layer the CPU oracle is timed on")
+    return ap.parse_args()
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported (batch and kv-head sharding need "
+              "no collective and are described in DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2604_04722_amd import binding as kvq
+    from paper_2604_04722_amd import workloads as wl
+
+    kvq.load_library()                      # fails loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    L = args.layers or cfg.n_layers
+    B, Hq, Hkv = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads
+    n_steps = args.warmup + args.steps
+    lens0 = wl.ragged_lengths(cfg).astype(np.int64) - 1          # prefill so that the first step reaches the context
+    max_ctx = int(cfg.context + n_steps + 8)
+
+    # ---------------- controller + per-token precisions of the prefill -----------------------------
+    if cfg.bits_kind == "controller":
+        Ws, bs = wl.calibrated_mlp(cfg)
+    else:
+        Ws, bs = wl.xavier_mlp(cfg)
+    mlp = kvq.MlpWeights([torch.from_numpy(w).to(dev) for w in Ws], [torch.from_numpy(b).to(dev) for b in bs])
+
+    def prefill_bits(variant):
+        T = int(lens0.max())
+        if variant == "static4":
+            return np.full((B, T), 4, np.uint8)
+        if variant == "fp16":
+            return np.full((B, T), 16, np.uint8)
+        if cfg.bits_kind == "uniform":
+            return wl.uniform_bits(cfg, B, T)
+        if cfg.bits_kind == "runs":
+            return np.stack([wl.run_bits(cfg, s, T) for s in range(B)])
+        out = np.empty((B, T), np.uint8)
+        for s in range(B):                                   # bulk controller launches on seeded feature draws
+            f = torch.from_numpy(wl.bulk_features(cfg, T, chunk=100 + s)).to(dev)
+            b = torch.empty(T, dtype=torch.uint8, device=dev)
+            kvq.kvq_controller(f, mlp, b)
+            out[s] = b.cpu().numpy()
+        return out
+
+    def build_cache(variant):
+        t0 = time.time()
+        bits = prefill_bits(variant)
+        pools = []
+        for w in (2, 4, 8, 16):
+            need = 0
+            for s in range(B):
+                need += math.ceil(((bits[s, :lens0[s]] == w).sum() + n_steps) / 256) + 1
+            pools.append(int(need))
+        cache = kvq.Cache(L, B, Hq, Hkv, max_ctx, pool_pages=pools)
+        CH = 512
+        Tmax = int(lens0.max())
+        lens_d = torch.from_numpy(lens0).to(dev)
+        for ci, t in enumerate(range(0, Tmax, CH)):
+            tc = min(CH, Tmax - t)
+            # ragged prefill: sequences shorter than this chunk's end take part with fewer tokens, so they are
+            # appended in groups of equal remaining length
+            rem = np.clip(lens0 - t, 0, tc)
+            for r in sorted(set(rem.tolist())):
+                if r == 0:
+                    continue
+                idx = np.where(rem == r)[0]
+                ids = torch.from_numpy(idx.astype(np.int32)).to(dev)
+                bt = torch.from_numpy(np.ascontiguousarray(bits[idx, t:t + r])).to(dev)
+                for layer in range(L):
+                    K, V = wl.kv_chunk_fast(cfg, layer, ci, B, tc, dev)
+                    if len(idx) == B and r == tc:
+                        kvq.kvq_append(cache, layer, K, V, bt if layer == 0 else None, None, B, tc)
+                    else:
+                        kvq.kvq_append(cache, layer, K[idx, :r].contiguous(), V[idx, :r].contiguous(),
+                                       bt if layer == 0 else None, ids, len(idx), r)
+                    del K, V
+        del lens_d
+        flags, free = cache.status()
+        if flags:
+            raise RuntimeError("cache build raised device flags %d (free pages %s)" % (flags, free))
+        log("[bench] built %s cache: %d layers, %.2f GB arena, %.1f s" %
+            (variant, L, kvq.Cache.arena_bytes(L, B, Hq, Hkv, max_ctx, pool_pages=pools) / 1e9, time.time() - t0))
+        return cache
+
+    # ---------------- per-step inputs, resident before timing ---------------------------------------
+    counts_np, N, Vobs, probs_tab = wl.zipf_table(cfg)
+    step_logits = [wl.logits(cfg, s, B, dev) for s in range(n_steps)]
+    step_ids = [torch.from_numpy(wl.zipf_ids(cfg, probs_tab, s, B)).to(dev) for s in range(n_steps)]
+    step_len = [torch.from_numpy((lens0 + s).astype(np.int32)).to(dev) for s in range(n_steps)]
+    n_in = min(n_steps, 4)                                   # K/V/q of the new token: a few distinct sets, cycled
+    step_k = [[wl.kv_chunk_fast(cfg, l, 5000 + s, B, 1, dev) for l in range(L)] for s in range(n_in)]
+    step_q = [[wl.queries(cfg, l, s, B, dev) for l in range(L)] for s in range(n_in)]
+    feats = torch.zeros((B, 4), dtype=torch.float32, device=dev)
+    step_bits = torch.zeros((B, 1), dtype=torch.uint8, device=dev)
+    out = torch.zeros((B, Hq, 64), dtype=torch.float32, device=dev)
+    sum_p2 = torch.full((B, Hq), 1.0 / float(cfg.context), dtype=torch.float32, device=dev)
+    fws = torch.empty(kvq.kvq_features_workspace(B, wl.VOCAB), dtype=torch.uint8, device=dev)
+
+    def algorithmic_bytes(counts):
+        """decode-attention bytes of ONE layer: codes + (scale, min) pairs of every cached token and kv-head, plus q in, out back"""
+        per_class = counts[:B, :4].to(torch.float64).sum(dim=0).tolist()
+        kv = sum(n * Hkv * wl.BYTES_PER_TOKEN_HEAD[w] for n, w in zip(per_class, (2, 4, 8, 16)))
+        return kv + B * Hq * 64 * (2 + 4), per_class
+
+    def run_variant(variant, timed_steps, warm_steps, events):
+        cache = build_cache(variant)
+        aws = torch.empty(kvq.kvq_decode_attn_workspace(cache, B), dtype=torch.uint8, device=dev)
+        counts_d = torch.from_numpy(counts_np).to(dev)
+        totals_d = torch.tensor([N, Vobs], dtype=torch.int64, device=dev)
+        fixed = None
+        if variant != "mixed":
+            fixed = torch.full((B, 1), 4 if variant == "static4" else 16, dtype=torch.uint8, device=dev)
+        ev_pairs, stage_ev = [], []
+
+        def step(s, record):
+            if record:
+                e0 = torch.cuda.Event(enable_timing=True); e0.record()
+            kvq.kvq_features(step_logits[s], step_ids[s], counts_d, totals_d, True, step_len[s], Hq, feats, fws, sum_p2=sum_p2)
+            if record:
+                e1 = torch.cuda.Event(enable_timing=True); e1.record()
+            kvq.kvq_controller(feats, mlp, step_bits.view(-1))
+            if record:
+                e2 = torch.cuda.Event(enable_timing=True); e2.record()
+                stage_ev.append((e0, e1, e2))
+            bits_now = step_bits if fixed is None else fixed
+            kin, qin = step_k[s % n_in], step_q[s % n_in]
+            for l in range(L):
+                kvq.kvq_append(cache, l, kin[l][0], kin[l][1], bits_now if l == 0 else None, None, B, 1)
+                if record:
+                    a0 = torch.cuda.Event(enable_timing=True); a0.record()
+                kvq.kvq_decode_attn(cache, l, qin[l], None, B, out, aws, None, sum_p2 if l == L - 1 else None)
+                if record:
+                    a1 = torch.cuda.Event(enable_timing=True); a1.record()
+                    ev_pairs.append((a0, a1))
+
+        for s in range(warm_steps):
+            step(s, False)
+        torch.cuda.synchronize()
+        c_before = cache.counts()
+        t0 = time.perf_counter()
+        for s in range(warm_steps, warm_steps + timed_steps):
+            step(s, events)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        c_after = cache.counts()
+        flags, _ = cache.status()
+        if flags:
+            raise RuntimeError("device flags %d raised during the timed steps" % flags)
+        ms_per_step = (t1 - t0) * 1e3 / timed_steps
+        bytes_b, mix_b = algorithmic_bytes(c_before)
+        bytes_a, mix_a = algorithmic_bytes(c_after)
+        abytes = 0.5 * (bytes_b + bytes_a)
+        res = {"ms_per_step": ms_per_step, "attn_bytes_per_layer": abytes,
+               "tokens_per_class": [0.5 * (x + y) for x, y in zip(mix_b, mix_a)]}
+        if events:
+            attn_us = [a0.elapsed_time(a1) * 1e3 for a0, a1 in ev_pairs]
+            res["attn_us_per_layer"] = float(np.mean(attn_us))
+            res["attn_us_min"] = float(np.min(attn_us))
+            res["features_us"] = float(np.mean([e0.elapsed_time(e1) * 1e3 for e0, e1, _ in stage_ev]))
+            res["controller_us"] = float(np.mean([e1.elapsed_time(e2) * 1e3 for _, e1, e2 in stage_ev]))
+            res["attn_GBps"] = abytes / (res["attn_us_per_layer"] * 1e-6) / 1e9
+        return cache, res
+
+    # ---------------- mixed-precision path: the metric ----------------------------------------------
+    cache, mixed = run_variant("mixed", args.steps, args.warmup, not args.no_events)
+
+    # measured streaming-read rate of a trivial kernel on this device (context for the 8 TB/s nominal peak)
+    probe = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    probe.zero_()
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    for _ in range(2):
+        kvq.kvq_probe_read(probe, sink)
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record()
+    for _ in range(5):
+        kvq.kvq_probe_read(probe, sink)
+    p1.record()
+    torch.cuda.synchronize()
+    stream_gbps = 5 * probe.numel() / (p0.elapsed_time(p1) * 1e-3) / 1e9
+    del probe
+
+    # ---------------- CPU oracle on a bounded sample -------------------------------------------------
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        ns = min(args.cpu_seqs, B)
+        T = int(lens0.max())
+        # the oracle runs its own pipeline on the same seeded inputs: controller -> quantize/append -> attention
+        exp_bits = []
+        for s in range(ns):
+            n_s = int(lens0[s])
+            if cfg.bits_kind == "controller":
+                b_s, _ = oracle.controller(wl.bulk_features(cfg, T, chunk=100 + s), Ws, bs)
+            elif cfg.bits_kind == "runs":
+                b_s = wl.run_bits(cfg, s, T)
+            else:
+                b_s = wl.uniform_bits(cfg, B, T)[s]
+            exp_bits.append(np.asarray(b_s[:n_s], np.uint8))
+        Lmax = max(len(b) for b in exp_bits)
+        # layer 0's source K/V of the sample sequences, regenerated from their seeds and copied to the host
+        codes = np.zeros((ns, Lmax, Hkv, 2, 128), np.uint8)
+        meta = np.zeros((ns, Lmax, Hkv, 2, 2), np.uint16)
+        bits_h = np.zeros((ns, Lmax), np.uint8)
+        CH = 512
+        for ci, t in enumerate(range(0, T, CH)):
+            tc = min(CH, T - t)
+            K, V = wl.kv_chunk_fast(cfg, 0, ci, B, tc, dev)
+            Kh = K[:ns].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+            Vh = V[:ns].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+            for s in range(ns):
+                r = int(min(max(lens0[s] - t, 0), tc))
+                if r:
+                    c, m = oracle.append(Kh[s, :r], Vh[s, :r], exp_bits[s][t:t + r])
+                    codes[s, t:t + r], meta[s, t:t + r], bits_h[s, t:t + r] = c, m, exp_bits[s][t:t + r]
+            del K, V
+        lens_h = np.array([min(int(lens0[s]), Lmax) for s in range(ns)], np.int32)
+        q = step_q[0][0][:ns].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        best, nthr = None, 1
+        for _ in range(2):
+            c0 = time.perf_counter()
+            _, _, _, nthr = oracle.decode_attn_batch(q, bits_h, codes, meta, lens_h, Hq)
+            dt = time.perf_counter() - c0
+            best = dt if best is None else min(best, dt)
+        scale = (float(lens0.sum()) / float(lens_h.sum())) * L
+        cpu = {"value": best * scale * 1e6, "unit": "us/step", "cores": nthr, "kind": "oracle",
+               "sample": "decode attention of %d of %d sequences of one layer at full context (%.2f s on %d threads), "
+                         "scaled by tokens to the batch and by %d layers; features, controller and append not included"
+                         % (ns, B, best, nthr, L)}
+    cache.destroy()
+    del cache
+    torch.cuda.empty_cache()
+
+    # ---------------- comparison caches built by the same library ------------------------------------
+    compare = {}
+    if not args.no_compare:
+        for variant in ("static4", "fp16"):
+            c2, r2 = run_variant(variant, max(3, args.steps // 4), 2, not args.no_events)
+            c2.destroy()
+            del c2
+            torch.cuda.empty_cache()
+            compare[variant] = {"us_per_step": r2["ms_per_step"] * 1e3, "attn_us_per_layer": r2.get("attn_us_per_layer"),
+                                "attn_GBps": r2.get("attn_GBps"), "attn_bytes_per_layer": r2["attn_bytes_per_layer"]}
+
+    tok = mixed["tokens_per_class"]
+    tot = sum(tok) or 1.0
+    result = {
+        "metric": "mixed-precision decode-attn us/step",
+        "value": mixed["ms_per_step"] * 1e3,
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": mixed["ms_per_step"],
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u2/u4/u8 codes + f16 scale/min, f16 storage class, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "config_index": cfg.index, "layers": L, "batch": B, "context": cfg.context,
+                   "q_heads": Hq, "kv_heads": Hkv, "head_dim": 64,
+                   "mix_2_4_8_16": [round(x / tot, 4) for x in tok],
+                   "expected_bits": round(sum(x * w for x, w in zip(tok, (2, 4, 8, 16))) / tot, 3)},
+        "stages_us": {"features": mixed.get("features_us"), "controller": mixed.get("controller_us"),
+                      "attn_per_layer": mixed.get("attn_us_per_layer"), "attn_per_layer_min": mixed.get("attn_us_min")},
+        "stream_read_GBps": stream_gbps,
+        "compare": compare,
+    }
+    if "attn_GBps" in mixed:
+        result["roofline"] = {"bound": "hbm", "achieved": mixed["attn_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                              "frac": mixed["attn_GBps"] / HBM_PEAK_GBPS, "traffic": None,
+                              "kernel": "k_decode_split", "bytes_per_launch": mixed["attn_bytes_per_layer"],
+                              "frac_of_stream_read": mixed["attn_GBps"] / stream_gbps}
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -8,17 +8,28 @@
 // (v_dot2_f32_f16).  For V each lane scales its token's codes by its softmax weight into 64 fp32
 // accumulators; the 64 lanes are summed once, when the wave has consumed all its blocks.
 //
-// Dequantization is folded out of the element loop.  A b-bit code c is turned into the fp16 number
-// h = 1 + c*2^-S (or 1024 + c for 8 bit) by one shift and one and-or that drops the code into the
-// mantissa of a constant; then x^ = min + scale*c = (min - OFF*scale) + (MUL*scale)*h, so that
-//   q . k^_j      = (min - OFF*scale) * sum(q)  +  MUL*scale * (q . h_j)
-//   sum_j p_j v^_j = sum_j p_j (min_j - OFF*scale_j)  +  sum_j (p_j MUL scale_j) h_j
-// and the per-element work is extract + one dot2 (K) or extract + two mixed fp16->fp32 FMAs (V).
+// Dequantization is folded out of the element loop.  A b-bit code c is turned into an fp16 number
+// h = 1 + c/M by ONE and-or that drops the code bits into the mantissa of the constant 1.0, wherever
+// in the mantissa they happen to sit (M = 2^(10 - bit position)); a shift is only needed for codes that
+// lie outside the mantissa window, and one shifted word serves two or three code pairs ("targets" with
+// different M).  For 8 bit a byte permute builds h = 1024 + c.  Then, with x^ = min + scale*c,
+//   q . k^_j       = min_j * sum(q) + scale_j * ( sum_t M_t (q . h_j)_t  -  sum_t M_t sum(q)_t )
+//   sum_j p_j v^_j = sum_j p_j min_j  -  M_t(c) * sum_j p_j scale_j  +  sum_j (p_j scale_j M_t(c)) h_jc
+// so the per-element work is an and-or plus one packed dot (K) or two mixed fp16->fp32 FMAs (V), and
+// the constant parts are carried as four extra accumulators per lane.
+//
+// Pipeline.  Every class streams through the same four 8-VGPR stage buffers (one stage = two
+// 16-byte loads per lane = 2 KiB per wave): [K, V] of two consecutive units (2 and 4 bit), the four
+// chunk pairs K01 K23 V01 V23 of an 8-bit block, or the eight chunk pairs of an FP16 block.  A buffer
+// is reloaded as soon as it has been consumed, so three stages are always in flight behind the one
+// being computed.
 #include "kvq_internal.h"
 
 namespace kvq {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -26,35 +37,58 @@ constexpr float kScoreScale = 0.125f * kLog2e;     // 1/sqrt(64), and exp(x) = e
 constexpr int kPartialFloats = 68;                 // 64 channels, m, l, l2, pad
 constexpr int kMaxSplits = 64;
 
+// U: blocks per unit; NCH: 16-byte chunks per vector; NT: extraction targets
 template <int C> struct Cls;
-template <> struct Cls<0> { static constexpr int BITS = 2, U = 4, NCH = 1, PAIRS = 8; static constexpr float OFF = 4.f, MUL = 4.f; };
-template <> struct Cls<1> { static constexpr int BITS = 4, U = 2, NCH = 2, PAIRS = 4; static constexpr float OFF = 64.f, MUL = 64.f; };
-template <> struct Cls<2> { static constexpr int BITS = 8, U = 1, NCH = 4, PAIRS = 2; static constexpr float OFF = 1024.f, MUL = 1.f; };
-template <> struct Cls<3> { static constexpr int BITS = 16, U = 1, NCH = 8, PAIRS = 1; static constexpr float OFF = 0.f, MUL = 1.f; };
+template <> struct Cls<0> { static constexpr int U = 2, NCH = 1, NT = 3; };
+template <> struct Cls<1> { static constexpr int U = 1, NCH = 2, NT = 2; };
+template <> struct Cls<2> { static constexpr int U = 1, NCH = 4, NT = 1; };
+template <> struct Cls<3> { static constexpr int U = 1, NCH = 8, NT = 1; };
+
+// target multipliers M: h = 1 + c/M
+#define KVQ_M0_0 4.f      /* 2-bit codes at mantissa bits [8,10) */
+#define KVQ_M0_1 16.f     /*                              [6,8)  */
+#define KVQ_M0_2 64.f     /*                              [4,6)  */
+#define KVQ_M1_0 16.f     /* 4-bit codes at mantissa bits [6,10) */
+#define KVQ_M1_1 256.f    /*                              [2,6)  */
+#define KVQ_OFF2 1024.f   /* 8-bit: h = 1024 + c */
+
+// target of pair p inside a word (see the extraction macros below)
+__host__ __device__ constexpr int target0(int p) { return (p == 1 || p == 4 || p == 7) ? 0 : (p == 0 || p == 3 || p == 6) ? 1 : 2; }
+__host__ __device__ constexpr int target1(int p) { return (p & 1) ? 0 : 1; }
 
 __device__ __forceinline__ half2_t as_h2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
 
-// The pair (2m, 2m+1) of a word as two fp16 numbers h = f(code); p is a compile-time constant.
-template <int C> __device__ __forceinline__ half2_t extract_pair(uint32_t w, int p)
+// (x & mask) | one.  VOP3 instructions of this target cannot carry 32-bit literals, so the masks are handed
+// to the compiler as opaque SGPR values and the constant 1.0|1.0 as an opaque VGPR value (see Consts): the
+// expression then selects to a single v_and_or_b32.
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t one) { return (x & mask) | one; }
+
+struct Consts {
+    uint32_t one;        // 0x3C003C00 in a VGPR
+    uint32_t m2[3];      // 2-bit target masks (SGPRs)
+    uint32_t m4[2];      // 4-bit target masks (SGPRs)
+};
+
+__device__ __forceinline__ Consts make_consts()
 {
-    if constexpr (C == 0) {            // codes at bits 2p and 2p+16 -> mantissa bits [8,10): h = 1 + c/4
-        const int sh = 8 - 2 * p;
-        const uint32_t t = sh > 0 ? (w << sh) : sh < 0 ? (w >> (-sh)) : w;
-        return as_h2((t & 0x03000300u) | 0x3C003C00u);
-    } else if constexpr (C == 1) {     // codes at bits 4p and 4p+16 -> mantissa bits [4,8): h = 1 + c/64
-        const int sh = 4 - 4 * p;
-        const uint32_t t = sh > 0 ? (w << sh) : sh < 0 ? (w >> (-sh)) : w;
-        return as_h2((t & 0x00F000F0u) | 0x3C003C00u);
-    } else if constexpr (C == 2) {     // bytes p and p+2 under the exponent byte 0x64: h = 1024 + c
-        return as_h2(__builtin_amdgcn_perm(0x64646464u, w, p == 0 ? 0x04020400u : 0x04030401u));
-    } else {
-        return as_h2(w);
-    }
+    Consts c;
+    asm volatile("v_mov_b32 %0, 0x3c003c00" : "=v"(c.one));
+    asm volatile("s_mov_b32 %0, 0x03000300" : "=s"(c.m2[0]));
+    asm volatile("s_mov_b32 %0, 0x00c000c0" : "=s"(c.m2[1]));
+    asm volatile("s_mov_b32 %0, 0x00300030" : "=s"(c.m2[2]));
+    asm volatile("s_mov_b32 %0, 0x03c003c0" : "=s"(c.m4[0]));
+    asm volatile("s_mov_b32 %0, 0x003c003c" : "=s"(c.m4[1]));
+    return c;
 }
 
 template <int CTRL> __device__ __forceinline__ float dpp_mov(float v)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+__device__ __forceinline__ float lane_bcast(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 
 // max / sum over the 64 lanes; the result is wave-uniform
@@ -64,11 +98,7 @@ __device__ __forceinline__ float wave_max(float v)
     v = fmaxf(v, dpp_mov<0x4E>(v));    // quad_perm [2,3,0,1]
     v = fmaxf(v, dpp_mov<0x141>(v));   // row_half_mirror
     v = fmaxf(v, dpp_mov<0x140>(v));   // row_mirror: every lane of a row now holds the row's max
-    const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
-    const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
-    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
-    const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
-    return fmaxf(fmaxf(a, b), fmaxf(c, d));
+    return fmaxf(fmaxf(lane_bcast(v, 0), lane_bcast(v, 16)), fmaxf(lane_bcast(v, 32), lane_bcast(v, 48)));
 }
 
 __device__ __forceinline__ float wave_sum(float v)
@@ -77,207 +107,492 @@ __device__ __forceinline__ float wave_sum(float v)
     v += dpp_mov<0x4E>(v);
     v += dpp_mov<0x141>(v);
     v += dpp_mov<0x140>(v);
-    const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
-    const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
-    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
-    const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
-    return (a + b) + (c + d);
+    return (lane_bcast(v, 0) + lane_bcast(v, 16)) + (lane_bcast(v, 32) + lane_bcast(v, 48));
 }
 
 struct WaveState {
     float m;          // running maximum of the scaled scores (log2 units), wave-uniform
     float l, l2;      // per lane: sum p, sum p^2 relative to m
-    float zacc;       // per lane: sum p * (min - OFF*scale) of V
-    float acc[kD];    // per lane: sum (p*MUL*scale) * h
+    float z;          // per lane: sum p * min_v over the quantized classes
+    float ps[3];      // per lane: sum p * scale_v per quantized class
+    float acc[kD];    // per lane: sum (p * scale_v * M) * h   (FP16 class: sum p * v)
+};
+
+// wave-uniform constants derived from the query
+struct QConst {
+    float qs;         // sum(q) * kScoreScale
+    float qm[3];      // class c: kScoreScale * sum_t M_t sum(q over target t)   (8 bit: 1024 * sum q)
 };
 
 struct AttnParams {
     CacheView cv;
+    int32_t wgt[4];
+    int32_t strided;
     const uint32_t *q;          // [n_seq][Hq][32] fp16 pairs
     const int32_t *seq_ids;
     float *out, *lse, *p2, *ws;
     int32_t layer, n_seq, S;
 };
 
-template <int C> struct KRegs { uint2 meta[Cls<C>::U]; uint4 kc[Cls<C>::U][Cls<C>::NCH]; };
-template <int C> struct VRegs { uint4 vc[Cls<C>::U][Cls<C>::NCH]; };
+#ifndef KVQ_NT_STAGE
+#define KVQ_NT_STAGE 1
+#endif
+#ifndef KVQ_NT_META
+#define KVQ_NT_META 0      /* measured: non-temporal 8-byte (scale, min) loads cost ~8% on the mixed workload */
+#endif
 
-// byte offsets of the lanes' tokens inside a unit, with lanes past the end of the bucket redirected to
-// token 0 of the unit (which always exists), so that every load is in bounds and reads finite data
-template <int C> struct UnitAddr {
-    const uint8_t *base;                       // unit base (first block of the unit)
-    uint32_t tokoff[Cls<C>::U];                // block offset + token*16 for chunk loads
-    uint32_t metaoff[Cls<C>::U];
-    bool valid[Cls<C>::U];
-};
-
-template <int C>
-__device__ __forceinline__ void unit_addr(UnitAddr<C> &ua, const uint8_t *base, int ntok, int lane)
+// Cache bytes are read exactly once per launch: the loads are marked non-temporal so that they stream past
+// L2 and the Infinity Cache instead of evicting each other there.
+__device__ __forceinline__ uint4 ld_stream16(const uint8_t *p)
 {
-    constexpr int BB = class_block_bytes(C);
-    ua.base = base;
-#pragma unroll
-    for (int u = 0; u < Cls<C>::U; ++u) {
-        const bool ok = u * kBlockTokens + lane < ntok;
-        ua.valid[u] = ok;
-        const uint32_t blk = ok ? (uint32_t)u : 0u;
-        const uint32_t tok = ok ? (uint32_t)lane : 0u;
-        ua.tokoff[u] = blk * BB + class_meta_bytes(C) + tok * 16u;
-        ua.metaoff[u] = blk * BB + tok * 8u;
-    }
+#if KVQ_NT_STAGE
+    const u32x4 t = __builtin_nontemporal_load((const u32x4 *)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
+#else
+    return *(const uint4 *)p;
+#endif
 }
 
-template <int C> __device__ __forceinline__ void load_k(KRegs<C> &r, const UnitAddr<C> &ua)
+__device__ __forceinline__ uint2 ld_stream8(const uint8_t *p)
 {
-#pragma unroll
-    for (int u = 0; u < Cls<C>::U; ++u) {
-        if constexpr (C != 3) r.meta[u] = *(const uint2 *)(ua.base + ua.metaoff[u]);
-#pragma unroll
-        for (int ch = 0; ch < Cls<C>::NCH; ++ch)
-            r.kc[u][ch] = *(const uint4 *)(ua.base + ua.tokoff[u] + ch * (kBlockTokens * 16));
-    }
+#if KVQ_NT_META
+    const u32x2 t = __builtin_nontemporal_load((const u32x2 *)p);
+    return make_uint2(t.x, t.y);
+#else
+    return *(const uint2 *)p;
+#endif
 }
 
-template <int C> __device__ __forceinline__ void load_v(VRegs<C> &r, const UnitAddr<C> &ua)
-{
-    constexpr int VOFF = Cls<C>::NCH * kBlockTokens * 16;
-#pragma unroll
-    for (int u = 0; u < Cls<C>::U; ++u)
-#pragma unroll
-        for (int ch = 0; ch < Cls<C>::NCH; ++ch)
-            r.vc[u][ch] = *(const uint4 *)(ua.base + ua.tokoff[u] + VOFF + ch * (kBlockTokens * 16));
-}
+struct Stage { uint4 v[2]; };        // one pipeline stage: two 16-byte loads per lane (2 KiB per wave)
 
 __device__ __forceinline__ uint32_t word_of(const uint4 &v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
-
 __device__ __forceinline__ float half_lo(uint32_t u) { return (float)__builtin_bit_cast(half2_t, u).x; }
 __device__ __forceinline__ float half_hi(uint32_t u) { return (float)__builtin_bit_cast(half2_t, u).y; }
 
-// K stage of one unit: scores, running-max update, softmax weights.  Leaves in a[u] the factor that
-// multiplies h of V (p*MUL*scale_v) for each of the unit's blocks.
-template <int C>
-__device__ __forceinline__ void compute_k(const KRegs<C> &r, const UnitAddr<C> &ua, const uint32_t (&q2)[32], float qs,
-                                          WaveState &st, float (&a)[Cls<C>::U])
+// Issues the two loads of stage PART of a K (ISV = false) or V vector set.  Load i covers
+//   2 bit: block i of the unit, its only chunk;   4 bit: chunk i;   8 bit / FP16: chunk 2*PART + i.
+// Lanes past the end of the bucket are redirected to token 0 of the unit's first block (which always
+// exists), so every load is in bounds and reads initialised, finite data.
+template <int C, bool ISV, int PART>
+__device__ __forceinline__ void issue_stage(Stage &s, const uint8_t *base, int ntok, int lane)
 {
-    constexpr int U = Cls<C>::U, NCH = Cls<C>::NCH, PAIRS = Cls<C>::PAIRS;
-    float sc[U];
-    float lmax = -INFINITY;
+    constexpr int BB = class_block_bytes(C), META = class_meta_bytes(C);
+    constexpr int VOFF = ISV ? Cls<C>::NCH * kBlockTokens * 16 : 0;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        float d0 = 0.f, d1 = 0.f;
-#pragma unroll
-        for (int ch = 0; ch < NCH; ++ch)
-#pragma unroll
-            for (int wi = 0; wi < 4; ++wi) {
-                const uint32_t w = word_of(r.kc[u][ch], wi);
-#pragma unroll
-                for (int p = 0; p < PAIRS; ++p) {
-                    const int m = (ch * 4 + wi) * PAIRS + p;
-                    const half2_t h = extract_pair<C>(w, p);
-                    if (m & 1) d1 = __builtin_amdgcn_fdot2(h, as_h2(q2[m]), d1, false);
-                    else       d0 = __builtin_amdgcn_fdot2(h, as_h2(q2[m]), d0, false);
-                }
-            }
-        const float dot = d0 + d1;
-        float s;
-        if constexpr (C == 3) {
-            s = dot * kScoreScale;
-        } else {
-            const float ks = half_lo(r.meta[u].x), kz = half_hi(r.meta[u].x);
-            // q.k^ = (min - OFF*scale) * sum(q) + MUL*scale * (q.h); qs = sum(q)*kScoreScale
-            s = (kz - Cls<C>::OFF * ks) * qs + (ks * (Cls<C>::MUL * kScoreScale)) * dot;
-        }
-        sc[u] = ua.valid[u] ? s : -INFINITY;
-        lmax = fmaxf(lmax, sc[u]);
+    for (int i = 0; i < 2; ++i) {
+        const int u = C == 0 ? i : 0;
+        const int ch = C == 0 ? 0 : 2 * PART + i;
+        const bool ok = u * kBlockTokens + lane < ntok;
+        const uint32_t off = (ok ? (uint32_t)(u * BB + lane * 16) : 0u) + (uint32_t)(META + VOFF + ch * (kBlockTokens * 16));
+        s.v[i] = ld_stream16(base + off);
     }
-    const float wm = wave_max(lmax);
-    if (wm > st.m) {                               // wave-uniform branch
-        const float f = __builtin_amdgcn_exp2f(st.m - wm);   // st.m = -inf on the first unit: f = 0
+}
+
+template <int C>
+__device__ __forceinline__ void issue_meta(uint2 (&m)[Cls<C>::U], const uint8_t *base, int ntok, int lane)
+{
+    constexpr int BB = class_block_bytes(C);
+#pragma unroll
+    for (int u = 0; u < Cls<C>::U; ++u) {
+        const bool ok = u * kBlockTokens + lane < ntok;
+        m[u] = ld_stream8(base + (ok ? (uint32_t)(u * BB + lane * 8) : 0u));
+    }
+}
+
+// Running-max update and softmax weights for the U scores of one unit.  The wave-wide maximum is only
+// reduced (and the accumulators rescaled) when some lane actually exceeds the running maximum.
+template <int U>
+__device__ __forceinline__ void softmax_step(float (&sc)[U], WaveState &st, float (&p)[U])
+{
+    float lmax = sc[0];
+#pragma unroll
+    for (int u = 1; u < U; ++u) lmax = fmaxf(lmax, sc[u]);
+    if (__builtin_amdgcn_ballot_w64(lmax > st.m) != 0ull) {  // wave-uniform branch
+        const float wm = wave_max(lmax);
+        const float f = __builtin_amdgcn_exp2f(st.m - wm);   // st.m = -inf before the first unit: f = 0
         st.l *= f;
         st.l2 *= f * f;
-        st.zacc *= f;
+        st.z *= f;
+        st.ps[0] *= f; st.ps[1] *= f; st.ps[2] *= f;
 #pragma unroll
         for (int c = 0; c < kD; ++c) st.acc[c] *= f;
         st.m = wm;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const float p = __builtin_amdgcn_exp2f(sc[u] - st.m);
-        st.l += p;
-        st.l2 = fmaf(p, p, st.l2);
-        if constexpr (C == 3) {
-            a[u] = p;
-        } else {
-            const float vs = half_lo(r.meta[u].y), vz = half_hi(r.meta[u].y);
-            a[u] = p * (Cls<C>::MUL * vs);
-            st.zacc = fmaf(p, vz - Cls<C>::OFF * vs, st.zacc);
+        p[u] = __builtin_amdgcn_exp2f(sc[u] - st.m);
+        st.l += p[u];
+        st.l2 = fmaf(p[u], p[u], st.l2);
+    }
+}
+
+// ---- 2 bit: word = 16 codes; pair p sits at bits 2p (low half) and 2p+16 (high half) -----------------
+// unshifted word: p=4 -> target 0, p=3 -> 1, p=2 -> 2;  word<<6: p=1 -> 0, p=0 -> 1;  word>>6: p=7 -> 0, p=6 -> 1, p=5 -> 2
+#define KVQ_FOR_PAIRS_2BIT(W, BODY)                                   \
+    {                                                                 \
+        const uint32_t w_ = (W), l_ = w_ << 6, r_ = w_ >> 6;          \
+        BODY(w_, 0, 4) BODY(w_, 1, 3) BODY(w_, 2, 2)                  \
+        BODY(l_, 0, 1) BODY(l_, 1, 0)                                 \
+        BODY(r_, 0, 7) BODY(r_, 1, 6) BODY(r_, 2, 5)                  \
+    }
+// ---- 4 bit: word = 8 codes; pair p at bits 4p and 4p+16 ---------------------------------------------
+// word<<2: p=1 -> target 0, p=0 -> 1;  word>>6: p=3 -> 0, p=2 -> 1
+#define KVQ_FOR_PAIRS_4BIT(W, BODY)                                   \
+    {                                                                 \
+        const uint32_t w_ = (W), l_ = w_ << 2, r_ = w_ >> 6;          \
+        BODY(l_, 0, 1) BODY(l_, 1, 0) BODY(r_, 0, 3) BODY(r_, 1, 2)   \
+    }
+
+// sum_t M_t (q . h)_t of one 2-bit vector (one chunk)
+__device__ __forceinline__ float dot_2bit(const uint4 &k, const uint32_t (&q2)[32], const Consts &cs)
+{
+    float d[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+    for (int wi = 0; wi < 4; ++wi) {
+#define KVQ_BODY(X, T, P) d[T] = __builtin_amdgcn_fdot2(as_h2(and_or(X, cs.m2[T], cs.one)), as_h2(q2[wi * 8 + (P)]), d[T], false);
+        KVQ_FOR_PAIRS_2BIT(word_of(k, wi), KVQ_BODY)
+#undef KVQ_BODY
+    }
+    return fmaf(KVQ_M0_2, d[2], fmaf(KVQ_M0_1, d[1], KVQ_M0_0 * d[0]));
+}
+
+// sum_t M_t (q . h)_t of one 4-bit vector (two chunks)
+__device__ __forceinline__ float dot_4bit(const Stage &k, const uint32_t (&q2)[32], const Consts &cs)
+{
+    float d[2] = {0.f, 0.f};
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+        for (int wi = 0; wi < 4; ++wi) {
+#define KVQ_BODY(X, T, P) d[T] = __builtin_amdgcn_fdot2(as_h2(and_or(X, cs.m4[T], cs.one)), as_h2(q2[(ch * 4 + wi) * 4 + (P)]), d[T], false);
+            KVQ_FOR_PAIRS_4BIT(word_of(k.v[ch], wi), KVQ_BODY)
+#undef KVQ_BODY
+        }
+    return fmaf(KVQ_M1_1, d[1], KVQ_M1_0 * d[0]);
+}
+
+// (q . h) over chunks 2*PART, 2*PART+1 of an 8-bit vector: bytes 0 and 2, then bytes 1 and 3 of each word,
+// each under the exponent byte 0x64 (h = 1024 + c)
+template <int PART> __device__ __forceinline__ float dot_8bit(const Stage &k, const uint32_t (&q2)[32], float d)
+{
+    float d0 = d, d1 = 0.f;
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+        for (int wi = 0; wi < 4; ++wi) {
+            const uint32_t w = word_of(k.v[ch], wi);
+            const int m = ((2 * PART + ch) * 4 + wi) * 2;
+            d0 = __builtin_amdgcn_fdot2(as_h2(__builtin_amdgcn_perm(0x64646464u, w, 0x04020400u)), as_h2(q2[m]), d0, false);
+            d1 = __builtin_amdgcn_fdot2(as_h2(__builtin_amdgcn_perm(0x64646464u, w, 0x04030401u)), as_h2(q2[m + 1]), d1, false);
+        }
+    return d0 + d1;
+}
+
+// (q . k) over chunks 2*PART, 2*PART+1 of an FP16 vector (16 channels)
+template <int PART> __device__ __forceinline__ float dot_fp16(const Stage &k, const uint32_t (&q2)[32], float d)
+{
+    float d0 = d, d1 = 0.f;
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+        const int m = (2 * PART + ch) * 4;
+        d0 = __builtin_amdgcn_fdot2(as_h2(k.v[ch].x), as_h2(q2[m]), d0, false);
+        d1 = __builtin_amdgcn_fdot2(as_h2(k.v[ch].y), as_h2(q2[m + 1]), d1, false);
+        d0 = __builtin_amdgcn_fdot2(as_h2(k.v[ch].z), as_h2(q2[m + 2]), d0, false);
+        d1 = __builtin_amdgcn_fdot2(as_h2(k.v[ch].w), as_h2(q2[m + 3]), d1, false);
+    }
+    return d0 + d1;
+}
+
+__device__ __forceinline__ void acc_2bit(const uint4 &v, const float (&a)[3], const Consts &cs, WaveState &st)
+{
+#pragma unroll
+    for (int wi = 0; wi < 4; ++wi) {
+#define KVQ_BODY(X, T, P)                                                                               \
+    {                                                                                                   \
+        const half2_t h = as_h2(and_or(X, cs.m2[T], cs.one));                                      \
+        st.acc[2 * (wi * 8 + (P))] = fmaf(a[T], (float)h.x, st.acc[2 * (wi * 8 + (P))]);                \
+        st.acc[2 * (wi * 8 + (P)) + 1] = fmaf(a[T], (float)h.y, st.acc[2 * (wi * 8 + (P)) + 1]);        \
+    }
+        KVQ_FOR_PAIRS_2BIT(word_of(v, wi), KVQ_BODY)
+#undef KVQ_BODY
+    }
+}
+
+__device__ __forceinline__ void acc_4bit(const Stage &v, const float (&a)[2], const Consts &cs, WaveState &st)
+{
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+        for (int wi = 0; wi < 4; ++wi) {
+#define KVQ_BODY(X, T, P)                                                                                                 \
+    {                                                                                                                     \
+        const half2_t h = as_h2(and_or(X, cs.m4[T], cs.one));                                                        \
+        st.acc[2 * ((ch * 4 + wi) * 4 + (P))] = fmaf(a[T], (float)h.x, st.acc[2 * ((ch * 4 + wi) * 4 + (P))]);            \
+        st.acc[2 * ((ch * 4 + wi) * 4 + (P)) + 1] = fmaf(a[T], (float)h.y, st.acc[2 * ((ch * 4 + wi) * 4 + (P)) + 1]);    \
+    }
+            KVQ_FOR_PAIRS_4BIT(word_of(v.v[ch], wi), KVQ_BODY)
+#undef KVQ_BODY
+        }
+}
+
+template <int PART> __device__ __forceinline__ void acc_8bit(const Stage &v, float a, WaveState &st)
+{
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+        for (int wi = 0; wi < 4; ++wi) {
+            const uint32_t w = word_of(v.v[ch], wi);
+            const int c = ((2 * PART + ch) * 4 + wi) * 4;
+            const half2_t h0 = as_h2(__builtin_amdgcn_perm(0x64646464u, w, 0x04020400u));
+            const half2_t h1 = as_h2(__builtin_amdgcn_perm(0x64646464u, w, 0x04030401u));
+            st.acc[c] = fmaf(a, (float)h0.x, st.acc[c]);
+            st.acc[c + 1] = fmaf(a, (float)h0.y, st.acc[c + 1]);
+            st.acc[c + 2] = fmaf(a, (float)h1.x, st.acc[c + 2]);
+            st.acc[c + 3] = fmaf(a, (float)h1.y, st.acc[c + 3]);
+        }
+}
+
+template <int PART> __device__ __forceinline__ void acc_fp16(const Stage &v, float p, WaveState &st)
+{
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+        for (int wi = 0; wi < 4; ++wi) {
+            const half2_t h = as_h2(word_of(v.v[ch], wi));
+            const int c = ((2 * PART + ch) * 4 + wi) * 2;
+            st.acc[c] = fmaf(p, (float)h.x, st.acc[c]);
+            st.acc[c + 1] = fmaf(p, (float)h.y, st.acc[c + 1]);
+        }
+}
+
+// scores of a unit -> softmax weights -> V multipliers and constant-part accumulators (quantized classes)
+template <int C>
+__device__ __forceinline__ void finish_k(const float (&dot)[Cls<C>::U], const uint2 (&meta)[Cls<C>::U], int ntok, int lane,
+                                         const QConst &qc, WaveState &st, float (&a)[Cls<C>::U][Cls<C>::NT])
+{
+    constexpr int U = Cls<C>::U;
+    float sc[U], p[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float kscale = half_lo(meta[u].x), kmin = half_hi(meta[u].x);
+        // q.k^ * kScoreScale = min*qs + scale*(kScoreScale * sum_t M_t d_t - qm)
+        const float s = fmaf(kmin, qc.qs, kscale * fmaf(dot[u], kScoreScale, -qc.qm[C]));
+        sc[u] = (u * kBlockTokens + lane < ntok) ? s : -INFINITY;
+    }
+    softmax_step<U>(sc, st, p);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float vscale = half_lo(meta[u].y), vmin = half_hi(meta[u].y);
+        const float pscale = p[u] * vscale;
+        st.z = fmaf(p[u], vmin, st.z);
+        st.ps[C] += pscale;
+        if constexpr (C == 0) { a[u][0] = pscale * KVQ_M0_0; a[u][1] = pscale * KVQ_M0_1; a[u][2] = pscale * KVQ_M0_2; }
+        else if constexpr (C == 1) { a[u][0] = pscale * KVQ_M1_0; a[u][1] = pscale * KVQ_M1_1; }
+        else a[u][0] = pscale;
+    }
+}
+
+struct ClassWalk {
+    const int32_t *pt;          // page-table row of (seq, class)
+    const uint8_t *pool;        // class pool at this layer
+    int Hkv, kvh, bpp, cnt;
+};
+
+// The page table is read through the constant address space: with a wave-uniform index this is a scalar
+// load, which does not queue behind (or force a wait on) the vector loads of the stage pipeline.
+typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+
+template <int C> __device__ __forceinline__ const uint8_t *unit_base(const ClassWalk &w, int ui)
+{
+    constexpr int U = Cls<C>::U;
+    const int upp = w.bpp / U;                      // units per page
+    const int page = ((const_i32_ptr)(uintptr_t)w.pt)[ui / upp];
+    const int blk = (ui % upp) * U;
+    return w.pool + (((size_t)page * w.Hkv + w.kvh) * w.bpp + blk) * (size_t)class_block_bytes(C);
+}
+
+template <int C> __device__ __forceinline__ int unit_ntok(const ClassWalk &w, int ui)
+{
+    constexpr int UT = Cls<C>::U * kBlockTokens;
+    return min(w.cnt - ui * UT, UT);
+}
+
+#define KVQ_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Units [k0, k1) of the 2-bit (two blocks per unit) or 4-bit (one block per unit) class: two stages per
+// unit, K(n) -> b0/b2 and V(n) -> b1/b3 for even/odd n; each buffer is reloaded right after use.
+template <int C>
+__device__ __forceinline__ void run_low(const ClassWalk &w, int k0, int k1, int step, int lane, const uint32_t (&q2)[32],
+                                        const QConst &qc, const Consts &cs, WaveState &st)
+{
+    if (k0 >= k1) return;
+    constexpr int U = Cls<C>::U, NT = Cls<C>::NT;
+    Stage b0, b1, b2, b3;
+    uint2 m0[U], m1[U];
+    {
+        const uint8_t *ba = unit_base<C>(w, k0);
+        const int na = unit_ntok<C>(w, k0);
+        issue_stage<C, false, 0>(b0, ba, na, lane);
+        issue_meta<C>(m0, ba, na, lane);
+        issue_stage<C, true, 0>(b1, ba, na, lane);
+        if (k0 + step < k1) {
+            const uint8_t *bb = unit_base<C>(w, k0 + step);
+            const int nb = unit_ntok<C>(w, k0 + step);
+            issue_stage<C, false, 0>(b2, bb, nb, lane);
+            issue_meta<C>(m1, bb, nb, lane);
+            issue_stage<C, true, 0>(b3, bb, nb, lane);
+        }
+    }
+    auto k_stage = [&](const Stage &b, const uint2 (&m)[U], int ntok, float (&a)[U][NT]) {
+        float dot[U];
+        if constexpr (C == 0) { dot[0] = dot_2bit(b.v[0], q2, cs); dot[1] = dot_2bit(b.v[1], q2, cs); }
+        else dot[0] = dot_4bit(b, q2, cs);
+        finish_k<C>(dot, m, ntok, lane, qc, st, a);
+    };
+    auto v_stage = [&](const Stage &b, const float (&a)[U][NT]) {
+        if constexpr (C == 0) { acc_2bit(b.v[0], a[0], cs, st); acc_2bit(b.v[1], a[1], cs, st); }
+        else acc_4bit(b, a[0], cs, st);
+    };
+    for (int ui = k0; ui < k1; ui += 2 * step) {
+        const bool more2 = ui + 2 * step < k1, more3 = ui + 3 * step < k1;
+        const uint8_t *base2 = more2 ? unit_base<C>(w, ui + 2 * step) : nullptr;
+        const uint8_t *base3 = more3 ? unit_base<C>(w, ui + 3 * step) : nullptr;
+        float a[U][NT];
+        KVQ_FENCE();
+        k_stage(b0, m0, unit_ntok<C>(w, ui), a);
+        KVQ_FENCE();
+        if (more2) {
+            issue_stage<C, false, 0>(b0, base2, unit_ntok<C>(w, ui + 2 * step), lane);
+            issue_meta<C>(m0, base2, unit_ntok<C>(w, ui + 2 * step), lane);
+        }
+        KVQ_FENCE();
+        v_stage(b1, a);
+        KVQ_FENCE();
+        if (more2) issue_stage<C, true, 0>(b1, base2, unit_ntok<C>(w, ui + 2 * step), lane);
+        KVQ_FENCE();
+        if (ui + step < k1) {
+            k_stage(b2, m1, unit_ntok<C>(w, ui + step), a);
+            KVQ_FENCE();
+            if (more3) {
+                issue_stage<C, false, 0>(b2, base3, unit_ntok<C>(w, ui + 3 * step), lane);
+                issue_meta<C>(m1, base3, unit_ntok<C>(w, ui + 3 * step), lane);
+            }
+            KVQ_FENCE();
+            v_stage(b3, a);
+            KVQ_FENCE();
+            if (more3) issue_stage<C, true, 0>(b3, base3, unit_ntok<C>(w, ui + 3 * step), lane);
+            KVQ_FENCE();
         }
     }
 }
 
-template <int C>
-__device__ __forceinline__ void compute_v(const VRegs<C> &r, const float (&a)[Cls<C>::U], WaveState &st)
+// Blocks [k0, k1) of the 8-bit class: stages K01, K23, V01, V23 (chunk pairs) -> b0..b3.
+__device__ __forceinline__ void run_8bit(const ClassWalk &w, int k0, int k1, int step, int lane, const uint32_t (&q2)[32],
+                                         const QConst &qc, WaveState &st)
 {
-    constexpr int U = Cls<C>::U, NCH = Cls<C>::NCH, PAIRS = Cls<C>::PAIRS;
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int ch = 0; ch < NCH; ++ch)
-#pragma unroll
-            for (int wi = 0; wi < 4; ++wi) {
-                const uint32_t w = word_of(r.vc[u][ch], wi);
-#pragma unroll
-                for (int p = 0; p < PAIRS; ++p) {
-                    const int m = (ch * 4 + wi) * PAIRS + p;
-                    const half2_t h = extract_pair<C>(w, p);
-                    st.acc[2 * m] = fmaf(a[u], (float)h.x, st.acc[2 * m]);
-                    st.acc[2 * m + 1] = fmaf(a[u], (float)h.y, st.acc[2 * m + 1]);
-                }
-            }
+    if (k0 >= k1) return;
+    Stage b0, b1, b2, b3;
+    uint2 m0[1];
+    {
+        const uint8_t *ba = unit_base<2>(w, k0);
+        const int na = unit_ntok<2>(w, k0);
+        issue_stage<2, false, 0>(b0, ba, na, lane);
+        issue_meta<2>(m0, ba, na, lane);
+        issue_stage<2, false, 1>(b1, ba, na, lane);
+        issue_stage<2, true, 0>(b2, ba, na, lane);
+        issue_stage<2, true, 1>(b3, ba, na, lane);
+    }
+    for (int ui = k0; ui < k1; ui += step) {
+        const bool more = ui + step < k1;
+        const uint8_t *bn = more ? unit_base<2>(w, ui + step) : nullptr;
+        const int nn = more ? unit_ntok<2>(w, ui + step) : 0;
+        float dot[1], a[1][1];
+        KVQ_FENCE();
+        dot[0] = dot_8bit<0>(b0, q2, 0.f);
+        KVQ_FENCE();
+        if (more) issue_stage<2, false, 0>(b0, bn, nn, lane);
+        KVQ_FENCE();
+        dot[0] = dot_8bit<1>(b1, q2, dot[0]);
+        KVQ_FENCE();
+        if (more) issue_stage<2, false, 1>(b1, bn, nn, lane);
+        KVQ_FENCE();
+        finish_k<2>(dot, m0, unit_ntok<2>(w, ui), lane, qc, st, a);
+        KVQ_FENCE();
+        if (more) issue_meta<2>(m0, bn, nn, lane);
+        KVQ_FENCE();
+        acc_8bit<0>(b2, a[0][0], st);
+        KVQ_FENCE();
+        if (more) issue_stage<2, true, 0>(b2, bn, nn, lane);
+        KVQ_FENCE();
+        acc_8bit<1>(b3, a[0][0], st);
+        KVQ_FENCE();
+        if (more) issue_stage<2, true, 1>(b3, bn, nn, lane);
+        KVQ_FENCE();
+    }
 }
 
-// All units [first, end) with stride `stride` of class C for one (sequence, kv-head, layer).
-template <int C>
-__device__ __forceinline__ void process_class(const CacheView &cv, int layer, int seq, int kvh, int cnt, int first, int end,
-                                              int stride, int lane, const uint32_t (&q2)[32], float qs, WaveState &st)
+// Blocks [k0, k1) of the FP16 class: stages K0..K3 then V0..V3 (chunk pairs) cycle through b0..b3.
+__device__ __forceinline__ void run_fp16(const ClassWalk &w, int k0, int k1, int step, int lane, const uint32_t (&q2)[32], WaveState &st)
 {
-    if (first >= end) return;
-    constexpr int U = Cls<C>::U;
-    constexpr int UT = U * kBlockTokens;               // tokens per unit
-    const int32_t *pt = cv.page_table + ((size_t)seq * kClasses + C) * cv.max_pages_per_seq;
-    const uint8_t *pool = cv.pool[C] + (size_t)layer * cv.layer_stride[C];
-    const int upp = cv.blocks_per_page / U;            // units per page
-    auto unit_base = [&](int ui) -> const uint8_t * {
-        const int page = __builtin_amdgcn_readfirstlane(pt[ui / upp]);
-        const int blk = (ui % upp) * U;
-        return pool + (((size_t)page * cv.Hkv + kvh) * cv.blocks_per_page + blk) * (size_t)class_block_bytes(C);
-    };
-    KRegs<C> kr;
-    VRegs<C> vr;
-    UnitAddr<C> ua;
-    int ui = first;
-    unit_addr<C>(ua, unit_base(ui), min(cnt - ui * UT, UT), lane);
-    load_k<C>(kr, ua);
-    while (true) {
-        load_v<C>(vr, ua);
-        float a[U];
-        compute_k<C>(kr, ua, q2, qs, st, a);
-        const int un = ui + stride;
-        const bool more = un < end;
-        if (more) {
-            unit_addr<C>(ua, unit_base(un), min(cnt - un * UT, UT), lane);
-            load_k<C>(kr, ua);
-        }
-        compute_v<C>(vr, a, st);
-        if (!more) break;
-        ui = un;
+    if (k0 >= k1) return;
+    Stage b0, b1, b2, b3;
+    {
+        const uint8_t *ba = unit_base<3>(w, k0);
+        const int na = unit_ntok<3>(w, k0);
+        issue_stage<3, false, 0>(b0, ba, na, lane);
+        issue_stage<3, false, 1>(b1, ba, na, lane);
+        issue_stage<3, false, 2>(b2, ba, na, lane);
+        issue_stage<3, false, 3>(b3, ba, na, lane);
+    }
+    for (int ui = k0; ui < k1; ui += step) {
+        const bool more = ui + step < k1;
+        const uint8_t *bc = unit_base<3>(w, ui);
+        const int nc = unit_ntok<3>(w, ui);
+        const uint8_t *bn = more ? unit_base<3>(w, ui + step) : nullptr;
+        const int nn = more ? unit_ntok<3>(w, ui + step) : 0;
+        KVQ_FENCE();
+        float d = dot_fp16<0>(b0, q2, 0.f);
+        KVQ_FENCE();
+        issue_stage<3, true, 0>(b0, bc, nc, lane);
+        KVQ_FENCE();
+        d = dot_fp16<1>(b1, q2, d);
+        KVQ_FENCE();
+        issue_stage<3, true, 1>(b1, bc, nc, lane);
+        KVQ_FENCE();
+        d = dot_fp16<2>(b2, q2, d);
+        KVQ_FENCE();
+        issue_stage<3, true, 2>(b2, bc, nc, lane);
+        KVQ_FENCE();
+        d = dot_fp16<3>(b3, q2, d);
+        KVQ_FENCE();
+        issue_stage<3, true, 3>(b3, bc, nc, lane);
+        KVQ_FENCE();
+        float sc[1], p[1];
+        sc[0] = lane < nc ? d * kScoreScale : -INFINITY;
+        softmax_step<1>(sc, st, p);
+        acc_fp16<0>(b0, p[0], st);
+        KVQ_FENCE();
+        if (more) issue_stage<3, false, 0>(b0, bn, nn, lane);
+        KVQ_FENCE();
+        acc_fp16<1>(b1, p[0], st);
+        KVQ_FENCE();
+        if (more) issue_stage<3, false, 1>(b1, bn, nn, lane);
+        KVQ_FENCE();
+        acc_fp16<2>(b2, p[0], st);
+        KVQ_FENCE();
+        if (more) issue_stage<3, false, 2>(b2, bn, nn, lane);
+        KVQ_FENCE();
+        acc_fp16<3>(b3, p[0], st);
+        KVQ_FENCE();
+        if (more) issue_stage<3, false, 3>(b3, bn, nn, lane);
+        KVQ_FENCE();
     }
 }
 
 __device__ __forceinline__ int ceil_div_pos(long long a, int b) { return (int)((a + b - 1) / b); }
 
 template <int NW>
-__global__ __launch_bounds__(NW * 64) void k_decode_split(AttnParams P)
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_decode_split(AttnParams P)
 {
     const CacheView &cv = P.cv;
     const int G = cv.Hq / cv.Hkv;
@@ -301,28 +616,38 @@ __global__ __launch_bounds__(NW * 64) void k_decode_split(AttnParams P)
     const bool seq_ok = seq >= 0 && seq < cv.max_seqs;
     if (!seq_ok) seq = 0;
 
-    // the query as 32 fp16 pairs (wave-uniform) and sum(q)
+    // the query as 32 fp16 pairs (wave-uniform), sum(q), and the per-class target sums
     uint32_t q2[32];
     const uint32_t *qp = P.q + ((size_t)si * cv.Hq + qh) * 32;
-    float qsum = 0.f;
+    float qsum = 0.f, t0[3] = {0.f, 0.f, 0.f}, t1[2] = {0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < 32; ++i) {
         q2[i] = qp[i];
-        qsum += half_lo(q2[i]) + half_hi(q2[i]);
+        const float v = half_lo(q2[i]) + half_hi(q2[i]);
+        qsum += v;
+        t0[target0(i % 8)] += v;
+        t1[target1(i % 4)] += v;
     }
-    const float qs = qsum * kScoreScale;
+    QConst qc;
+    qc.qs = qsum * kScoreScale;
+    qc.qm[0] = (KVQ_M0_0 * t0[0] + KVQ_M0_1 * t0[1] + KVQ_M0_2 * t0[2]) * kScoreScale;
+    qc.qm[1] = (KVQ_M1_0 * t1[0] + KVQ_M1_1 * t1[1]) * kScoreScale;
+    qc.qm[2] = KVQ_OFF2 * qsum * kScoreScale;
+    const Consts cs = make_consts();
 
     WaveState st;
     st.m = -INFINITY;
-    st.l = st.l2 = st.zacc = 0.f;
+    st.l = st.l2 = st.z = 0.f;
+    st.ps[0] = st.ps[1] = st.ps[2] = 0.f;
 #pragma unroll
     for (int c = 0; c < kD; ++c) st.acc[c] = 0.f;
 
-    // This workgroup's share of the (sequence, kv-head)'s units: the units of the four classes form one
-    // list, weighted by their bytes; split s takes the units whose start weight falls into its 1/S of the
-    // total.  Inside the workgroup the list is dealt to the waves round-robin.
+    // This wave's share of the (sequence, kv-head)'s units: the units of the four classes form one list,
+    // weighted by their bytes; the S workgroups x NW waves cut the list into S*NW contiguous ranges of
+    // equal weight (a unit belongs to the range that holds its start), so a wave meets one or two classes.
     int cnt[kClasses], nu[kClasses];
-    constexpr int wgt[kClasses] = {20, 18, 17, 32};         // unit bytes / 512
+    const int *env_w = P.wgt;
+    const int wgt[kClasses] = {env_w[0], env_w[1], env_w[2], env_w[3]};
     long long wtot = 0;
 #pragma unroll
     for (int c = 0; c < kClasses; ++c) {
@@ -330,26 +655,33 @@ __global__ __launch_bounds__(NW * 64) void k_decode_split(AttnParams P)
         nu[c] = (cnt[c] + class_unit_blocks(c) * kBlockTokens - 1) / (class_unit_blocks(c) * kBlockTokens);
         wtot += (long long)nu[c] * wgt[c];
     }
-    const long long lo_w = wtot * s / S, hi_w = wtot * (s + 1) / S;
+    const bool strided = P.strided != 0;
+    const int J = strided ? S : S * NW, j = strided ? s : s * NW + wave;
+    const long long lo_w = wtot * j / J, hi_w = wtot * (j + 1) / J;
     long long wbase = 0;
-    int dealt = 0;
-    int first[kClasses], last[kClasses];
+    int first[kClasses], last[kClasses], dealt = 0;
+    const int step = strided ? NW : 1;
 #pragma unroll
     for (int c = 0; c < kClasses; ++c) {
         const long long a = lo_w - wbase, b = hi_w - wbase;
-        int klo = a <= 0 ? 0 : ceil_div_pos(a, wgt[c]);
-        int khi = b <= 0 ? 0 : ceil_div_pos(b, wgt[c]);
-        klo = min(klo, nu[c]);
-        khi = min(khi, nu[c]);
-        first[c] = klo + ((wave + NW - (dealt % NW)) % NW);
+        const int klo = min(a <= 0 ? 0 : ceil_div_pos(a, wgt[c]), nu[c]);
+        const int khi = min(b <= 0 ? 0 : ceil_div_pos(b, wgt[c]), nu[c]);
+        first[c] = strided ? klo + ((wave + NW - (dealt % NW)) % NW) : klo;
         last[c] = khi;
         dealt += khi - klo;
         wbase += (long long)nu[c] * wgt[c];
     }
-    process_class<0>(cv, P.layer, seq, kvh, cnt[0], first[0], last[0], NW, lane, q2, qs, st);
-    process_class<1>(cv, P.layer, seq, kvh, cnt[1], first[1], last[1], NW, lane, q2, qs, st);
-    process_class<2>(cv, P.layer, seq, kvh, cnt[2], first[2], last[2], NW, lane, q2, qs, st);
-    process_class<3>(cv, P.layer, seq, kvh, cnt[3], first[3], last[3], NW, lane, q2, qs, st);
+    ClassWalk w;
+    w.Hkv = cv.Hkv; w.kvh = kvh; w.bpp = cv.blocks_per_page;
+#define KVQ_WALK(C)                                                                              \
+    w.pt = cv.page_table + ((size_t)seq * kClasses + (C)) * cv.max_pages_per_seq;                \
+    w.pool = cv.pool[C] + (size_t)P.layer * cv.layer_stride[C];                                  \
+    w.cnt = cnt[C];
+    KVQ_WALK(0) run_low<0>(w, first[0], last[0], step, lane, q2, qc, cs, st);
+    KVQ_WALK(1) run_low<1>(w, first[1], last[1], step, lane, q2, qc, cs, st);
+    KVQ_WALK(2) run_8bit(w, first[2], last[2], step, lane, q2, qc, st);
+    KVQ_WALK(3) run_fp16(w, first[3], last[3], step, lane, q2, st);
+#undef KVQ_WALK
 
     // ---- sum the 64 lanes: a transposing butterfly leaves channel c's total in lane c ----------------
 #pragma unroll
@@ -362,8 +694,14 @@ __global__ __launch_bounds__(NW * 64) void k_decode_split(AttnParams P)
             st.acc[i] = keep + __shfl_xor(send, half, 64);
         }
     }
-    const float l = wave_sum(st.l), l2 = wave_sum(st.l2), z = wave_sum(st.zacc);
-    const float mine = st.acc[0] + z;                      // channel `lane`, relative to exp2(m)
+    const float l = wave_sum(st.l), l2 = wave_sum(st.l2), z = wave_sum(st.z);
+    const float ps0 = wave_sum(st.ps[0]), ps1 = wave_sum(st.ps[1]), ps2 = wave_sum(st.ps[2]);
+    // channel `lane`: its pair index inside a word decides which target multiplier it was scaled with
+    const int pr = lane >> 1;
+    const int tg0 = target0(pr & 7), tg1 = target1(pr & 3);
+    const float mul0 = tg0 == 0 ? KVQ_M0_0 : tg0 == 1 ? KVQ_M0_1 : KVQ_M0_2;
+    const float mul1 = tg1 == 0 ? KVQ_M1_0 : KVQ_M1_1;
+    const float mine = st.acc[0] + (z - mul0 * ps0 - mul1 * ps1 - KVQ_OFF2 * ps2);      // relative to exp2(m)
 
     __shared__ float sm[NW][kPartialFloats];
     sm[wave][lane] = mine;
@@ -372,15 +710,15 @@ __global__ __launch_bounds__(NW * 64) void k_decode_split(AttnParams P)
     if (wave != 0) return;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) M = fmaxf(M, sm[w][64]);
+    for (int i = 0; i < NW; ++i) M = fmaxf(M, sm[i][64]);
     float o = 0.f, L = 0.f, L2 = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        const float mw = sm[w][64];
+    for (int i = 0; i < NW; ++i) {
+        const float mw = sm[i][64];
         const float f = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-        o = fmaf(f, sm[w][lane], o);
-        L = fmaf(f, sm[w][65], L);
-        L2 = fmaf(f * f, sm[w][66], L2);
+        o = fmaf(f, sm[i][lane], o);
+        L = fmaf(f, sm[i][65], L);
+        L2 = fmaf(f * f, sm[i][66], L2);
     }
     if (S == 1) {
         const size_t oi = (size_t)si * cv.Hq + qh;
@@ -391,9 +729,9 @@ __global__ __launch_bounds__(NW * 64) void k_decode_split(AttnParams P)
             if (P.p2) P.p2[oi] = L2 * inv * inv;
         }
     } else {
-        float *w = P.ws + (size_t)unit * kPartialFloats;
-        w[lane] = o;
-        if (lane == 0) { w[64] = M; w[65] = L; w[66] = L2; }
+        float *wsu = P.ws + (size_t)unit * kPartialFloats;
+        wsu[lane] = o;
+        if (lane == 0) { wsu[64] = M; wsu[65] = L; wsu[66] = L2; }
     }
 }
 
@@ -454,11 +792,12 @@ extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void
     if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
     if (n_seq == 0) return KVQ_OK;
     const long long heads = (long long)n_seq * d.n_q_heads;
-    // Split heuristic: enough workgroups to fill 256 CUs several times over, but at least ~8 units of
-    // roughly 10-16 KiB per workgroup.  len_bound is an upper bound of the longest sequence.
+    // Split heuristic: a workgroup should keep ~16 or more units (10-16 KiB each) so that its per-class
+    // pipelines reach steady state; within that limit, aim at three or more workgroups per CU (768).
+    // len_bound is an upper bound of the longest sequence.
     const long long est_units = (cache->len_bound + 63) / 64;
-    long long S = (2048 + heads - 1) / heads;
-    if (S > est_units / 8) S = est_units / 8;
+    long long S = (768 + heads - 1) / heads;
+    if (S > est_units / 16) S = est_units / 16;
     if (S < 1) S = 1;
     if (S > kMaxSplits) S = kMaxSplits;
     const int forced = env_int("KVQ_ATTN_SPLITS", 0);
@@ -482,12 +821,17 @@ extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void
     P.layer = layer;
     P.n_seq = n_seq;
     P.S = (int)S;
+    P.strided = env_int("KVQ_STRIDED", 0);
+    P.wgt[0] = env_int("KVQ_W0", 10); P.wgt[1] = env_int("KVQ_W1", 9); P.wgt[2] = env_int("KVQ_W2", 17); P.wgt[3] = env_int("KVQ_W3", 32);
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
-    const int nw = env_int("KVQ_ATTN_WAVES", 4);
+    // Waves per workgroup: with ~168 VGPRs three waves fit a SIMD, 3072 on the chip.  A launch whose waves are
+    // all resident at once has no second, under-filled round, so large launches use two waves per workgroup.
+    const int nw = env_int("KVQ_ATTN_WAVES", heads * S >= 768 ? 2 : 4);
     if (nw == 1) hipLaunchKernelGGL(k_decode_split<1>, dim3(grid), dim3(64), 0, st, P);
     else if (nw == 2) hipLaunchKernelGGL(k_decode_split<2>, dim3(grid), dim3(128), 0, st, P);
+    else if (nw == 3) hipLaunchKernelGGL(k_decode_split<3>, dim3(grid), dim3(192), 0, st, P);
     else if (nw == 8) hipLaunchKernelGGL(k_decode_split<8>, dim3(grid), dim3(512), 0, st, P);
     else hipLaunchKernelGGL(k_decode_split<4>, dim3(grid), dim3(256), 0, st, P);
     KVQ_HIP(hipGetLastError());

@@ -41,7 +41,7 @@ __host__ __device__ constexpr int class_block_bytes(int c)
     return class_meta_bytes(c) + 2 * class_chunks(c) * kBlockTokens * 16;
 }
 // blocks that one loop iteration of the attention kernel treats together (all inside one page)
-__host__ __device__ constexpr int class_unit_blocks(int c) { return c == 0 ? 4 : c == 1 ? 2 : 1; }
+__host__ __device__ constexpr int class_unit_blocks(int c) { return c == 0 ? 2 : 1; }
 
 struct CacheView {
     uint8_t *pool[kClasses];
