@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--no-compare", action="store_true", help="skip the static-4-bit and FP16 caches")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-events", action="store_true", help="do not bracket attention launches with events")
-    ap.add_argument("--cpu-seqs", type=int, default=4, help="sequences of one layer the CPU oracle is timed on")
+    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences of one layer the CPU oracle is timed on (0 = the whole batch)")
     return ap.parse_args()
 
 
@@ -227,13 +227,17 @@ def main():
     p1.record()
     torch.cuda.synchronize()
     stream_gbps = 5 * probe.numel() / (p0.elapsed_time(p1) * 1e-3) / 1e9
+    # one plain copy of known size (1 GiB read + 1 GiB written): the reference reading for the hardware byte counters
+    half = probe.numel() // 2
+    kvq.kvq_probe_copy(probe[half:], probe[:half])
+    torch.cuda.synchronize()
     del probe
 
     # ---------------- CPU oracle on a bounded sample -------------------------------------------------
     cpu = None
     if not args.no_cpu:
         import oracle
-        ns = min(args.cpu_seqs, B)
+        ns = min(args.cpu_seqs, B) if args.cpu_seqs > 0 else B
         T = int(lens0.max())
         # the oracle runs its own pipeline on the same seeded inputs: controller -> quantize/append -> attention
         exp_bits = []
@@ -260,13 +264,13 @@ def main():
             for s in range(ns):
                 r = int(min(max(lens0[s] - t, 0), tc))
                 if r:
-                    c, m = oracle.append(Kh[s, :r], Vh[s, :r], exp_bits[s][t:t + r])
+                    c, m = oracle.append(Kh[s, :r], Vh[s, :r], exp_bits[s][t:t + r], parallel=True)
                     codes[s, t:t + r], meta[s, t:t + r], bits_h[s, t:t + r] = c, m, exp_bits[s][t:t + r]
             del K, V
         lens_h = np.array([min(int(lens0[s]), Lmax) for s in range(ns)], np.int32)
         q = step_q[0][0][:ns].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
         best, nthr = None, 1
-        for _ in range(2):
+        for _ in range(3):
             c0 = time.perf_counter()
             _, _, _, nthr = oracle.decode_attn_batch(q, bits_h, codes, meta, lens_h, Hq)
             dt = time.perf_counter() - c0
@@ -315,9 +319,15 @@ def main():
         "stream_read_GBps": stream_gbps,
         "compare": compare,
     }
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "k_decode_split_cfg%d_traffic.txt" % cfg.index)
+    if os.path.exists(tpath) and L == cfg.n_layers:
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch="):
+                traffic = float(line.split("=", 1)[1])
     if "attn_GBps" in mixed:
         result["roofline"] = {"bound": "hbm", "achieved": mixed["attn_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                              "frac": mixed["attn_GBps"] / HBM_PEAK_GBPS, "traffic": None,
+                              "frac": mixed["attn_GBps"] / HBM_PEAK_GBPS, "traffic": traffic,
                               "kernel": "k_decode_split", "bytes_per_launch": mixed["attn_bytes_per_layer"],
                               "frac_of_stream_read": mixed["attn_GBps"] / stream_gbps}
     if cpu is not None:

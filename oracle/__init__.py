@@ -48,6 +48,7 @@ def lib() -> ctypes.CDLL:
         _lib.kvq_oracle_f32_to_f16.restype = ctypes.c_uint16
         _lib.kvq_oracle_f32_to_f16.argtypes = [ctypes.c_float]
         _lib.kvq_oracle_append.restype = ctypes.c_int
+        _lib.kvq_oracle_append_parallel.restype = ctypes.c_int
         _lib.kvq_oracle_decode_attn_batch.restype = ctypes.c_int
     return _lib
 
@@ -111,7 +112,7 @@ def dequantize_vec(codes, scale_bits: int, zero_bits: int, bits: int) -> np.ndar
     return out
 
 
-def append(k_bits, v_bits, bits):
+def append(k_bits, v_bits, bits, parallel: bool = False):
     """Quantize T tokens of one sequence/layer.  k_bits, v_bits: uint16[T,Hkv,64]; bits: uint8[T].
 
     Returns (codes uint8[T,Hkv,2,128], meta uint16[T,Hkv,2,2]).
@@ -123,7 +124,8 @@ def append(k_bits, v_bits, bits):
     assert d == D and v.shape == k.shape and b.shape == (T,)
     codes = np.zeros((T, Hkv, 2, REC), np.uint8)
     meta = np.zeros((T, Hkv, 2, 2), np.uint16)
-    rc = lib().kvq_oracle_append(_p(k), _p(v), _p(b), ctypes.c_int64(T), ctypes.c_int(Hkv), _p(codes), _p(meta))
+    fn = lib().kvq_oracle_append_parallel if parallel else lib().kvq_oracle_append
+    rc = fn(_p(k), _p(v), _p(b), ctypes.c_int64(T), ctypes.c_int(Hkv), _p(codes), _p(meta))
     if rc != 0:
         raise ValueError("bit width must be one of 2, 4, 8, 16")
     return codes, meta

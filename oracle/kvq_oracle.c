@@ -205,6 +205,18 @@ int kvq_oracle_append(const uint16_t *k, const uint16_t *v, const uint8_t *bits,
     return 0;
 }
 
+/* Batch form of the above for timing runs: the T tokens are independent, so they are split over threads. */
+int kvq_oracle_append_parallel(const uint16_t *k, const uint16_t *v, const uint8_t *bits, int64_t T, int Hkv,
+                               uint8_t *codes, uint16_t *meta)
+{
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t t = 0; t < T; ++t)
+        bad |= kvq_oracle_append(k + t * Hkv * KVQ_D, v + t * Hkv * KVQ_D, bits + t, 1, Hkv,
+                                 codes + t * Hkv * 2 * KVQ_REC, meta + t * Hkv * 2 * 2) != 0;
+    return bad ? -1 : 0;
+}
+
 /* ------------------------------------------------------------------------------------------ */
 /* Sec. 3.2: a = Softmax(q K^^T / sqrt(d_k)) V^  for one sequence, all query heads             */
 /* ------------------------------------------------------------------------------------------ */

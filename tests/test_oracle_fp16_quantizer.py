@@ -266,3 +266,12 @@ def test_append_rejects_unknown_bit_width_and_mixes_widths_per_token():
                     cw, sw, zw = static_quantizer_numpy(X[t, h][None], int(b))
                     assert np.array_equal(unpack_codes(codes[t, h, which], int(b)), cw[0])
                     assert meta[t, h, which, 0] == sw[0] and meta[t, h, which, 1] == zw[0]
+
+
+def test_threaded_append_wrapper_equals_the_plain_loop():
+    K = gen_vectors("outlier", 300 * 3, 77).reshape(300, 3, 64)
+    V = gen_vectors("student", 300 * 3, 78).reshape(300, 3, 64)
+    bits = np.random.default_rng(79).choice([2, 4, 8, 16], 300).astype(np.uint8)
+    a = oracle.append(K.view(np.uint16), V.view(np.uint16), bits)
+    b = oracle.append(K.view(np.uint16), V.view(np.uint16), bits, parallel=True)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
