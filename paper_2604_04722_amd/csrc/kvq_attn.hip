@@ -134,6 +134,12 @@ struct AttnParams {
     int32_t layer, n_seq, S;
 };
 
+// Register budget: two waves per SIMD (256 VGPRs each).  The four-buffer ring, 64 accumulators and the per-class
+// state need ~185 VGPRs; at three waves per SIMD (168) the compiler spills inside the loops, and every spill
+// reload waits for ALL outstanding loads (they share one counter), which stalls the pipeline.
+#ifndef KVQ_WAVES_PER_EU
+#define KVQ_WAVES_PER_EU 2
+#endif
 #ifndef KVQ_NT_STAGE
 #define KVQ_NT_STAGE 1
 #endif
@@ -592,7 +598,7 @@ __device__ __forceinline__ void run_fp16(const ClassWalk &w, int k0, int k1, int
 __device__ __forceinline__ int ceil_div_pos(long long a, int b) { return (int)((a + b - 1) / b); }
 
 template <int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_decode_split(AttnParams P)
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAVES_PER_EU, KVQ_WAVES_PER_EU))) void k_decode_split(AttnParams P)
 {
     const CacheView &cv = P.cv;
     const int G = cv.Hq / cv.Hkv;
@@ -643,7 +649,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(3, 3)))
     for (int c = 0; c < kD; ++c) st.acc[c] = 0.f;
 
     // This wave's share of the (sequence, kv-head)'s units: the units of the four classes form one list,
-    // weighted by their bytes; the S workgroups x NW waves cut the list into S*NW contiguous ranges of
+    // weighted by their cost; the S workgroups x NW waves cut the list into S*NW contiguous ranges of
     // equal weight (a unit belongs to the range that holds its start), so a wave meets one or two classes.
     int cnt[kClasses], nu[kClasses];
     const int *env_w = P.wgt;
@@ -822,7 +828,10 @@ extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void
     P.n_seq = n_seq;
     P.S = (int)S;
     P.strided = env_int("KVQ_STRIDED", 0);
-    P.wgt[0] = env_int("KVQ_W0", 10); P.wgt[1] = env_int("KVQ_W1", 9); P.wgt[2] = env_int("KVQ_W2", 17); P.wgt[3] = env_int("KVQ_W3", 32);
+    // Relative cost of one unit of each class (2 bit: 128 tokens, 5 KiB; 4 bit: 64 tokens, 4.5 KiB; 8 bit: 8.5 KiB;
+    // FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost VALU time for unpacking,
+    // and the ratios below are the ones that equalise the finishing times of a workgroup's waves (measured).
+    P.wgt[0] = env_int("KVQ_W0", 16); P.wgt[1] = env_int("KVQ_W1", 12); P.wgt[2] = env_int("KVQ_W2", 18); P.wgt[3] = env_int("KVQ_W3", 32);
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
