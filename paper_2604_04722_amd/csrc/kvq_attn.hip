@@ -401,7 +401,7 @@ __device__ __forceinline__ void finish_k(const float (&dot)[Cls<C>::U], const ui
 struct ClassWalk {
     const int32_t *pt;          // page-table row of (seq, class)
     const uint8_t *pool;        // class pool at this layer
-    int Hkv, kvh, bpp, cnt;
+    int Hkv, kvh, bpp, bpp_log2, cnt;
 };
 
 // The page table is read through the constant address space: with a wave-uniform index this is a scalar
@@ -411,9 +411,9 @@ typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
 template <int C> __device__ __forceinline__ const uint8_t *unit_base(const ClassWalk &w, int ui)
 {
     constexpr int U = Cls<C>::U;
-    const int upp = w.bpp / U;                      // units per page
-    const int page = ((const_i32_ptr)(uintptr_t)w.pt)[ui / upp];
-    const int blk = (ui % upp) * U;
+    const int sh = w.bpp_log2 - (U == 2 ? 1 : 0);   // log2(units per page); page_tokens is a power of two
+    const int page = ((const_i32_ptr)(uintptr_t)w.pt)[ui >> sh];
+    const int blk = (ui & ((1 << sh) - 1)) * U;
     return w.pool + (((size_t)page * w.Hkv + w.kvh) * w.bpp + blk) * (size_t)class_block_bytes(C);
 }
 
@@ -425,8 +425,13 @@ template <int C> __device__ __forceinline__ int unit_ntok(const ClassWalk &w, in
 
 #define KVQ_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// Units [k0, k1) of the 2-bit (two blocks per unit) or 4-bit (one block per unit) class: two stages per
-// unit, K(n) -> b0/b2 and V(n) -> b1/b3 for even/odd n; each buffer is reloaded right after use.
+// Prefetches past the end of a wave's range are not skipped: a conditional load would make the stage buffer a
+// merge of "new load" and "old value", and the register copies that merge needs wait for every outstanding
+// load.  Instead the loads are issued unconditionally with a token count of zero, which redirects all 64 lanes
+// to the first 16 bytes of a unit that is known to exist: one cache line of traffic per load, no branch.
+
+// Units k0, k0+step, ... < k1 of the 2-bit (two blocks per unit) or 4-bit (one block per unit) class: two
+// stages per unit, K(n) -> b0/b2 and V(n) -> b1/b3 for even/odd n; each buffer is reloaded right after use.
 template <int C>
 __device__ __forceinline__ void run_low(const ClassWalk &w, int k0, int k1, int step, int lane, const uint32_t (&q2)[32],
                                         const QConst &qc, const Consts &cs, WaveState &st)
@@ -435,19 +440,18 @@ __device__ __forceinline__ void run_low(const ClassWalk &w, int k0, int k1, int 
     constexpr int U = Cls<C>::U, NT = Cls<C>::NT;
     Stage b0, b1, b2, b3;
     uint2 m0[U], m1[U];
+    const uint8_t *safe = unit_base<C>(w, k0);
     {
-        const uint8_t *ba = unit_base<C>(w, k0);
         const int na = unit_ntok<C>(w, k0);
-        issue_stage<C, false, 0>(b0, ba, na, lane);
-        issue_meta<C>(m0, ba, na, lane);
-        issue_stage<C, true, 0>(b1, ba, na, lane);
-        if (k0 + step < k1) {
-            const uint8_t *bb = unit_base<C>(w, k0 + step);
-            const int nb = unit_ntok<C>(w, k0 + step);
-            issue_stage<C, false, 0>(b2, bb, nb, lane);
-            issue_meta<C>(m1, bb, nb, lane);
-            issue_stage<C, true, 0>(b3, bb, nb, lane);
-        }
+        issue_stage<C, false, 0>(b0, safe, na, lane);
+        issue_meta<C>(m0, safe, na, lane);
+        issue_stage<C, true, 0>(b1, safe, na, lane);
+        const bool two = k0 + step < k1;
+        const uint8_t *bb = two ? unit_base<C>(w, k0 + step) : safe;
+        const int nb = two ? unit_ntok<C>(w, k0 + step) : 0;
+        issue_stage<C, false, 0>(b2, bb, nb, lane);
+        issue_meta<C>(m1, bb, nb, lane);
+        issue_stage<C, true, 0>(b3, bb, nb, lane);
     }
     auto k_stage = [&](const Stage &b, const uint2 (&m)[U], int ntok, float (&a)[U][NT]) {
         float dot[U];
@@ -461,100 +465,98 @@ __device__ __forceinline__ void run_low(const ClassWalk &w, int k0, int k1, int 
     };
     for (int ui = k0; ui < k1; ui += 2 * step) {
         const bool more2 = ui + 2 * step < k1, more3 = ui + 3 * step < k1;
-        const uint8_t *base2 = more2 ? unit_base<C>(w, ui + 2 * step) : nullptr;
-        const uint8_t *base3 = more3 ? unit_base<C>(w, ui + 3 * step) : nullptr;
+        const uint8_t *base2 = more2 ? unit_base<C>(w, ui + 2 * step) : safe;
+        const uint8_t *base3 = more3 ? unit_base<C>(w, ui + 3 * step) : safe;
+        const int n2 = more2 ? unit_ntok<C>(w, ui + 2 * step) : 0;
+        const int n3 = more3 ? unit_ntok<C>(w, ui + 3 * step) : 0;
+        const int n1 = ui + step < k1 ? unit_ntok<C>(w, ui + step) : 0;     // 0: every lane of the odd unit is masked
         float a[U][NT];
         KVQ_FENCE();
         k_stage(b0, m0, unit_ntok<C>(w, ui), a);
         KVQ_FENCE();
-        if (more2) {
-            issue_stage<C, false, 0>(b0, base2, unit_ntok<C>(w, ui + 2 * step), lane);
-            issue_meta<C>(m0, base2, unit_ntok<C>(w, ui + 2 * step), lane);
-        }
+        issue_stage<C, false, 0>(b0, base2, n2, lane);
+        issue_meta<C>(m0, base2, n2, lane);
         KVQ_FENCE();
         v_stage(b1, a);
         KVQ_FENCE();
-        if (more2) issue_stage<C, true, 0>(b1, base2, unit_ntok<C>(w, ui + 2 * step), lane);
+        issue_stage<C, true, 0>(b1, base2, n2, lane);
         KVQ_FENCE();
-        if (ui + step < k1) {
-            k_stage(b2, m1, unit_ntok<C>(w, ui + step), a);
-            KVQ_FENCE();
-            if (more3) {
-                issue_stage<C, false, 0>(b2, base3, unit_ntok<C>(w, ui + 3 * step), lane);
-                issue_meta<C>(m1, base3, unit_ntok<C>(w, ui + 3 * step), lane);
-            }
+        if (n1 > 0) {
+            k_stage(b2, m1, n1, a);
             KVQ_FENCE();
             v_stage(b3, a);
-            KVQ_FENCE();
-            if (more3) issue_stage<C, true, 0>(b3, base3, unit_ntok<C>(w, ui + 3 * step), lane);
-            KVQ_FENCE();
         }
+        KVQ_FENCE();
+        issue_stage<C, false, 0>(b2, base3, n3, lane);
+        issue_meta<C>(m1, base3, n3, lane);
+        issue_stage<C, true, 0>(b3, base3, n3, lane);
+        KVQ_FENCE();
     }
 }
 
-// Blocks [k0, k1) of the 8-bit class: stages K01, K23, V01, V23 (chunk pairs) -> b0..b3.
+// Blocks of the 8-bit class: stages K01, K23, V01, V23 (chunk pairs) -> b0..b3.
 __device__ __forceinline__ void run_8bit(const ClassWalk &w, int k0, int k1, int step, int lane, const uint32_t (&q2)[32],
                                          const QConst &qc, WaveState &st)
 {
     if (k0 >= k1) return;
     Stage b0, b1, b2, b3;
     uint2 m0[1];
+    const uint8_t *safe = unit_base<2>(w, k0);
     {
-        const uint8_t *ba = unit_base<2>(w, k0);
         const int na = unit_ntok<2>(w, k0);
-        issue_stage<2, false, 0>(b0, ba, na, lane);
-        issue_meta<2>(m0, ba, na, lane);
-        issue_stage<2, false, 1>(b1, ba, na, lane);
-        issue_stage<2, true, 0>(b2, ba, na, lane);
-        issue_stage<2, true, 1>(b3, ba, na, lane);
+        issue_stage<2, false, 0>(b0, safe, na, lane);
+        issue_meta<2>(m0, safe, na, lane);
+        issue_stage<2, false, 1>(b1, safe, na, lane);
+        issue_stage<2, true, 0>(b2, safe, na, lane);
+        issue_stage<2, true, 1>(b3, safe, na, lane);
     }
     for (int ui = k0; ui < k1; ui += step) {
         const bool more = ui + step < k1;
-        const uint8_t *bn = more ? unit_base<2>(w, ui + step) : nullptr;
+        const uint8_t *bn = more ? unit_base<2>(w, ui + step) : safe;
         const int nn = more ? unit_ntok<2>(w, ui + step) : 0;
         float dot[1], a[1][1];
         KVQ_FENCE();
         dot[0] = dot_8bit<0>(b0, q2, 0.f);
         KVQ_FENCE();
-        if (more) issue_stage<2, false, 0>(b0, bn, nn, lane);
+        issue_stage<2, false, 0>(b0, bn, nn, lane);
         KVQ_FENCE();
         dot[0] = dot_8bit<1>(b1, q2, dot[0]);
         KVQ_FENCE();
-        if (more) issue_stage<2, false, 1>(b1, bn, nn, lane);
+        issue_stage<2, false, 1>(b1, bn, nn, lane);
         KVQ_FENCE();
         finish_k<2>(dot, m0, unit_ntok<2>(w, ui), lane, qc, st, a);
         KVQ_FENCE();
-        if (more) issue_meta<2>(m0, bn, nn, lane);
+        issue_meta<2>(m0, bn, nn, lane);
         KVQ_FENCE();
         acc_8bit<0>(b2, a[0][0], st);
         KVQ_FENCE();
-        if (more) issue_stage<2, true, 0>(b2, bn, nn, lane);
+        issue_stage<2, true, 0>(b2, bn, nn, lane);
         KVQ_FENCE();
         acc_8bit<1>(b3, a[0][0], st);
         KVQ_FENCE();
-        if (more) issue_stage<2, true, 1>(b3, bn, nn, lane);
+        issue_stage<2, true, 1>(b3, bn, nn, lane);
         KVQ_FENCE();
     }
 }
 
-// Blocks [k0, k1) of the FP16 class: stages K0..K3 then V0..V3 (chunk pairs) cycle through b0..b3.
+// Blocks of the FP16 class: stages K0..K3 then V0..V3 (chunk pairs) cycle through b0..b3.
 __device__ __forceinline__ void run_fp16(const ClassWalk &w, int k0, int k1, int step, int lane, const uint32_t (&q2)[32], WaveState &st)
 {
     if (k0 >= k1) return;
     Stage b0, b1, b2, b3;
+    const uint8_t *safe = unit_base<3>(w, k0);
     {
-        const uint8_t *ba = unit_base<3>(w, k0);
         const int na = unit_ntok<3>(w, k0);
-        issue_stage<3, false, 0>(b0, ba, na, lane);
-        issue_stage<3, false, 1>(b1, ba, na, lane);
-        issue_stage<3, false, 2>(b2, ba, na, lane);
-        issue_stage<3, false, 3>(b3, ba, na, lane);
+        issue_stage<3, false, 0>(b0, safe, na, lane);
+        issue_stage<3, false, 1>(b1, safe, na, lane);
+        issue_stage<3, false, 2>(b2, safe, na, lane);
+        issue_stage<3, false, 3>(b3, safe, na, lane);
     }
+    const uint8_t *bc = safe;
     for (int ui = k0; ui < k1; ui += step) {
         const bool more = ui + step < k1;
-        const uint8_t *bc = unit_base<3>(w, ui);
         const int nc = unit_ntok<3>(w, ui);
-        const uint8_t *bn = more ? unit_base<3>(w, ui + step) : nullptr;
+        const uint8_t *bn = more ? unit_base<3>(w, ui + step) : safe;
         const int nn = more ? unit_ntok<3>(w, ui + step) : 0;
         KVQ_FENCE();
         float d = dot_fp16<0>(b0, q2, 0.f);
@@ -578,20 +580,21 @@ __device__ __forceinline__ void run_fp16(const ClassWalk &w, int k0, int k1, int
         softmax_step<1>(sc, st, p);
         acc_fp16<0>(b0, p[0], st);
         KVQ_FENCE();
-        if (more) issue_stage<3, false, 0>(b0, bn, nn, lane);
+        issue_stage<3, false, 0>(b0, bn, nn, lane);
         KVQ_FENCE();
         acc_fp16<1>(b1, p[0], st);
         KVQ_FENCE();
-        if (more) issue_stage<3, false, 1>(b1, bn, nn, lane);
+        issue_stage<3, false, 1>(b1, bn, nn, lane);
         KVQ_FENCE();
         acc_fp16<2>(b2, p[0], st);
         KVQ_FENCE();
-        if (more) issue_stage<3, false, 2>(b2, bn, nn, lane);
+        issue_stage<3, false, 2>(b2, bn, nn, lane);
         KVQ_FENCE();
         acc_fp16<3>(b3, p[0], st);
         KVQ_FENCE();
-        if (more) issue_stage<3, false, 3>(b3, bn, nn, lane);
+        issue_stage<3, false, 3>(b3, bn, nn, lane);
         KVQ_FENCE();
+        bc = bn;
     }
 }
 
@@ -678,7 +681,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         wbase += (long long)nu[c] * wgt[c];
     }
     ClassWalk w;
-    w.Hkv = cv.Hkv; w.kvh = kvh; w.bpp = cv.blocks_per_page;
+    w.Hkv = cv.Hkv; w.kvh = kvh; w.bpp = cv.blocks_per_page; w.bpp_log2 = 31 - __builtin_clz(cv.blocks_per_page);
 #define KVQ_WALK(C)                                                                              \
     w.pt = cv.page_table + ((size_t)seq * kClasses + (C)) * cv.max_pages_per_seq;                \
     w.pool = cv.pool[C] + (size_t)P.layer * cv.layer_stride[C];                                  \

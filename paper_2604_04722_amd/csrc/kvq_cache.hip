@@ -89,7 +89,7 @@ static bool valid_desc(const kvq_cache_desc *d)
         set_error("n_q_heads (%d) must be a multiple of n_kv_heads (%d)", d->n_q_heads, d->n_kv_heads); return false;
     }
     const int P = d->page_tokens ? d->page_tokens : 256;
-    if (P < 256 || P % 256 != 0 || P > (1 << 20)) { set_error("page_tokens must be a multiple of 256"); return false; }
+    if (P < 256 || (P & (P - 1)) != 0 || P > (1 << 20)) { set_error("page_tokens must be a power of two, at least 256"); return false; }
     if (d->max_context < 1 || d->max_context > (int64_t)0x7fff0000) { set_error("max_context out of range"); return false; }
     const int64_t mpps = (d->max_context + P - 1) / P;
     for (int c = 0; c < kClasses; ++c) {
