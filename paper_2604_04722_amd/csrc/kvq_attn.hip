@@ -834,7 +834,7 @@ extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void
     // Relative cost of one unit of each class (2 bit: 128 tokens, 5 KiB; 4 bit: 64 tokens, 4.5 KiB; 8 bit: 8.5 KiB;
     // FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost VALU time for unpacking,
     // and the ratios below are the ones that equalise the finishing times of a workgroup's waves (measured).
-    P.wgt[0] = env_int("KVQ_W0", 16); P.wgt[1] = env_int("KVQ_W1", 12); P.wgt[2] = env_int("KVQ_W2", 18); P.wgt[3] = env_int("KVQ_W3", 32);
+    P.wgt[0] = env_int("KVQ_W0", 14); P.wgt[1] = env_int("KVQ_W1", 11); P.wgt[2] = env_int("KVQ_W2", 17); P.wgt[3] = env_int("KVQ_W3", 32);
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
