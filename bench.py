@@ -13,6 +13,7 @@ oracle on a bounded sample of the same workload on the host cores of this machine.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import math
 import os
@@ -36,6 +37,8 @@ def parse():
     ap.add_argument("--no-compare", action="store_true", help="skip the static-4-bit and FP16 caches")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-events", action="store_true", help="do not bracket attention launches with events")
+    ap.add_argument("--no-fused", action="store_true", help="skip the second timed loop that uses kvq_append_decode_attn")
+    ap.add_argument("--trace-steps", action="store_true", help="log the mean attention time per layer of every timed step")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences of one layer the CPU oracle is timed on (0 = the whole batch)")
     return ap.parse_args()
 
@@ -65,7 +68,7 @@ def main():
     B, Hq, Hkv = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads
     n_steps = args.warmup + args.steps
     lens0 = wl.ragged_lengths(cfg).astype(np.int64) - 1          # prefill so that the first step reaches the context
-    max_ctx = int(cfg.context + n_steps + 8)
+    max_ctx = int(cfg.context + 2 * n_steps + 16)
 
     # ---------------- controller + per-token precisions of the prefill -----------------------------
     if cfg.bits_kind == "controller":
@@ -99,7 +102,7 @@ def main():
         for w in (2, 4, 8, 16):
             need = 0
             for s in range(B):
-                need += math.ceil(((bits[s, :lens0[s]] == w).sum() + n_steps) / 256) + 1
+                need += math.ceil(((bits[s, :lens0[s]] == w).sum() + 2 * n_steps + 16) / 256) + 1
             pools.append(int(need))
         cache = kvq.Cache(L, B, Hq, Hkv, max_ctx, pool_pages=pools)
         CH = 512
@@ -136,7 +139,8 @@ def main():
     counts_np, N, Vobs, probs_tab = wl.zipf_table(cfg)
     step_logits = [wl.logits(cfg, s, B, dev) for s in range(n_steps)]
     step_ids = [torch.from_numpy(wl.zipf_ids(cfg, probs_tab, s, B)).to(dev) for s in range(n_steps)]
-    step_len = [torch.from_numpy((lens0 + s).astype(np.int32)).to(dev) for s in range(n_steps)]
+    step_len = [torch.from_numpy((lens0 + s).astype(np.int32)).to(dev) for s in range(2 * n_steps + 16)]
+    done_steps = {}                                          # cache id -> decode steps already run on it
     n_in = min(n_steps, 4)                                   # K/V/q of the new token: a few distinct sets, cycled
     step_k = [[wl.kv_chunk_fast(cfg, l, 5000 + s, B, 1, dev) for l in range(L)] for s in range(n_in)]
     step_q = [[wl.queries(cfg, l, s, B, dev) for l in range(L)] for s in range(n_in)]
@@ -152,8 +156,8 @@ def main():
         kv = sum(n * Hkv * wl.BYTES_PER_TOKEN_HEAD[w] for n, w in zip(per_class, (2, 4, 8, 16)))
         return kv + B * Hq * 64 * (2 + 4), per_class
 
-    def run_variant(variant, timed_steps, warm_steps, events):
-        cache = build_cache(variant)
+    def run_variant(variant, timed_steps, warm_steps, events, fused=False, cache=None):
+        cache = cache or build_cache(variant)
         aws = torch.empty(kvq.kvq_decode_attn_workspace(cache, B), dtype=torch.uint8, device=dev)
         counts_d = torch.from_numpy(counts_np).to(dev)
         totals_d = torch.tensor([N, Vobs], dtype=torch.int64, device=dev)
@@ -161,11 +165,13 @@ def main():
         if variant != "mixed":
             fixed = torch.full((B, 1), 4 if variant == "static4" else 16, dtype=torch.uint8, device=dev)
         ev_pairs, stage_ev = [], []
+        base_step = done_steps.get(id(cache), 0)
+        done_steps[id(cache)] = base_step + warm_steps + timed_steps
 
         def step(s, record):
             if record:
                 e0 = torch.cuda.Event(enable_timing=True); e0.record()
-            kvq.kvq_features(step_logits[s], step_ids[s], counts_d, totals_d, True, step_len[s], Hq, feats, fws, sum_p2=sum_p2)
+            kvq.kvq_features(step_logits[s % n_steps], step_ids[s % n_steps], counts_d, totals_d, True, step_len[base_step + s], Hq, feats, fws, sum_p2=sum_p2)
             if record:
                 e1 = torch.cuda.Event(enable_timing=True); e1.record()
             kvq.kvq_controller(feats, mlp, step_bits.view(-1))
@@ -175,10 +181,15 @@ def main():
             bits_now = step_bits if fixed is None else fixed
             kin, qin = step_k[s % n_in], step_q[s % n_in]
             for l in range(L):
-                kvq.kvq_append(cache, l, kin[l][0], kin[l][1], bits_now if l == 0 else None, None, B, 1)
+                if not fused:
+                    kvq.kvq_append(cache, l, kin[l][0], kin[l][1], bits_now if l == 0 else None, None, B, 1)
                 if record:
                     a0 = torch.cuda.Event(enable_timing=True); a0.record()
-                kvq.kvq_decode_attn(cache, l, qin[l], None, B, out, aws, None, sum_p2 if l == L - 1 else None)
+                if fused:
+                    kvq.kvq_append_decode_attn(cache, l, kin[l][0], kin[l][1], bits_now.view(-1) if l == 0 else None, qin[l], None, B,
+                                               out, aws, None, sum_p2 if l == L - 1 else None)
+                else:
+                    kvq.kvq_decode_attn(cache, l, qin[l], None, B, out, aws, None, sum_p2 if l == L - 1 else None)
                 if record:
                     a1 = torch.cuda.Event(enable_timing=True); a1.record()
                     ev_pairs.append((a0, a1))
@@ -187,11 +198,16 @@ def main():
             step(s, False)
         torch.cuda.synchronize()
         c_before = cache.counts()
+        # a collector pause on the host drains the launch queue and shows up as device idle time inside the event
+        # brackets, so the cyclic collector is off while the steps are timed
+        gc.collect()
+        gc.disable()
         t0 = time.perf_counter()
         for s in range(warm_steps, warm_steps + timed_steps):
             step(s, events)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        gc.enable()
         c_after = cache.counts()
         flags, _ = cache.status()
         if flags:
@@ -204,6 +220,9 @@ def main():
                "tokens_per_class": [0.5 * (x + y) for x, y in zip(mix_b, mix_a)]}
         if events:
             attn_us = [a0.elapsed_time(a1) * 1e3 for a0, a1 in ev_pairs]
+            if args.trace_steps:
+                per = np.array(attn_us).reshape(timed_steps, L).mean(axis=1)
+                log("[bench] attn us/layer by step: " + " ".join("%.0f" % x for x in per))
             res["attn_us_per_layer"] = float(np.mean(attn_us))
             res["attn_us_min"] = float(np.min(attn_us))
             res["features_us"] = float(np.mean([e0.elapsed_time(e1) * 1e3 for e0, e1, _ in stage_ev]))
@@ -213,6 +232,11 @@ def main():
 
     # ---------------- mixed-precision path: the metric ----------------------------------------------
     cache, mixed = run_variant("mixed", args.steps, args.warmup, not args.no_events)
+    # the same step with append fused into the attention launch (one kernel per layer instead of two), continuing on
+    # the same cache; its token count stays below max_context because n_steps covers both loops
+    fused = None
+    if not args.no_fused:
+        _, fused = run_variant("mixed", args.steps, args.warmup, not args.no_events, fused=True, cache=cache)
 
     # measured streaming-read rate of a trivial kernel on this device (context for the 8 TB/s nominal peak)
     probe = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
@@ -317,6 +341,9 @@ def main():
         "stages_us": {"features": mixed.get("features_us"), "controller": mixed.get("controller_us"),
                       "attn_per_layer": mixed.get("attn_us_per_layer"), "attn_per_layer_min": mixed.get("attn_us_min")},
         "stream_read_GBps": stream_gbps,
+        "fused_append_attn": None if fused is None else {
+            "us_per_step": fused["ms_per_step"] * 1e3, "launch_us_per_layer": fused.get("attn_us_per_layer"),
+            "note": "same step with kvq_append_decode_attn (append fused into the attention launch); `value` above is the four-call path"},
         "compare": compare,
     }
     traffic = None

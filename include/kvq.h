@@ -207,6 +207,21 @@ int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void *q, const 
                     void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Stages 3 + 4 in one launch, for the decode step (one new token per sequence): the Concat update of
+ * Sec. 3.2 followed by the attention of the same section, exactly as kvq_append(T = 1) followed by
+ * kvq_decode_attn would compute them.  The new token is quantized in registers (Q_b of Sec. 3.7), takes
+ * part in the softmax in its quantized form, and is stored into the cache for later steps; the older
+ * tokens are streamed from the cache.  Saves one kernel launch per layer.
+ *   k, v    device fp16 [n_seq][1][Hkv][64] (the new token)
+ *   bits    device uint8 [n_seq]; read only when layer == 0, which also does the bookkeeping (see
+ *           kvq_append); layers >= 1 must follow a layer-0 call with the same n_seq and seq_ids
+ *   q, seq_ids, out, lse_out, sum_p2_out, workspace: as for kvq_decode_attn
+ * ------------------------------------------------------------------------------------------- */
+int kvq_append_decode_attn(kvq_cache *cache, int32_t layer, const void *k, const void *v, const uint8_t *bits,
+                           const void *q, const int32_t *seq_ids, int32_t n_seq, float *out, float *lse_out,
+                           float *sum_p2_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement helpers (not part of the method): a streaming read-reduce and a plain copy of `bytes`
  * bytes (a multiple of 16), used to measure the attainable HBM rate next to the kernels above and to
  * calibrate hardware byte counters against a transfer of known size.

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
     "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_export",
     "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_append", "kvq_decode_attn_workspace",
-    "kvq_decode_attn", "kvq_probe_read", "kvq_probe_copy",
+    "kvq_decode_attn", "kvq_append_decode_attn", "kvq_probe_read", "kvq_probe_copy",
 )
 
 
@@ -81,6 +81,7 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_decode_attn_workspace.restype = sz
     lib.kvq_decode_attn_workspace.argtypes = [vp, i32]
     lib.kvq_decode_attn.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.kvq_append_decode_attn.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.kvq_probe_read.argtypes = [vp, sz, vp, vp]
     lib.kvq_probe_copy.argtypes = [vp, vp, sz, vp]
     _lib = lib
@@ -248,6 +249,17 @@ def kvq_decode_attn(cache: Cache, layer: int, q: torch.Tensor, seq_ids: Optional
                                           _ptr(out, torch.float32, "out"), _ptr(lse_out, torch.float32, "lse_out"),
                                           _ptr(sum_p2_out, torch.float32, "sum_p2_out"),
                                           _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+def kvq_append_decode_attn(cache: Cache, layer: int, k: torch.Tensor, v: torch.Tensor, bits: Optional[torch.Tensor],
+                           q: torch.Tensor, seq_ids: Optional[torch.Tensor], n_seq: int, out: torch.Tensor,
+                           workspace: torch.Tensor, lse_out: Optional[torch.Tensor] = None,
+                           sum_p2_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(load_library().kvq_append_decode_attn(
+        cache.handle, layer, _ptr(k, torch.float16, "k"), _ptr(v, torch.float16, "v"), _ptr(bits, torch.uint8, "bits"),
+        _ptr(q, torch.float16, "q"), _ptr(seq_ids, torch.int32, "seq_ids"), n_seq, _ptr(out, torch.float32, "out"),
+        _ptr(lse_out, torch.float32, "lse_out"), _ptr(sum_p2_out, torch.float32, "sum_p2_out"),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
 
 
 def kvq_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:

@@ -24,6 +24,7 @@
 // is reloaded as soon as it has been consumed, so three stages are always in flight behind the one
 // being computed.
 #include "kvq_internal.h"
+#include "kvq_quant.h"
 
 namespace kvq {
 
@@ -129,6 +130,7 @@ struct AttnParams {
     int32_t wgt[4];
     int32_t strided;
     const uint32_t *q;          // [n_seq][Hq][32] fp16 pairs
+    const __half *k_new, *v_new; // fused append: the new token's K/V [n_seq][Hkv][64], or nullptr
     const int32_t *seq_ids;
     float *out, *lse, *p2, *ws;
     int32_t layer, n_seq, S;
@@ -658,9 +660,37 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     const int *env_w = P.wgt;
     const int wgt[kClasses] = {env_w[0], env_w[1], env_w[2], env_w[3]};
     long long wtot = 0;
+    // Fused append: the newest token of the sequence (logged by the bookkeeping kernel, slot = last of its class)
+    // is not read from the cache.  It is quantized in registers from k_new / v_new, joins the softmax as one extra
+    // partial result, and the workgroup with s == 0, g == 0 stores it for later steps.
+    bool has_new = false;
+    int new_bits = 16, new_cls = 3, new_slot = 0;
+    if (P.k_new != nullptr && seq_ok && cv.last_T[seq] == 1) {
+        const size_t pos = (size_t)seq * cv.max_context + (cv.counts[(size_t)seq * 5 + 4] - 1);
+        new_bits = cv.bits_log[pos];
+        new_slot = cv.slot_log[pos];
+        new_cls = bits_to_class(new_bits);
+        has_new = true;
+    }
+    float new_score = -INFINITY, new_v = 0.f;
+    if (has_new && s == 0 && wave == 0) {
+        const size_t src = ((size_t)si * cv.Hkv + kvh) * kD + lane;
+        const int page = cv.page_table[((size_t)seq * kClasses + new_cls) * cv.max_pages_per_seq + new_slot / cv.page_tokens];
+        const int blk = (new_slot % cv.page_tokens) / kBlockTokens, tok = new_slot % kBlockTokens;
+        uint8_t *base = cv.pool[new_cls] + block_offset(cv, new_cls, P.layer, page, kvh, blk);
+        const size_t region = (size_t)class_chunks(new_cls) * kBlockTokens * 16;
+        const int mb = class_meta_bytes(new_cls);
+        __half *meta = (__half *)(base + tok * 8);
+        const bool writer = g == 0;
+        const float khat = quantize_store(P.k_new[src], new_bits, lane, tok, base + mb, meta, writer);
+        new_v = quantize_store(P.v_new[src], new_bits, lane, tok, base + mb + region, meta + 2, writer);
+        const float qf = __half2float(((const __half *)P.q)[((size_t)si * cv.Hq + qh) * kD + lane]);
+        new_score = wave_sum(qf * khat) * kScoreScale;
+    }
 #pragma unroll
     for (int c = 0; c < kClasses; ++c) {
         cnt[c] = seq_ok ? cv.counts[(size_t)seq * 5 + c] : 0;
+        if (has_new && c == new_cls) cnt[c] -= 1;
         nu[c] = (cnt[c] + class_unit_blocks(c) * kBlockTokens - 1) / (class_unit_blocks(c) * kBlockTokens);
         wtot += (long long)nu[c] * wgt[c];
     }
@@ -712,17 +742,21 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     const float mul1 = tg1 == 0 ? KVQ_M1_0 : KVQ_M1_1;
     const float mine = st.acc[0] + (z - mul0 * ps0 - mul1 * ps1 - KVQ_OFF2 * ps2);      // relative to exp2(m)
 
-    __shared__ float sm[NW][kPartialFloats];
+    __shared__ float sm[NW + 1][kPartialFloats];     // row NW: the fused new token (m = its score, l = l2 = 1, value = v^)
     sm[wave][lane] = mine;
     if (lane == 0) { sm[wave][64] = st.m; sm[wave][65] = l; sm[wave][66] = l2; }
+    if (wave == 0) {
+        sm[NW][lane] = new_v;
+        if (lane == 0) { sm[NW][64] = new_score; sm[NW][65] = 1.f; sm[NW][66] = 1.f; }
+    }
     __syncthreads();
     if (wave != 0) return;
     float M = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < NW; ++i) M = fmaxf(M, sm[i][64]);
+    for (int i = 0; i <= NW; ++i) M = fmaxf(M, sm[i][64]);
     float o = 0.f, L = 0.f, L2 = 0.f;
 #pragma unroll
-    for (int i = 0; i < NW; ++i) {
+    for (int i = 0; i <= NW; ++i) {
         const float mw = sm[i][64];
         const float f = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
         o = fmaf(f, sm[i][lane], o);
@@ -791,15 +825,11 @@ extern "C" size_t kvq_decode_attn_workspace(const kvq_cache *cache, int32_t n_se
     return (size_t)n_seq * cache->desc.n_q_heads * kMaxSplits * kPartialFloats * sizeof(float) + 256;
 }
 
-extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void *q, const int32_t *seq_ids,
-                               int32_t n_seq, float *out, float *lse_out, float *sum_p2_out,
-                               void *workspace, size_t workspace_bytes, void *stream)
+static int launch_attn(const kvq_cache *cache, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                       const int32_t *seq_ids, int32_t n_seq, float *out, float *lse_out, float *sum_p2_out,
+                       void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!cache || !q || !out) { set_error("cache, q or out is NULL"); return KVQ_ERR_INVALID_ARG; }
     const kvq_cache_desc &d = cache->desc;
-    if (layer < 0 || layer >= d.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
-    if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
-    if (n_seq == 0) return KVQ_OK;
     const long long heads = (long long)n_seq * d.n_q_heads;
     // Split heuristic: a workgroup should keep ~16 or more units (10-16 KiB each) so that its per-class
     // pipelines reach steady state; within that limit, aim at three or more workgroups per CU (768).
@@ -822,6 +852,8 @@ extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void
     AttnParams P;
     P.cv = cache->view;
     P.q = (const uint32_t *)q;
+    P.k_new = (const __half *)k_new;
+    P.v_new = (const __half *)v_new;
     P.seq_ids = seq_ids;
     P.out = out;
     P.lse = lse_out;
@@ -838,8 +870,8 @@ extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
-    // Waves per workgroup: with ~168 VGPRs three waves fit a SIMD, 3072 on the chip.  A launch whose waves are
-    // all resident at once has no second, under-filled round, so large launches use two waves per workgroup.
+    // Waves per workgroup: two waves fit a SIMD, 2048 on the chip.  A launch whose waves are all resident at once
+    // has no second, under-filled round, so large launches use two waves per workgroup.
     const int nw = env_int("KVQ_ATTN_WAVES", heads * S >= 768 ? 2 : 4);
     if (nw == 1) hipLaunchKernelGGL(k_decode_split<1>, dim3(grid), dim3(64), 0, st, P);
     else if (nw == 2) hipLaunchKernelGGL(k_decode_split<2>, dim3(grid), dim3(128), 0, st, P);
@@ -853,4 +885,33 @@ extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void
         KVQ_HIP(hipGetLastError());
     }
     return KVQ_OK;
+}
+
+extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void *q, const int32_t *seq_ids,
+                               int32_t n_seq, float *out, float *lse_out, float *sum_p2_out,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cache || !q || !out) { set_error("cache, q or out is NULL"); return KVQ_ERR_INVALID_ARG; }
+    const kvq_cache_desc &d = cache->desc;
+    if (layer < 0 || layer >= d.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq == 0) return KVQ_OK;
+    return launch_attn(cache, layer, q, nullptr, nullptr, seq_ids, n_seq, out, lse_out, sum_p2_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int kvq_append_decode_attn(kvq_cache *cache, int32_t layer, const void *k, const void *v, const uint8_t *bits,
+                                      const void *q, const int32_t *seq_ids, int32_t n_seq, float *out, float *lse_out,
+                                      float *sum_p2_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cache || !k || !v || !q || !out) { set_error("cache, k, v, q or out is NULL"); return KVQ_ERR_INVALID_ARG; }
+    const kvq_cache_desc &d = cache->desc;
+    if (layer < 0 || layer >= d.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
+    if (layer == 0 && !bits) { set_error("bits is NULL on the bookkeeping call (layer 0)"); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq == 0) return KVQ_OK;
+    if (layer == 0) {
+        const int rc = kvq_append_bookkeeping(cache, bits, seq_ids, n_seq, 1, stream);
+        if (rc != KVQ_OK) return rc;
+    }
+    return launch_attn(cache, layer, q, k, v, seq_ids, n_seq, out, lse_out, sum_p2_out, workspace, workspace_bytes, stream);
 }

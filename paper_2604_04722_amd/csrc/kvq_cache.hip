@@ -2,7 +2,7 @@
 // and the canonical export.
 #include "kvq_internal.h"
 
-#include <hip/hip_fp16.h>
+#include "kvq_quant.h"
 
 #include <cstdarg>
 #include <cstdio>
@@ -201,66 +201,6 @@ __global__ __launch_bounds__(64) void k_advance(CacheView cv, const uint8_t *bit
         cnt[0] = cc[0]; cnt[1] = cc[1]; cnt[2] = cc[2]; cnt[3] = cc[3];
         cnt[4] = len + T;
         cv.last_T[seq] = T;
-    }
-}
-
-__device__ __forceinline__ float wave_min_all(float x)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fminf(x, __shfl_xor(x, o, 64));
-    return x;
-}
-__device__ __forceinline__ float wave_max_all(float x)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
-    return x;
-}
-
-// OR of `word` over the aligned group of `per` lanes (per = 2, 4, 8 or 16)
-__device__ __forceinline__ uint32_t group_or(uint32_t word, int per)
-{
-    for (int o = 1; o < per; o <<= 1) word |= (uint32_t)__shfl_xor((int)word, o, 64);
-    return word;
-}
-
-// Q_b of one 64-vector held one element per lane, written into its block.  Every lane passes the same
-// uniform arguments.  `codes` points at the K or V code region of the block, `meta` at the token's
-// (scale, min) pair for this tensor (nullptr for FP16).
-__device__ __forceinline__ void quantize_store(__half xh, int b, int lane, int tok, uint8_t *codes, __half *meta)
-{
-    uint32_t word;
-    int per;
-    if (b == 16) {
-        per = 2;
-        word = (uint32_t)__half_as_ushort(xh) << (16 * (lane & 1));
-    } else {
-        const float x = __half2float(xh);
-        float mn = wave_min_all(x);
-        const float mx = wave_max_all(x);
-        if (mn == 0.0f) mn = 0.0f;                                  // a zero minimum of either sign is stored as +0
-        const float levels = (float)((1 << b) - 1);
-        const float range = mx - mn;
-        const float scale32 = range / levels;                      // IEEE binary32 division
-        const __half sh = __float2half_rn(scale32);                // RNE, subnormals kept
-        const float s = __half2float(sh);
-        float code = 0.0f;
-        if (s != 0.0f) {
-            code = rintf((x - mn) / s);                            // IEEE division, ties to even
-            code = fminf(fmaxf(code, 0.0f), levels);
-        }
-        per = 32 / b;
-        const int r = lane % per;
-        word = (uint32_t)code << (b * (r >> 1) + 16 * (r & 1));
-        if (lane == 0) {
-            meta[0] = sh;
-            meta[1] = __float2half_rn(mn);                         // exact: mn is an fp16 value
-        }
-    }
-    word = group_or(word, per);
-    if (lane % per == 0) {
-        const int w = lane / per;
-        *(uint32_t *)(codes + (size_t)(w >> 2) * (kBlockTokens * 16) + tok * 16 + (w & 3) * 4) = word;
     }
 }
 
@@ -471,6 +411,16 @@ extern "C" int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t s
     return KVQ_OK;
 }
 
+// launches the bookkeeping kernel for T new tokens per listed sequence (internal; arguments already validated)
+int kvq_append_bookkeeping(kvq_cache *cache, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T, void *stream)
+{
+    hipLaunchKernelGGL(k_advance, dim3(n_seq), dim3(64), 0, (hipStream_t)stream, cache->view, bits, seq_ids, n_seq, T);
+    KVQ_HIP(hipGetLastError());
+    cache->len_bound += T;
+    if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;
+    return KVQ_OK;
+}
+
 extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const void *v, const uint8_t *bits,
                           const int32_t *seq_ids, int32_t n_seq, int32_t T, void *stream)
 {
@@ -488,10 +438,8 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
     if ((total + 3) / 4 > 0x7fffffffLL) { set_error("append too large for one launch"); return KVQ_ERR_CAPACITY; }
     hipStream_t st = (hipStream_t)stream;
     if (bookkeeping) {
-        hipLaunchKernelGGL(k_advance, dim3(n_seq), dim3(64), 0, st, cache->view, bits, seq_ids, n_seq, T);
-        KVQ_HIP(hipGetLastError());
-        cache->len_bound += T;
-        if (cache->len_bound > d.max_context) cache->len_bound = d.max_context;
+        const int rc = kvq_append_bookkeeping(cache, bits, seq_ids, n_seq, T, stream);
+        if (rc != KVQ_OK) return rc;
     }
     hipLaunchKernelGGL(k_append_write, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, st, cache->view, layer,
                        (const __half *)k, (const __half *)v, seq_ids, n_seq, T, total);

@@ -72,6 +72,8 @@ struct kvq_cache {
     int64_t len_bound;                 // host-side upper bound of any sequence's length (split heuristic only)
 };
 
+int kvq_append_bookkeeping(kvq_cache *cache, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T, void *stream);
+
 namespace kvq {
 
 void set_error(const char *fmt, ...);

@@ -1,0 +1,79 @@
+// Q_b of one 64-element fp16 vector held one element per lane (paper Sec. 3.7; the scheme is the reading stated in
+// include/kvq.h), shared by the append kernel and by the fused append + attention kernel.
+#pragma once
+
+#include <hip/hip_fp16.h>
+
+#include "kvq_internal.h"
+
+namespace kvq {
+
+__device__ __forceinline__ float wave_min_all(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fminf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+__device__ __forceinline__ float wave_max_all(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+// OR of `word` over the aligned group of `per` lanes (per = 2, 4, 8 or 16)
+__device__ __forceinline__ uint32_t group_or(uint32_t word, int per)
+{
+    for (int o = 1; o < per; o <<= 1) word |= (uint32_t)__shfl_xor((int)word, o, 64);
+    return word;
+}
+
+// Q_b of one 64-vector held one element per lane, written into its block.  Every lane passes the same
+// uniform arguments.  `codes` points at the K or V code region of the block, `meta` at the token's
+// (scale, min) pair for this tensor (nullptr for FP16).
+//
+// Returns the lane's dequantized element min + code*scale (exact product, one fp32 rounding on the sum), so that a
+// caller can use the token in registers exactly as a later read of the cache would see it.  With store == false
+// nothing is written.
+__device__ __forceinline__ float quantize_store(__half xh, int b, int lane, int tok, uint8_t *codes, __half *meta, bool store = true)
+{
+    uint32_t word;
+    int per;
+    float deq;
+    if (b == 16) {
+        per = 2;
+        word = (uint32_t)__half_as_ushort(xh) << (16 * (lane & 1));
+        deq = __half2float(xh);
+    } else {
+        const float x = __half2float(xh);
+        float mn = wave_min_all(x);
+        const float mx = wave_max_all(x);
+        if (mn == 0.0f) mn = 0.0f;                                  // a zero minimum of either sign is stored as +0
+        const float levels = (float)((1 << b) - 1);
+        const float range = mx - mn;
+        const float scale32 = range / levels;                      // IEEE binary32 division
+        const __half sh = __float2half_rn(scale32);                // RNE, subnormals kept
+        const float s = __half2float(sh);
+        float code = 0.0f;
+        if (s != 0.0f) {
+            code = rintf((x - mn) / s);                            // IEEE division, ties to even
+            code = fminf(fmaxf(code, 0.0f), levels);
+        }
+        per = 32 / b;
+        const int r = lane % per;
+        word = (uint32_t)code << (b * (r >> 1) + 16 * (r & 1));
+        deq = fmaf(code, s, mn);
+        if (store && lane == 0) {
+            meta[0] = sh;
+            meta[1] = __float2half_rn(mn);                         // exact: mn is an fp16 value
+        }
+    }
+    word = group_or(word, per);
+    if (store && lane % per == 0) {
+        const int w = lane / per;
+        *(uint32_t *)(codes + (size_t)(w >> 2) * (kBlockTokens * 16) + tok * 16 + (w & 3) * 4) = word;
+    }
+    return deq;
+}
+
+}  // namespace kvq

@@ -309,3 +309,59 @@ def test_running_twice_gives_bitwise_identical_attention():
         a, _, _ = run_attn(cache, 0, q, B, Hq)
         b, _, _ = run_attn(cache, 0, q, B, Hq)
     assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (9, 3)])
+@pytest.mark.parametrize("splits", [0, 1, 3])
+def test_fused_append_attention_equals_the_oracle_and_the_two_call_path(Hq, Hkv, splits):
+    say("fused append+attention Hq=%d Hkv=%d splits=%d: decode steps from an empty cache and after a prefill" % (Hq, Hkv, splits))
+    B, L, T0, steps = 3, 2, 333, 70
+    rng = np.random.default_rng(140 + Hq)
+    for prefill_len in (0, T0):
+        cache = kvq.Cache(L, B, Hq, Hkv, 512)
+        ref = kvq.Cache(L, B, Hq, Hkv, 512)                       # same tokens through kvq_append + kvq_decode_attn
+        ocs = [OracleCache(B, Hkv) for _ in range(L)]
+        if prefill_len:
+            bits = rng.choice([2, 4, 8, 16], (B, prefill_len)).astype(np.uint8)
+            bt = torch.from_numpy(bits).to(dev())
+            for l in range(L):
+                K, V = make_kv((B, prefill_len, Hkv, 64), 150 + l), make_kv((B, prefill_len, Hkv, 64), 160 + l)
+                for c in (cache, ref):
+                    kvq.kvq_append(c, l, gpu_f16(K), gpu_f16(V), bt if l == 0 else None, None, B, prefill_len)
+                for s in range(B):
+                    ocs[l].append(s, K[s], V[s], bits[s])
+        ws = torch.empty(kvq.kvq_decode_attn_workspace(cache, B), dtype=torch.uint8, device=dev())
+        for step in range(steps):
+            sb = rng.choice([2, 4, 8, 16], (B, 1)).astype(np.uint8)
+            bt = torch.from_numpy(sb).to(dev())
+            for l in range(L):
+                K, V = make_kv((B, 1, Hkv, 64), 1000 + 10 * step + l), make_kv((B, 1, Hkv, 64), 5000 + 10 * step + l)
+                q = make_kv((B, Hq, 64), 9000 + 10 * step + l, outlier=False)
+                out = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=dev())
+                lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
+                p2 = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
+                with env(KVQ_ATTN_SPLITS=splits):
+                    kvq.kvq_append_decode_attn(cache, l, gpu_f16(K), gpu_f16(V), bt if l == 0 else None, gpu_f16(q), None, B,
+                                               out, ws, lse, p2)
+                for s in range(B):
+                    ocs[l].append(s, K[s, 0:1].reshape(1, Hkv, 64), V[s, 0:1].reshape(1, Hkv, 64), sb[s])
+                if step % 23 == 0 or step == steps - 1:
+                    out2 = torch.zeros_like(out)
+                    kvq.kvq_append(ref, l, gpu_f16(K), gpu_f16(V), bt if l == 0 else None, None, B, 1)
+                    with env(KVQ_ATTN_SPLITS=splits):
+                        kvq.kvq_decode_attn(ref, l, gpu_f16(q), None, B, out2, ws)
+                    torch.cuda.synchronize()
+                    o, o2 = out.cpu().numpy(), out2.cpu().numpy()
+                    for s in range(B):
+                        want, want_lse, probs = ocs[l].attn(s, q[s], Hq, want_probs=True)
+                        assert_attn_close(o[s], want, "fused step %d layer %d seq %d" % (step, l, s))
+                        assert_attn_close(o2[s], want, "two-call step %d layer %d seq %d" % (step, l, s))
+                        np.testing.assert_allclose(lse.cpu().numpy()[s], want_lse, rtol=1e-4, atol=1e-4)
+                        np.testing.assert_allclose(p2.cpu().numpy()[s], (probs ** 2).sum(axis=1), rtol=2e-3)
+                else:
+                    kvq.kvq_append(ref, l, gpu_f16(K), gpu_f16(V), bt if l == 0 else None, None, B, 1)
+        torch.cuda.synchronize()
+        for l in range(L):
+            for s in range(B):
+                assert_export_equals(cache, l, s, ocs[l])         # what the fused kernel stored is bit-exact
+        assert cache.status()[0] == 0
