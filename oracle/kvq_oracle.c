@@ -139,6 +139,7 @@ void kvq_oracle_quantize_vec(const uint16_t *x, int bits, uint8_t *codes, uint16
         if (f > mx) { mx = f; }
     }
     if (mn == 0.0f) { mn = 0.0f; mn_bits = 0; }               /* canonical +0 */
+    if (mx == 0.0f) { mx = 0.0f; }                            /* likewise: the range of a vector of zeros of either sign is +0 */
     volatile float range = mx - mn;
     volatile float scale32 = range / (float)levels;
     const uint16_t sh = kvq_oracle_f32_to_f16(scale32);

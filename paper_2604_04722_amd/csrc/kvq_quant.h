@@ -47,8 +47,9 @@ __device__ __forceinline__ float quantize_store(__half xh, int b, int lane, int 
     } else {
         const float x = __half2float(xh);
         float mn = wave_min_all(x);
-        const float mx = wave_max_all(x);
+        float mx = wave_max_all(x);
         if (mn == 0.0f) mn = 0.0f;                                  // a zero minimum of either sign is stored as +0
+        if (mx == 0.0f) mx = 0.0f;                                  // and a zero maximum counts as +0: zeros have range +0
         const float levels = (float)((1 << b) - 1);
         const float range = mx - mn;
         const float scale32 = range / levels;                      // IEEE binary32 division

@@ -172,6 +172,24 @@ def test_zero_minimum_of_either_sign_is_stored_as_plus_zero():
 
 
 @pytest.mark.parametrize("bits", [2, 4, 8])
+def test_vectors_of_zeros_of_any_sign_are_constant_vectors_with_scale_plus_zero(bits):
+    # the constant-vector case: scale 0 (bit pattern +0), codes 0, zero-point +0, whatever the signs and their order
+    pz, nz = np.float16(0.0), np.float16(-0.0)
+    for x in (np.full(64, nz), np.full(64, pz), np.where(np.arange(64) % 2 == 0, nz, pz), np.where(np.arange(64) % 2 == 0, pz, nz)):
+        x = x.astype(np.float16)
+        codes, s, z = oracle.quantize_vec(x.view(np.uint16), bits)
+        assert s == 0 and z == 0 and not codes.any()
+    # a negative minimum with a zero maximum of either sign: same scale and codes for both signs
+    a = -np.abs(gen_vectors("normal", 1, 12)[0])
+    a[5] = pz
+    b = a.copy()
+    b[5] = nz
+    ca, sa, za = oracle.quantize_vec(a.view(np.uint16), bits)
+    cb, sb, zb = oracle.quantize_vec(b.view(np.uint16), bits)
+    assert sa == sb and za == zb and np.array_equal(ca, cb)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
 @pytest.mark.parametrize("kind", ["normal", "outlier", "student", "huge"])
 def test_min_gets_code_zero_max_gets_top_code_and_error_is_at_most_half_a_step(bits, kind):
     levels = 2 ** bits - 1
