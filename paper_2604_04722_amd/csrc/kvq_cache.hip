@@ -240,6 +240,172 @@ __global__ __launch_bounds__(256) void k_append_write(CacheView cv, int layer, c
     quantize_store(v[src], b, lane, tok, base + meta_bytes + region, meta + 2);
 }
 
+// ---- bulk (prefill) append: lane = token ------------------------------------------------------------------
+//
+// With many tokens per sequence in one call, a wavefront takes 64 consecutive input tokens of one (layer, sequence,
+// kv-head); each lane holds its token's whole 64-element vector in 32 registers (element pair (2m, 2m+1) per
+// register, exactly the pairing of the cache's words), finds min and max without any cross-lane traffic, quantizes
+// in place and writes its 16-byte chunks.  Lanes of one class hold consecutive slots, so their chunk stores are
+// contiguous.
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// Q_b of the lane's vector, in place: p[m] becomes code(2m) | code(2m+1) << 16.  Returns scale bits | min bits << 16.
+// Same arithmetic as quantize_store.  The quotient (x - min) / s is first formed with a reciprocal (error below
+// 7e-5 for quotients up to 1.5 * 255); it decides the rounding unless it lies within 2^-12 of a tie, where the
+// IEEE division is evaluated, so every code equals rint of the correctly rounded quotient.
+__device__ __forceinline__ uint32_t quantize_lane(uint32_t (&p)[32], float levels)
+{
+    f16x2 mn2 = __builtin_bit_cast(f16x2, p[0]), mx2 = mn2;
+#pragma unroll
+    for (int m = 1; m < 32; ++m) {
+        const f16x2 x = __builtin_bit_cast(f16x2, p[m]);
+        mn2 = __builtin_elementwise_min(mn2, x);
+        mx2 = __builtin_elementwise_max(mx2, x);
+    }
+    float mn = fminf((float)mn2[0], (float)mn2[1]);
+    float mx = fmaxf((float)mx2[0], (float)mx2[1]);
+    if (mn == 0.0f) mn = 0.0f;
+    if (mx == 0.0f) mx = 0.0f;
+    const float range = mx - mn;
+    const float scale32 = range / levels;                          // IEEE binary32 division
+    const __half sh = __float2half_rn(scale32);
+    const float s = __half2float(sh);
+    const float inv = s != 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f;  // s == 0: every quotient reads 0, every code is 0
+#pragma unroll
+    for (int m = 0; m < 32; ++m) {
+        const f16x2 x = __builtin_bit_cast(f16x2, p[m]);
+        uint32_t c[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const float d = (float)x[e] - mn;
+            const float q = d * inv;
+            float r = rintf(q);
+            if (fabsf(q - r) > 0.5f - 0x1p-12f) r = rintf(d / s);
+            r = fminf(fmaxf(r, 0.0f), levels);
+            c[e] = (uint32_t)r;
+        }
+        p[m] = c[0] | (c[1] << 16);
+    }
+    return (uint32_t)__half_as_ushort(sh) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
+}
+
+// packs the lane's 32 pair registers into the words of class C and stores them as 16-byte chunks
+template <int C> __device__ __forceinline__ void pack_store(const uint32_t (&p)[32], uint8_t *codes, int tok)
+{
+    constexpr int b = class_bits(C);
+    constexpr int PW = 16 / b;                                      // pair registers per 32-bit word
+    constexpr int NWORDS = 32 / PW;
+#pragma unroll
+    for (int c = 0; c < NWORDS / 4; ++c) {
+        u32x4 o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int j = 0; j < PW; ++j) word |= p[(4 * c + k) * PW + j] << (b * j);
+            o[k] = word;
+        }
+        *(u32x4 *)(codes + (size_t)c * (kBlockTokens * 16) + tok * 16) = o;
+    }
+}
+
+constexpr int kStageRow = 2 * kD + 16;                             // LDS row: one 128-byte vector + 16 bytes of padding
+
+// Coalesced read of a tile's 64 vectors (row stride `row_halves`): each load instruction takes 8 whole 128-byte
+// rows, 8 lanes per row.  Rows past the ragged tail repeat the last valid row.
+__device__ __forceinline__ void tile_load(u32x4 (&x)[8], const __half *tile_src, size_t row_halves, int nrow, int lane)
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int row = i * 8 + (lane >> 3);
+        row = row < nrow ? row : nrow - 1;
+        x[i] = __builtin_nontemporal_load((const u32x4 *)(tile_src + (size_t)row * row_halves) + (lane & 7));
+    }
+}
+
+// Transposition through the wavefront's own LDS rows: afterwards lane t holds row t in p[0..31].  The padded row
+// stride keeps both the 8-lanes-per-row writes and the lane-per-row reads free of bank conflicts.
+__device__ __forceinline__ void tile_transpose(const u32x4 (&x)[8], uint32_t (&p)[32], uint8_t *stage, int lane)
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        *(u32x4 *)(stage + (i * 8 + (lane >> 3)) * kStageRow + (lane & 7) * 16) = x[i];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const u32x4 y = *(const u32x4 *)(stage + lane * kStageRow + c * 16);
+        p[4 * c + 0] = y[0]; p[4 * c + 1] = y[1]; p[4 * c + 2] = y[2]; p[4 * c + 3] = y[3];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ void quantize_pack_store(uint32_t (&p)[32], int cls, uint8_t *codes, uint32_t *meta, int tok)
+{
+    if (cls != 3) *meta = quantize_lane(p, (float)((1 << (2 << cls)) - 1));
+    switch (cls) {
+    case 0: pack_store<0>(p, codes, tok); break;
+    case 1: pack_store<1>(p, codes, tok); break;
+    case 2: pack_store<2>(p, codes, tok); break;
+    default: pack_store<3>(p, codes, tok); break;
+    }
+}
+
+// One wavefront per (layer, sequence, tile of 64 input tokens, kv-head); k and v must be 16-byte aligned.
+__global__ __launch_bounds__(256) void k_append_bulk(CacheView cv, int layer, const __half *k, const __half *v,
+                                                     const int32_t *seq_ids, int n_seq, int T, int tiles, long long total_waves)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][kBlockTokens * kStageRow];
+    const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    uint8_t *stage = stage_all[threadIdx.x >> 6];
+    if (wave >= total_waves) return;
+    long long r = wave;
+    const int h = (int)(r % cv.Hkv); r /= cv.Hkv;
+    const int tile = (int)(r % tiles); r /= tiles;
+    const int si = (int)(r % n_seq);
+    const int li = (int)(r / n_seq);
+    const int L = layer < 0 ? li : layer;
+    const int seq = seq_ids ? seq_ids[si] : si;
+    if (seq < 0 || seq >= cv.max_seqs) return;
+    const int lastT = cv.last_T[seq];
+    if (lastT != T) return;                                        // the bookkeeping call skipped this sequence
+    const int nrow = T - tile * kBlockTokens < kBlockTokens ? T - tile * kBlockTokens : kBlockTokens;
+    const size_t row_halves = (size_t)cv.Hkv * kD;
+    const size_t src = ((((size_t)li * n_seq + si) * T + (size_t)tile * kBlockTokens) * cv.Hkv + h) * kD;
+    u32x4 x[8];
+    uint32_t p[32];
+    tile_load(x, k + src, row_halves, nrow, lane);
+
+    // where this lane's token goes (lanes past the ragged tail compute nothing and store nothing)
+    const bool valid = lane < nrow;
+    int cls = 3, tok = 0;
+    uint8_t *base = nullptr;
+    if (valid) {
+        const int len = cv.counts[(size_t)seq * 5 + 4];
+        const size_t pos = (size_t)seq * cv.max_context + (len - lastT + tile * kBlockTokens + lane);
+        const int b = cv.bits_log[pos];
+        const int slot = cv.slot_log[pos];
+        cls = bits_to_class(b);
+        const int page = cv.page_table[((size_t)seq * kClasses + cls) * cv.max_pages_per_seq + slot / cv.page_tokens];
+        const int blk = (slot % cv.page_tokens) / kBlockTokens;
+        tok = slot % kBlockTokens;
+        base = cv.pool[cls] + block_offset(cv, cls, L, page, h, blk);
+    }
+    const int meta_bytes = cls == 3 ? 0 : kBlockTokens * 8;
+    const size_t region = (size_t)(1 << cls) * kBlockTokens * 16;
+    uint32_t *meta = (uint32_t *)(base + tok * 8);
+
+    tile_transpose(x, p, stage, lane);
+    tile_load(x, v + src, row_halves, nrow, lane);                 // V is in flight while K is quantized
+    if (valid) quantize_pack_store(p, cls, base + meta_bytes, meta, tok);
+    tile_transpose(x, p, stage, lane);
+    if (valid) quantize_pack_store(p, cls, base + meta_bytes + region, meta + 1, tok);
+}
+
 // Canonical dump of one (layer, sequence): one wavefront per (token, kv-head), lane = element.
 __global__ __launch_bounds__(256) void k_export(CacheView cv, int layer, int seq, uint8_t *bits_out, uint8_t *codes_out,
                                                 uint16_t *meta_out, long long max_tokens)
@@ -441,8 +607,17 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
         const int rc = kvq_append_bookkeeping(cache, bits, seq_ids, n_seq, T, stream);
         if (rc != KVQ_OK) return rc;
     }
-    hipLaunchKernelGGL(k_append_write, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, st, cache->view, layer,
-                       (const __half *)k, (const __half *)v, seq_ids, n_seq, T, total);
+    // many tokens per sequence: the lane-per-token kernel (needs 16-byte aligned vectors); else a wave per vector
+    static const int bulk_min_T = getenv("KVQ_APPEND_BULK_MIN_T") ? atoi(getenv("KVQ_APPEND_BULK_MIN_T")) : 32;
+    if (T >= bulk_min_T && (((uintptr_t)k | (uintptr_t)v) & 15) == 0) {
+        const int tiles = (T + kBlockTokens - 1) / kBlockTokens;
+        const long long waves = nl * n_seq * (long long)tiles * d.n_kv_heads;
+        hipLaunchKernelGGL(k_append_bulk, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer,
+                           (const __half *)k, (const __half *)v, seq_ids, n_seq, T, tiles, waves);
+    } else {
+        hipLaunchKernelGGL(k_append_write, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, st, cache->view, layer,
+                           (const __half *)k, (const __half *)v, seq_ids, n_seq, T, total);
+    }
     KVQ_HIP(hipGetLastError());
     return KVQ_OK;
 }
