@@ -1,12 +1,17 @@
 // Controller forward (paper Sec. 3.6): h1 = ReLU(W1 s + b1), h2 = ReLU(W2 h1 + b2), o = W3 h2 + b3,
 // class = argmax_k o_k, bits = {2,4,8,16}[class] (label mapping of Algorithm 1).
 //
-// Two launch shapes compute bit-identical logits (each output is the same sequential fp32 FMA chain
-// bias + sum_i W[j][i]*h[i], i ascending):
+// Three launch shapes:
 //   - per-step shape (few rows): one workgroup per row, thread = output unit, activations in LDS;
-//   - bulk shape (cache construction, thousands to millions of rows): thread = row, activations in LDS
-//     columns, weights read through wave-uniform loads, four outputs per pass to reuse each activation.
+//   - bulk shape on the matrix cores (cache construction, thousands to millions of rows; hidden widths 32, 64 or
+//     128): a wavefront takes 32 rows, the hidden layers are fp32 MFMA 32x32x2 tiles whose accumulators feed the
+//     next layer's B operand directly, the 4-output layer is a short vector dot product;
+//   - bulk shape on the vector ALU (any other width up to 256): thread = row, activations in LDS columns.
+// The first and the last compute bit-identical logits (each output is the same sequential fp32 FMA chain
+// bias + sum_i W[j][i]*h[i], i ascending); the MFMA shape sums the same fp32 products in another order.
 #include "kvq_internal.h"
+
+#include <cstdlib>
 
 namespace kvq {
 
@@ -103,6 +108,152 @@ __global__ __launch_bounds__(kBulkThreads) void k_mlp_bulk(MlpArgs A, int maxw)
     emit_decision(o, nout, row, A.bits, A.logits);
 }
 
+// ---- bulk shape on the matrix cores -------------------------------------------------------------------------
+//
+// v_mfma_f32_32x32x2_f32 computes D[32x32] = A[32x2] * B[2x32] + C.  Here i (rows of A, D) is the output unit and
+// j (columns of B, D) is the token, so one wavefront carries 32 tokens through the network:
+//   A: lane l holds A[i = l%32][k = l/32];  B: lane l holds B[k = l/32][j = l%32];
+//   D: lane l, register r holds D[i = 8*(r/4) + 4*(l/32) + r%4][j = l%32].
+// A layer's output register r therefore holds, in the lanes of half hh = l/32, unit u(r, hh) = 8*(r/4) + 4*hh + r%4
+// of token l%32: exactly a B operand for one k-step of the next layer whose two k indices are u(r,0) and u(r,1).
+// The order of the k-steps is free, so the registers are used as they are and the weights are staged in LDS in the
+// matching order (lane l of step r reads W[i = l%32][u(r, l/32)]).  Nothing is shuffled between layers.
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__host__ __device__ constexpr size_t mfma_lds_floats(int T1, int T2)
+{
+    const int TL = T2 ? T2 : T1;
+    return (size_t)T1 * 128 + T1 * 32 + (size_t)T2 * T1 * 1024 + T2 * 32 + TL * 128 + 4;
+}
+
+template <int T1, int T2>       // hidden widths 32*T1 and 32*T2; T2 == 0: one hidden layer
+__global__ __launch_bounds__(256) void k_mlp_mfma(MlpArgs A, long long ntiles)
+{
+    extern __shared__ float lds[];
+    constexpr int TL = T2 ? T2 : T1;
+    float *w1p = lds;                               // [T1][2 k-steps][64 lanes]
+    float *b1p = w1p + T1 * 128;                    // [T1][16 regs][2 halves]
+    float *w2p = b1p + T1 * 32;                     // [T2][T1][16 regs][64 lanes]
+    float *b2p = w2p + (size_t)T2 * T1 * 1024;      // [T2][16][2]
+    float *wfp = b2p + T2 * 32;                     // [TL][16][2][4 outputs]
+    float *bfp = wfp + TL * 128;                    // [4]
+    const int tid = threadIdx.x;
+    const float *W1 = A.W[0], *Wf = A.W[T2 ? 2 : 1];
+    for (int idx = tid; idx < T1 * 128; idx += 256) {
+        const int l = idx & 63, s = (idx >> 6) & 1, ot = idx >> 7;
+        w1p[idx] = W1[(32 * ot + (l & 31)) * 4 + 2 * s + (l >> 5)];
+    }
+    for (int idx = tid; idx < T1 * 32; idx += 256) {
+        const int hh = idx & 1, r = (idx >> 1) & 15, it = idx >> 5;
+        b1p[idx] = A.b[0][32 * it + (r >> 2) * 8 + hh * 4 + (r & 3)];
+    }
+    if constexpr (T2 > 0) {
+        const float *W2 = A.W[1];
+        for (int idx = tid; idx < T2 * T1 * 1024; idx += 256) {
+            const int l = idx & 63, r = (idx >> 6) & 15, rest = idx >> 10;
+            const int it = rest % T1, ot = rest / T1;
+            w2p[idx] = W2[(size_t)(32 * ot + (l & 31)) * (32 * T1) + 32 * it + (r >> 2) * 8 + (l >> 5) * 4 + (r & 3)];
+        }
+        for (int idx = tid; idx < T2 * 32; idx += 256) {
+            const int hh = idx & 1, r = (idx >> 1) & 15, it = idx >> 5;
+            b2p[idx] = A.b[1][32 * it + (r >> 2) * 8 + hh * 4 + (r & 3)];
+        }
+    }
+    for (int idx = tid; idx < TL * 128; idx += 256) {
+        const int o = idx & 3, hh = (idx >> 2) & 1, r = (idx >> 3) & 15, it = idx >> 7;
+        wfp[idx] = Wf[o * (32 * TL) + 32 * it + (r >> 2) * 8 + hh * 4 + (r & 3)];
+    }
+    if (tid < 4) bfp[tid] = A.b[T2 ? 2 : 1][tid];
+    __syncthreads();
+
+    const int lane = tid & 63, hh = lane >> 5, j = lane & 31;
+    const long long stride = (long long)gridDim.x * 4;
+    for (long long tile = (long long)blockIdx.x * 4 + (tid >> 6); tile < ntiles; tile += stride) {
+        const long long row = tile * 32 + j;
+        const bool live = row < A.n;
+        const f32x4 x = *(const f32x4 *)(A.feats + (live ? row : A.n - 1) * 4);
+        const float xb[2] = {hh ? x[1] : x[0], hh ? x[3] : x[2]};
+        f32x16 h1[T1];
+#pragma unroll
+        for (int it = 0; it < T1; ++it) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) h1[it][r] = b1p[(it * 16 + r) * 2 + hh];
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                h1[it] = __builtin_amdgcn_mfma_f32_32x32x2f32(w1p[(it * 2 + s) * 64 + lane], xb[s], h1[it], 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) h1[it][r] = fmaxf(h1[it][r], 0.f);
+        }
+        f32x16 h2[T2 ? T2 : 1];
+        if constexpr (T2 > 0) {
+#pragma unroll
+            for (int ot = 0; ot < T2; ++ot)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) h2[ot][r] = b2p[(ot * 16 + r) * 2 + hh];
+#pragma unroll
+            for (int it = 0; it < T1; ++it)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+#pragma unroll
+                    for (int ot = 0; ot < T2; ++ot)
+                        h2[ot] = __builtin_amdgcn_mfma_f32_32x32x2f32(w2p[((ot * T1 + it) * 16 + r) * 64 + lane], h1[it][r], h2[ot], 0, 0, 0);
+#pragma unroll
+            for (int ot = 0; ot < T2; ++ot)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) h2[ot][r] = fmaxf(h2[ot][r], 0.f);
+        }
+        // 4-output layer: each lane sums over the 16*TL units it holds, the two halves of a token are then added
+        float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int it = 0; it < TL; ++it)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const f32x4 w = *(const f32x4 *)(wfp + ((it * 16 + r) * 2 + hh) * 4);
+                float h;
+                if constexpr (T2 > 0) h = h2[it][r]; else h = h1[it][r];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o[k] = fmaf(h, w[k], o[k]);
+            }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = (o[k] + __shfl_xor(o[k], 32, 64)) + bfp[k];
+        if (live && hh == 0) emit_decision(o, 4, row, A.bits, A.logits);
+    }
+}
+
+template <int T1, int T2> static int launch_mfma(const MlpArgs &A, hipStream_t st)
+{
+    const size_t lds = mfma_lds_floats(T1, T2) * sizeof(float);
+    if (lds > 48 * 1024)
+        KVQ_HIP(hipFuncSetAttribute((const void *)k_mlp_mfma<T1, T2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    const long long ntiles = (A.n + 31) / 32;
+    // persistent: one workgroup per compute unit stages the weights once and walks over the row tiles
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        KVQ_HIP(hipGetDevice(&dev));
+        KVQ_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+        if (n_cu < 1) n_cu = 1;
+    }
+    long long blocks = (ntiles + 3) / 4;
+    if (blocks > n_cu) blocks = n_cu;
+    hipLaunchKernelGGL((k_mlp_mfma<T1, T2>), dim3((unsigned)blocks), dim3(256), lds, st, A, ntiles);
+    return KVQ_OK;
+}
+
+template <int T1> static int launch_mfma_t2(int t2, const MlpArgs &A, hipStream_t st)
+{
+    switch (t2) {
+    case 0: return launch_mfma<T1, 0>(A, st);
+    case 1: return launch_mfma<T1, 1>(A, st);
+    case 2: return launch_mfma<T1, 2>(A, st);
+    default: return launch_mfma<T1, 4>(A, st);
+    }
+}
+
+static bool mfma_width(int w) { return w == 32 || w == 64 || w == 128; }
+
 }  // namespace kvq
 
 using namespace kvq;
@@ -141,6 +292,11 @@ extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp,
     hipStream_t st = (hipStream_t)stream;
     if (n <= 2048) {
         hipLaunchKernelGGL(k_mlp_row, dim3((unsigned)n), dim3(kRowThreads), 0, st, A);
+    } else if (mfma_width(A.dims[1]) && (A.n_linear == 2 || mfma_width(A.dims[2])) && ((uintptr_t)feats & 15) == 0 &&
+               !getenv("KVQ_CONTROLLER_NO_MFMA")) {
+        const int t1 = A.dims[1] / 32, t2 = A.n_linear == 3 ? A.dims[2] / 32 : 0;
+        const int rc = t1 == 1 ? launch_mfma_t2<1>(t2, A, st) : t1 == 2 ? launch_mfma_t2<2>(t2, A, st) : launch_mfma_t2<4>(t2, A, st);
+        if (rc != KVQ_OK) return rc;
     } else {
         const long long blocks = (n + kBulkThreads - 1) / kBulkThreads;
         if (blocks > 0x7fffffffLL) { set_error("n too large for one launch"); return KVQ_ERR_CAPACITY; }

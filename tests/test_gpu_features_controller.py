@@ -172,14 +172,37 @@ def test_controller_ties_zero_weights_and_two_layer_network():
     assert list(bits) == [2, 2, 4, 4, 8, 8, 16, 16]
 
 
-def test_controller_row_and_bulk_launch_shapes_agree_bitwise():
-    say("controller: per-step and bulk launch shapes give identical logits")
+def test_controller_row_and_bulk_launch_shapes_agree():
+    say("controller: per-step, vector-ALU bulk and matrix-core bulk launch shapes")
     cfg = wl.CONFIGS[4]
     Ws, bs = wl.calibrated_mlp(cfg)
     feats = wl.bulk_features(cfg, 5000, chunk=3)
+    # widths 128/128 take the matrix-core shape in bulk: same fp32 products, another summation order
     b_bulk, l_bulk = gpu_controller(feats, Ws, bs)
     b_row, l_row = gpu_controller(feats[:2048], Ws, bs)
+    scale = np.abs(l_row).max() + 1.0
+    np.testing.assert_allclose(l_bulk[:2048], l_row, rtol=0, atol=2e-6 * scale * 8)
+    srt = np.sort(l_row, axis=1)
+    assert not np.any((b_bulk[:2048] != b_row) & (srt[:, -1] - srt[:, -2] > 1e-5))
+    # widths that are no multiple of 32 take the vector-ALU bulk shape: the same FMA chain as the per-step shape
+    rng = np.random.default_rng(12)
+    Wo = [rng.uniform(-0.5, 0.5, s).astype(np.float32) for s in ((48, 4), (40, 48), (4, 40))]
+    bo = [rng.uniform(-0.1, 0.1, s).astype(np.float32) for s in (48, 40, 4)]
+    b_bulk, l_bulk = gpu_controller(feats, Wo, bo)
+    b_row, l_row = gpu_controller(feats[:2048], Wo, bo)
     assert np.array_equal(l_bulk[:2048].view(np.uint32), l_row.view(np.uint32)) and np.array_equal(b_bulk[:2048], b_row)
+    check_controller(feats, Wo, bo)
+
+
+@pytest.mark.parametrize("dims", [(4, 32, 4), (4, 64, 4), (4, 128, 4), (4, 32, 32, 4), (4, 64, 128, 4), (4, 128, 32, 4), (4, 128, 64, 4)])
+@pytest.mark.parametrize("n", [2049, 4097, 33333])
+def test_controller_matrix_core_shape_all_width_combinations(dims, n):
+    say("controller matrix-core shape dims %s n=%d" % (dims, n))
+    rng = np.random.default_rng(sum(dims) + n)
+    Ws = [rng.uniform(-1, 1, (dims[i + 1], dims[i])).astype(np.float32) * np.float32(np.sqrt(3.0 / dims[i])) for i in range(len(dims) - 1)]
+    bs = [rng.uniform(-0.3, 0.3, dims[i + 1]).astype(np.float32) for i in range(len(dims) - 1)]
+    feats = rng.standard_normal((n, 4)).astype(np.float32) * np.array([3.0, 4.0, 1e-3, 0.5], np.float32)
+    check_controller(feats, Ws, bs)
 
 
 def test_end_to_end_step_features_controller_append_attention():
