@@ -171,13 +171,22 @@ def main():
         def step(s, record):
             if record:
                 e0 = torch.cuda.Event(enable_timing=True); e0.record()
-            kvq.kvq_features(step_logits[s % n_steps], step_ids[s % n_steps], counts_d, totals_d, True, step_len[base_step + s], Hq, feats, fws, sum_p2=sum_p2)
-            if record:
-                e1 = torch.cuda.Event(enable_timing=True); e1.record()
-            kvq.kvq_controller(feats, mlp, step_bits.view(-1))
-            if record:
-                e2 = torch.cuda.Event(enable_timing=True); e2.record()
-                stage_ev.append((e0, e1, e2))
+            if fused:
+                # one launch: features, controller and the cache's bucket bookkeeping for the new token
+                kvq.kvq_features_controller(step_logits[s % n_steps], step_ids[s % n_steps], counts_d, totals_d, True, sum_p2,
+                                            step_len[base_step + s], Hq, mlp, feats, step_bits.view(-1),
+                                            cache=cache if fixed is None else None)
+                if record:
+                    e2 = torch.cuda.Event(enable_timing=True); e2.record()
+                    stage_ev.append((e0, e2, e2))
+            else:
+                kvq.kvq_features(step_logits[s % n_steps], step_ids[s % n_steps], counts_d, totals_d, True, step_len[base_step + s], Hq, feats, fws, sum_p2=sum_p2)
+                if record:
+                    e1 = torch.cuda.Event(enable_timing=True); e1.record()
+                kvq.kvq_controller(feats, mlp, step_bits.view(-1))
+                if record:
+                    e2 = torch.cuda.Event(enable_timing=True); e2.record()
+                    stage_ev.append((e0, e1, e2))
             bits_now = step_bits if fixed is None else fixed
             kin, qin = step_k[s % n_in], step_q[s % n_in]
             for l in range(L):
@@ -186,7 +195,9 @@ def main():
                 if record:
                     a0 = torch.cuda.Event(enable_timing=True); a0.record()
                 if fused:
-                    kvq.kvq_append_decode_attn(cache, l, kin[l][0], kin[l][1], bits_now.view(-1) if l == 0 else None, qin[l], None, B,
+                    # layer 0 passes no bits when the front end has already advanced the cache
+                    b0 = bits_now.view(-1) if (l == 0 and fixed is not None) else None
+                    kvq.kvq_append_decode_attn(cache, l, kin[l][0], kin[l][1], b0, qin[l], None, B,
                                                out, aws, None, sum_p2 if l == L - 1 else None)
                 else:
                     kvq.kvq_decode_attn(cache, l, qin[l], None, B, out, aws, None, sum_p2 if l == L - 1 else None)
@@ -227,6 +238,7 @@ def main():
             res["attn_us_min"] = float(np.min(attn_us))
             res["features_us"] = float(np.mean([e0.elapsed_time(e1) * 1e3 for e0, e1, _ in stage_ev]))
             res["controller_us"] = float(np.mean([e1.elapsed_time(e2) * 1e3 for _, e1, e2 in stage_ev]))
+            res["front_us"] = float(np.mean([e0.elapsed_time(e2) * 1e3 for e0, _, e2 in stage_ev]))
             res["attn_GBps"] = abytes / (res["attn_us_per_layer"] * 1e-6) / 1e9
         return cache, res
 
@@ -341,9 +353,11 @@ def main():
         "stages_us": {"features": mixed.get("features_us"), "controller": mixed.get("controller_us"),
                       "attn_per_layer": mixed.get("attn_us_per_layer"), "attn_per_layer_min": mixed.get("attn_us_min")},
         "stream_read_GBps": stream_gbps,
-        "fused_append_attn": None if fused is None else {
+        "fused_path": None if fused is None else {
             "us_per_step": fused["ms_per_step"] * 1e3, "launch_us_per_layer": fused.get("attn_us_per_layer"),
-            "note": "same step with kvq_append_decode_attn (append fused into the attention launch); `value` above is the four-call path"},
+            "front_us": fused.get("front_us"),
+            "note": "same step through kvq_features_controller (features + controller + bookkeeping, one launch) and "
+                    "kvq_append_decode_attn (append + attention, one launch per layer); `value` above is the four-call path"},
         "compare": compare,
     }
     traffic = None

@@ -169,6 +169,24 @@ int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp, uint8_t *b
                    float *logits_out, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Stages 1 + 2 in one launch, for the decode step (Sec. 3.4: saliency profiling, then the controller's decision,
+ * then the token's place in the mixed-precision cache): the features of kvq_features in its sum_p2 form, the
+ * decision of kvq_controller on them, and -- if `cache` is given -- the bucket bookkeeping that
+ * kvq_append(layer 0, T = 1) would do with those decisions.  Results are bit-identical to the separate calls.
+ * One launch (plus the count update when update_counts is set) instead of five.
+ *   logits .. attn_len, n_q_heads   as in kvq_features (sum_p2 is required, there is no attn_probs form)
+ *   mlp, bits_out, logits_out       as in kvq_controller
+ *   cache      NULL, or the cache whose sequences receive one token each: row i belongs to sequence seq_ids[i]
+ *              (i if seq_ids is NULL); the following kvq_append / kvq_append_decode_attn calls of this step then
+ *              pass bits = NULL on layer 0, which means "bookkeeping already done"
+ * ------------------------------------------------------------------------------------------- */
+int kvq_features_controller(const float *logits, int64_t n, int64_t vocab, const int32_t *token_ids,
+                            int64_t *counts, int64_t *totals, int32_t update_counts, const float *sum_p2,
+                            const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp, kvq_cache *cache,
+                            const int32_t *seq_ids, float *feats_out, uint8_t *bits_out, float *logits_out,
+                            void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Stage 3 -- quantize and append (Sec. 3.7: k^ = Q_b(k), v^ = Q_b(v); Sec. 3.2: K <- Concat(K, k)).
  * Q_b for b in {2,4,8}, per (token, kv-head) vector x of 64 fp16 values, every step in IEEE binary32
  * round-to-nearest-even:  levels = 2^b - 1;  scale = fp16((max x - min x) / levels);  the stored
@@ -184,7 +202,8 @@ int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp, uint8_t *b
  * Bookkeeping rule: the bucket slots, page allocation and bit-width log of the T new tokens are
  * shared by all layers and are advanced by the call with layer == 0 (or layer == -1).  Calls with
  * layer >= 1 write the K/V of the tokens appended by the latest layer-0 call on those sequences and
- * must use the same n_seq, T and seq_ids; they ignore `bits`.
+ * must use the same n_seq, T and seq_ids; they ignore `bits`.  A layer-0 (or -1) call with bits == NULL
+ * does no bookkeeping either: it follows a kvq_features_controller call that advanced the cache (T = 1).
  * ------------------------------------------------------------------------------------------- */
 int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const void *v, const uint8_t *bits,
                const int32_t *seq_ids, int32_t n_seq, int32_t T, void *stream);

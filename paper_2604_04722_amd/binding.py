@@ -24,7 +24,7 @@ EXPORT_REC = 128
 EXPORTED_SYMBOLS = (
     "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
     "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_export",
-    "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_append", "kvq_decode_attn_workspace",
+    "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_features_controller", "kvq_append", "kvq_decode_attn_workspace",
     "kvq_decode_attn", "kvq_append_decode_attn", "kvq_probe_read", "kvq_probe_copy",
 )
 
@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_features_workspace.argtypes = [i64, i64]
     lib.kvq_features.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp, sz, vp]
     lib.kvq_controller.argtypes = [vp, i64, ctypes.POINTER(Mlp), vp, vp, vp]
+    lib.kvq_features_controller.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, i32, ctypes.POINTER(Mlp), vp, vp, vp, vp,
+                                            vp, vp]
     lib.kvq_append.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, vp]
     lib.kvq_decode_attn_workspace.restype = sz
     lib.kvq_decode_attn_workspace.argtypes = [vp, i32]
@@ -202,6 +204,21 @@ def kvq_features(logits: torch.Tensor, token_ids: torch.Tensor, counts: torch.Te
         _ptr(attn_probs, torch.float32, "attn_probs"), _ptr(sum_p2, torch.float32, "sum_p2"),
         _ptr(attn_len, torch.int32, "attn_len"), n_q_heads, ld, _ptr(feats_out, torch.float32, "feats_out"),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+def kvq_features_controller(logits: torch.Tensor, token_ids: torch.Tensor, counts: torch.Tensor, totals: torch.Tensor,
+                            update_counts: bool, sum_p2: torch.Tensor, attn_len: torch.Tensor, n_q_heads: int,
+                            mlp: "MlpWeights", feats_out: torch.Tensor, bits_out: torch.Tensor,
+                            cache: Optional["Cache"] = None, seq_ids: Optional[torch.Tensor] = None,
+                            logits_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    n, vocab = logits.shape
+    _check(load_library().kvq_features_controller(
+        _ptr(logits, torch.float32, "logits"), n, vocab, _ptr(token_ids, torch.int32, "token_ids"),
+        _ptr(counts, torch.int64, "counts"), _ptr(totals, torch.int64, "totals"), int(bool(update_counts)),
+        _ptr(sum_p2, torch.float32, "sum_p2"), _ptr(attn_len, torch.int32, "attn_len"), n_q_heads,
+        ctypes.byref(mlp.c), cache.handle if cache is not None else None, _ptr(seq_ids, torch.int32, "seq_ids"),
+        _ptr(feats_out, torch.float32, "feats_out"), _ptr(bits_out, torch.uint8, "bits_out"),
+        _ptr(logits_out, torch.float32, "logits_out"), _stream(stream)))
 
 
 class MlpWeights:

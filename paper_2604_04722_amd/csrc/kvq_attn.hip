@@ -907,9 +907,8 @@ extern "C" int kvq_append_decode_attn(kvq_cache *cache, int32_t layer, const voi
     const kvq_cache_desc &d = cache->desc;
     if (layer < 0 || layer >= d.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
     if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
-    if (layer == 0 && !bits) { set_error("bits is NULL on the bookkeeping call (layer 0)"); return KVQ_ERR_INVALID_ARG; }
     if (n_seq == 0) return KVQ_OK;
-    if (layer == 0) {
+    if (layer == 0 && bits) {                                     // bits == NULL: done by kvq_features_controller
         const int rc = kvq_append_bookkeeping(cache, bits, seq_ids, n_seq, 1, stream);
         if (rc != KVQ_OK) return rc;
     }

@@ -596,8 +596,7 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
     if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
     if (T < 0) { set_error("T negative"); return KVQ_ERR_INVALID_ARG; }
     if ((int64_t)T > d.max_context) { set_error("T %d exceeds max_context", T); return KVQ_ERR_CAPACITY; }
-    const bool bookkeeping = layer <= 0;
-    if (bookkeeping && !bits) { set_error("bits is NULL on the bookkeeping call (layer 0 or -1)"); return KVQ_ERR_INVALID_ARG; }
+    const bool bookkeeping = layer <= 0 && bits != nullptr;       // bits == NULL: done by kvq_features_controller
     if (n_seq == 0 || T == 0) return KVQ_OK;
     const long long nl = layer < 0 ? d.n_layers : 1;
     const long long total = nl * n_seq * (long long)T * d.n_kv_heads;

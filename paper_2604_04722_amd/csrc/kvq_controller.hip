@@ -2,7 +2,8 @@
 // class = argmax_k o_k, bits = {2,4,8,16}[class] (label mapping of Algorithm 1).
 //
 // Three launch shapes:
-//   - per-step shape (few rows): one workgroup per row, thread = output unit, activations in LDS;
+//   - per-step shape (few rows): one workgroup per row, thread = output unit, weights staged in LDS by contiguous
+//     reads that share one memory latency, activations in LDS;
 //   - bulk shape on the matrix cores (cache construction, thousands to millions of rows; hidden widths 32, 64 or
 //     128): a wavefront takes 32 rows, the hidden layers are fp32 MFMA 32x32x2 tiles whose accumulators feed the
 //     next layer's B operand directly, the 4-output layer is a short vector dot product;
@@ -10,54 +11,24 @@
 // The first and the last compute bit-identical logits (each output is the same sequential fp32 FMA chain
 // bias + sum_i W[j][i]*h[i], i ascending); the MFMA shape sums the same fp32 products in another order.
 #include "kvq_internal.h"
+#include "kvq_mlp.h"
 
 #include <cstdlib>
 
 namespace kvq {
 
-constexpr int kMaxWidth = 256;
-constexpr int kRowThreads = 256;     // per-step shape
-constexpr int kBulkThreads = 64;     // bulk shape: rows per workgroup
+constexpr int kBulkThreads = 64;     // vector-ALU bulk shape: rows per workgroup
 
-struct MlpArgs {
-    const float *feats;
-    const float *W[4];
-    const float *b[4];
-    uint8_t *bits;
-    float *logits;
-    long long n;
-    int n_linear;
-    int dims[5];
-};
-
-__device__ __forceinline__ void emit_decision(const float *o, int nout, long long row, uint8_t *bits, float *logits)
+__global__ __launch_bounds__(kRowThreads) void k_mlp_row(MlpArgs A, int staged)
 {
-    int best = 0;
-    for (int k = 1; k < nout; ++k) if (o[k] > o[best]) best = k;     // strict: the first maximum wins
-    bits[row] = (uint8_t)(2 << best);                                // 2, 4, 8, 16
-    if (logits) for (int k = 0; k < 4; ++k) logits[row * 4 + k] = k < nout ? o[k] : -INFINITY;
-}
-
-__global__ __launch_bounds__(kRowThreads) void k_mlp_row(MlpArgs A)
-{
+    extern __shared__ float stage[];               // all weights, when they fit
     __shared__ float act[2][kMaxWidth];
     const long long row = blockIdx.x;
     const int tid = threadIdx.x;
+    if (staged) mlp_stage_weights(A, stage, tid, kRowThreads);
     if (tid < A.dims[0]) act[0][tid] = A.feats[row * A.dims[0] + tid];
     __syncthreads();
-    int cur = 0;
-    for (int l = 0; l < A.n_linear; ++l) {
-        const int in = A.dims[l], outw = A.dims[l + 1];
-        if (tid < outw) {
-            const float *w = A.W[l] + (size_t)tid * in;
-            float a = A.b[l][tid];
-            for (int i = 0; i < in; ++i) a = fmaf(w[i], act[cur][i], a);
-            if (l + 1 < A.n_linear) a = fmaxf(a, 0.f);
-            act[cur ^ 1][tid] = a;
-        }
-        __syncthreads();
-        cur ^= 1;
-    }
+    const int cur = mlp_row_forward(A, act, tid, staged ? stage : nullptr);
     if (tid == 0) emit_decision(act[cur], A.dims[A.n_linear], row, A.bits, A.logits);
 }
 
@@ -258,10 +229,9 @@ static bool mfma_width(int w) { return w == 32 || w == 64 || w == 128; }
 
 using namespace kvq;
 
-extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp, uint8_t *bits_out,
-                              float *logits_out, void *stream)
+// validates the network description and copies it into kernel arguments (feats, bits, logits and n are left to the caller)
+int kvq::mlp_args_from(const kvq_mlp *mlp, MlpArgs *out, int *max_width)
 {
-    if (n < 0) { set_error("n negative"); return KVQ_ERR_INVALID_ARG; }
     if (!mlp) { set_error("mlp is NULL"); return KVQ_ERR_INVALID_ARG; }
     if (mlp->n_linear < 2 || mlp->n_linear > 3) { set_error("n_linear must be 2 or 3"); return KVQ_ERR_UNSUPPORTED; }
     if (mlp->dims[0] != 4) { set_error("dims[0] must be 4 (the feature vector)"); return KVQ_ERR_INVALID_ARG; }
@@ -276,22 +246,43 @@ extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp,
     }
     for (int l = 0; l < mlp->n_linear; ++l)
         if (!mlp->W[l] || !mlp->b[l]) { set_error("W[%d] or b[%d] is NULL", l, l); return KVQ_ERR_INVALID_ARG; }
-    if (n == 0) return KVQ_OK;
-    if (!feats || !bits_out) { set_error("feats or bits_out is NULL"); return KVQ_ERR_INVALID_ARG; }
-    MlpArgs A;
-    A.feats = feats;
-    A.bits = bits_out;
-    A.logits = logits_out;
-    A.n = n;
+    MlpArgs &A = *out;
+    A.feats = nullptr;
+    A.bits = nullptr;
+    A.logits = nullptr;
+    A.n = 0;
     A.n_linear = mlp->n_linear;
     for (int l = 0; l < 5; ++l) A.dims[l] = l <= mlp->n_linear ? mlp->dims[l] : 0;
     for (int l = 0; l < 4; ++l) {
         A.W[l] = l < mlp->n_linear ? mlp->W[l] : nullptr;
         A.b[l] = l < mlp->n_linear ? mlp->b[l] : nullptr;
     }
+    if (max_width) *max_width = maxw;
+    return KVQ_OK;
+}
+
+extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp, uint8_t *bits_out,
+                              float *logits_out, void *stream)
+{
+    if (n < 0) { set_error("n negative"); return KVQ_ERR_INVALID_ARG; }
+    MlpArgs A;
+    int maxw = 4;
+    const int rc0 = mlp_args_from(mlp, &A, &maxw);
+    if (rc0 != KVQ_OK) return rc0;
+    if (n == 0) return KVQ_OK;
+    if (!feats || !bits_out) { set_error("feats or bits_out is NULL"); return KVQ_ERR_INVALID_ARG; }
+    A.feats = feats;
+    A.bits = bits_out;
+    A.logits = logits_out;
+    A.n = n;
     hipStream_t st = (hipStream_t)stream;
     if (n <= 2048) {
-        hipLaunchKernelGGL(k_mlp_row, dim3((unsigned)n), dim3(kRowThreads), 0, st, A);
+        const int stage_floats = mlp_stage_floats(A);
+        const int staged = stage_floats <= kMlpStageMaxFloats;
+        const size_t lds = staged ? (size_t)stage_floats * sizeof(float) : 0;
+        if (lds > 48 * 1024)
+            KVQ_HIP(hipFuncSetAttribute((const void *)k_mlp_row, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(k_mlp_row, dim3((unsigned)n), dim3(kRowThreads), lds, st, A, staged);
     } else if (mfma_width(A.dims[1]) && (A.n_linear == 2 || mfma_width(A.dims[2])) && ((uintptr_t)feats & 15) == 0 &&
                !getenv("KVQ_CONTROLLER_NO_MFMA")) {
         const int t1 = A.dims[1] / 32, t2 = A.n_linear == 3 ? A.dims[2] / 32 : 0;

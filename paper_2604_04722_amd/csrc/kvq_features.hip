@@ -6,6 +6,7 @@
 // (m, S, T) triple, triples are merged exactly (rescaling by exp(m_a - m_b)), slice results go to a
 // small workspace and a second kernel merges them and adds R_t and V_t.
 #include "kvq_internal.h"
+#include "kvq_mlp.h"
 
 namespace kvq {
 
@@ -14,6 +15,11 @@ constexpr int kMaxSlices = 64;
 
 struct Lse3 { float m, s, t; };
 
+// e^d for d <= 0 through the hardware 2^x: relative error below 2e-6 over the range that still contributes to a
+// sum (d > -20), which is a tenth of the tolerance of the features; the library routine costs ten times the issue
+// slots, and one compute unit takes a whole row of 49 152 logits in the fused kernel.
+__device__ __forceinline__ float exp_neg(float d) { return __builtin_amdgcn_exp2f(d * 1.44269504088896340736f); }
+
 // merge b into a:  both are (max, sum e^{z-max}, sum (z-max) e^{z-max}) of disjoint sets
 __device__ __forceinline__ Lse3 lse3_merge(Lse3 a, Lse3 b)
 {
@@ -21,7 +27,7 @@ __device__ __forceinline__ Lse3 lse3_merge(Lse3 a, Lse3 b)
     if (a.m == -INFINITY) return b;
     const float M = fmaxf(a.m, b.m);
     const float da = a.m - M, db = b.m - M;              // <= 0
-    const float fa = expf(da), fb = expf(db);
+    const float fa = exp_neg(da), fb = exp_neg(db);
     Lse3 r;
     r.m = M;
     r.s = a.s * fa + b.s * fb;
@@ -35,14 +41,14 @@ __device__ __forceinline__ void lse3_add4(Lse3 &a, float z0, float z1, float z2,
     if (m4 > a.m) {
         if (a.m != -INFINITY) {
             const float d = a.m - m4;
-            const float f = expf(d);
+            const float f = exp_neg(d);
             a.t = f * (a.t + d * a.s);
             a.s *= f;
         }
         a.m = m4;
     }
     const float d0 = z0 - a.m, d1 = z1 - a.m, d2 = z2 - a.m, d3 = z3 - a.m;
-    const float e0 = expf(d0), e1 = expf(d1), e2 = expf(d2), e3 = expf(d3);
+    const float e0 = exp_neg(d0), e1 = exp_neg(d1), e2 = exp_neg(d2), e3 = exp_neg(d3);
     a.s += (e0 + e1) + (e2 + e3);
     a.t += (d0 * e0 + d1 * e1) + (d2 * e2 + d3 * e3);
 }
@@ -52,22 +58,21 @@ __device__ __forceinline__ void lse3_add1(Lse3 &a, float z)
     if (z > a.m) {
         if (a.m != -INFINITY) {
             const float d = a.m - z;
-            const float f = expf(d);
+            const float f = exp_neg(d);
             a.t = f * (a.t + d * a.s);
             a.s *= f;
         }
         a.m = z;
     }
     const float d = z - a.m;
-    const float e = expf(d);
+    const float e = exp_neg(d);
     a.s += e;
     a.t = fmaf(d, e, a.t);
 }
 
-__global__ __launch_bounds__(kFeatThreads) void k_lse_partial(const float *logits, long long vocab, int slices, float *ws)
+// (m, S, T) of the part of one slice of a logits row that thread `lt` of kFeatThreads takes
+__device__ __forceinline__ Lse3 thread_partial(const float *logits, long long vocab, int slices, long long row, int slice, int lt)
 {
-    const long long row = blockIdx.y;
-    const int slice = blockIdx.x;
     const float *z = logits + row * vocab;
     const long long per = (vocab + slices - 1) / slices;
     long long lo = per * slice, hi = lo + per;
@@ -79,29 +84,99 @@ __global__ __launch_bounds__(kFeatThreads) void k_lse_partial(const float *logit
         // peel to a 16-byte boundary
         long long head = ((16 - ((uintptr_t)p & 15)) & 15) / 4;
         if (head > n) head = n;
-        if ((long long)threadIdx.x < head) lse3_add1(a, p[threadIdx.x]);
+        if ((long long)lt < head) lse3_add1(a, p[lt]);
         p += head;
         n -= head;
         const long long n4 = n / 4;
         const float4 *p4 = (const float4 *)p;
-        for (long long i = threadIdx.x; i < n4; i += kFeatThreads) {
-            const float4 v = p4[i];
-            lse3_add4(a, v.x, v.y, v.z, v.w);
+        // four loads in flight per thread; the quadruples are added in ascending order
+        for (long long i = lt; i < n4; i += 4 * kFeatThreads) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const long long k = i + u * kFeatThreads;
+                v[u] = p4[k < n4 ? k : i];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i + u * kFeatThreads < n4) lse3_add4(a, v[u].x, v[u].y, v[u].z, v[u].w);
         }
         const long long tail = n - n4 * 4;
-        if ((long long)threadIdx.x < tail) lse3_add1(a, p[n4 * 4 + threadIdx.x]);
+        if ((long long)lt < tail) lse3_add1(a, p[n4 * 4 + lt]);
     }
-    __shared__ Lse3 sm[kFeatThreads];
-    sm[threadIdx.x] = a;
+    return a;
+}
+
+// tree merge of kFeatThreads triples sm[0..kFeatThreads) (thread lt owns sm[lt]); the result is sm[0].  Every
+// thread of the workgroup calls it, also in workgroups made of several such groups (sm then is the group's part).
+__device__ __forceinline__ void group_merge(Lse3 *sm, int lt)
+{
     __syncthreads();
-    for (int o = kFeatThreads / 2; o >= 1; o >>= 1) {
-        if ((int)threadIdx.x < o) sm[threadIdx.x] = lse3_merge(sm[threadIdx.x], sm[threadIdx.x + o]);
+    for (int o = kFeatThreads / 2; o >= 64; o >>= 1) {
+        if (lt < o) sm[lt] = lse3_merge(sm[lt], sm[lt + o]);
         __syncthreads();
     }
+    // the last levels stay inside the group's first wavefront: the same pairs (lt, lt + o), passed by lane shuffles
+    if (lt < 64) {
+        Lse3 a = sm[lt];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) {
+            Lse3 b;
+            b.m = __shfl_down(a.m, o, 64);
+            b.s = __shfl_down(a.s, o, 64);
+            b.t = __shfl_down(a.t, o, 64);
+            a = lse3_merge(a, b);
+        }
+        if (lt == 0) sm[0] = a;
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kFeatThreads) void k_lse_partial(const float *logits, long long vocab, int slices, float *ws)
+{
+    __shared__ Lse3 sm[kFeatThreads];
+    const long long row = blockIdx.y;
+    const int slice = blockIdx.x;
+    sm[threadIdx.x] = thread_partial(logits, vocab, slices, row, slice, threadIdx.x);
+    group_merge(sm, threadIdx.x);
     if (threadIdx.x == 0) {
         float *w = ws + (row * slices + slice) * 4;
         w[0] = sm[0].m; w[1] = sm[0].s; w[2] = sm[0].t;
     }
+}
+
+__device__ __forceinline__ float entropy_of(const Lse3 &a) { return logf(a.s) - a.t / a.s; }
+__device__ __forceinline__ float confidence_of(const Lse3 &a) { return 1.0f / a.s; }
+__device__ __forceinline__ float rarity_from(long long c, long long seen)
+{
+    // one fp64 logarithm per token: the ratio is close to 1 for common tokens
+    return (float)(-log((double)(c + 1) / (double)(seen + 1)));
+}
+__device__ __forceinline__ float rarity_of(long long id, long long vocab, const long long *counts, const long long *totals)
+{
+    const long long c = (id >= 0 && id < vocab) ? counts[id] : 0;        // an id outside the table counts as unseen
+    return rarity_from(c, totals[0] + totals[1]);
+}
+
+// mean over the heads of the closed form of the population variance of a probability row: sum p^2 / l - 1 / l^2.
+// Every thread of the workgroup calls it; the threads with `active` (kFeatThreads of them, numbered lt) do the
+// work; the value is returned to every thread.
+__device__ __forceinline__ float variance_from_sum_p2(const float *sum_p2_row, int Hq, int l, float *red, int lt, bool active)
+{
+    const float inv_l = 1.0f / (float)l;
+    if (active) {
+        float s = 0.f;
+        for (int h = lt; h < Hq; h += kFeatThreads) s += sum_p2_row[h] * inv_l - inv_l * inv_l;
+        red[lt] = s;
+    }
+    __syncthreads();
+    for (int o = kFeatThreads / 2; o >= 1; o >>= 1) {
+        if (active && lt < o) red[lt] += red[lt + o];
+        __syncthreads();
+    }
+    const float V = red[0] / (float)Hq;
+    __syncthreads();
+    return V;
 }
 
 struct FeatArgs {
@@ -153,15 +228,7 @@ __global__ __launch_bounds__(kFeatThreads) void k_features_finalize(FeatArgs A)
         }
         V /= (float)A.Hq;
     } else {
-        float s = 0.f;
-        for (int h = threadIdx.x; h < A.Hq; h += kFeatThreads) s += A.sum_p2[t * A.Hq + h] * inv_l - inv_l * inv_l;
-        red[threadIdx.x] = s;
-        __syncthreads();
-        for (int o = kFeatThreads / 2; o >= 1; o >>= 1) {
-            if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
-            __syncthreads();
-        }
-        V = red[0] / (float)A.Hq;
+        V = variance_from_sum_p2(A.sum_p2 + t * A.Hq, A.Hq, l, red, threadIdx.x, true);
     }
     if (threadIdx.x != 0) return;
     Lse3 a = {-INFINITY, 0.f, 0.f};
@@ -170,14 +237,96 @@ __global__ __launch_bounds__(kFeatThreads) void k_features_finalize(FeatArgs A)
         Lse3 b = {w[0], w[1], w[2]};
         a = lse3_merge(a, b);
     }
-    const float H = logf(a.s) - a.t / a.s;
-    const float C = 1.0f / a.s;
-    const long long id = A.token_ids[t];
-    const long long c = (id >= 0 && id < A.vocab) ? A.counts[id] : 0;    // an id outside the table counts as unseen
-    // one fp64 logarithm per token: the ratio is close to 1 for common tokens
-    const float R = (float)(-log((double)(c + 1) / (double)(A.totals[0] + A.totals[1] + 1)));
     float *f = A.feats + t * 4;
-    f[0] = H; f[1] = R; f[2] = V; f[3] = C;
+    f[0] = entropy_of(a);
+    f[1] = rarity_of(A.token_ids[t], A.vocab, A.counts, A.totals);
+    f[2] = V;
+    f[3] = confidence_of(a);
+}
+
+// ---- fused per-step front end: features, controller and bucket bookkeeping in one launch --------------------
+//
+// One workgroup of four groups of kFeatThreads threads per row.  The groups take the row's slices in turn and
+// reduce each exactly as k_lse_partial does, thread 0 merges the slice triples in slice order as
+// k_features_finalize does, and the controller's row shape follows, so features and logits equal those of the
+// separate kernels bit for bit.  A row never needs another row's result; the count update stays a kernel of its
+// own behind this one, which keeps "every row reads the table before any count changes" a matter of stream order.
+constexpr int kFrontGroups = 4;
+
+struct FrontArgs {
+    const float *logits;
+    const int32_t *token_ids;
+    const long long *counts;
+    const long long *totals;
+    const float *sum_p2;
+    const int32_t *attn_len;
+    const int32_t *seq_ids;
+    float *feats;
+    long long vocab;
+    int slices, Hq, advance;
+};
+
+__global__ __launch_bounds__(kFrontGroups * kFeatThreads) void k_front(FrontArgs F, MlpArgs M, CacheView cv, int staged)
+{
+    extern __shared__ float stage[];               // the controller's weights, fetched while the logits stream in
+    __shared__ Lse3 sm[kFrontGroups * kFeatThreads];
+    __shared__ Lse3 slice_res[kMaxSlices];
+    __shared__ float act[2][kMaxWidth];
+    const long long row = blockIdx.x;
+    const int tid = threadIdx.x, g = tid / kFeatThreads, lt = tid % kFeatThreads;
+    // thread 0 fetches what the row's serial tail needs (the token's count, the totals, the sequence's counters) now,
+    // so that these dependent reads overlap the pass over the logits
+    long long tok_count = 0, seen = 0;
+    int seq = 0, pre[5] = {0, 0, 0, 0, 0};
+    if (tid == 0) {
+        const long long id = F.token_ids[row];
+        tok_count = (id >= 0 && id < F.vocab) ? F.counts[id] : 0;
+        seen = F.totals[0] + F.totals[1];
+        if (F.advance) {
+            seq = F.seq_ids ? F.seq_ids[row] : (int)row;
+            if (seq >= 0 && seq < cv.max_seqs) {
+#pragma unroll
+                for (int c = 0; c < 5; ++c) pre[c] = cv.counts[(size_t)seq * 5 + c];
+            }
+        }
+    }
+    if (staged) mlp_stage_weights(M, stage, tid, kFrontGroups * kFeatThreads);
+    // four rounds of slices at a time: their loads are issued together, their reductions follow one by one
+    constexpr int kRounds = 4;
+    for (int s0 = 0; s0 < F.slices; s0 += kFrontGroups * kRounds) {
+        Lse3 part[kRounds];
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const int slice = s0 + r * kFrontGroups + g;
+            part[r].m = -INFINITY; part[r].s = 0.f; part[r].t = 0.f;
+            if (slice < F.slices) part[r] = thread_partial(F.logits, F.vocab, F.slices, row, slice, lt);
+        }
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const int slice = s0 + r * kFrontGroups + g;
+            if (s0 + r * kFrontGroups >= F.slices) break;           // uniform over the workgroup
+            sm[tid] = part[r];
+            group_merge(sm + g * kFeatThreads, lt);
+            if (lt == 0 && slice < F.slices) slice_res[slice] = sm[tid];
+        }
+    }
+    const float V = variance_from_sum_p2(F.sum_p2 + row * F.Hq, F.Hq, F.attn_len[row], (float *)sm, lt, g == 0);
+    if (tid == 0) {
+        Lse3 a = {-INFINITY, 0.f, 0.f};
+        for (int s = 0; s < F.slices; ++s) a = lse3_merge(a, slice_res[s]);
+        act[0][0] = entropy_of(a);
+        act[0][1] = rarity_from(tok_count, seen);
+        act[0][2] = V;
+        act[0][3] = confidence_of(a);
+        float *f = F.feats + row * 4;
+        f[0] = act[0][0]; f[1] = act[0][1]; f[2] = act[0][2]; f[3] = act[0][3];
+    }
+    __syncthreads();
+    const int cur = mlp_row_forward(M, act, tid, staged ? stage : nullptr);
+    if (tid == 0) {
+        const int b = emit_decision(act[cur], 4, row, M.bits, M.logits);
+        if (F.advance) advance_one_token(cv, seq, b, pre);
+    }
 }
 
 // counting pass that follows scoring: c[id] += 1 for every token, |V_obs| += ids seen for the first time
@@ -254,6 +403,63 @@ extern "C" int kvq_features(const float *logits, int64_t n, int64_t vocab, const
     A.slices = slices;
     A.Hq = n_q_heads;
     hipLaunchKernelGGL(k_features_finalize, dim3((unsigned)n), dim3(kFeatThreads), 0, st, A);
+    KVQ_HIP(hipGetLastError());
+    if (update_counts) {
+        hipLaunchKernelGGL(k_counts_update, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, token_ids, (long long)n,
+                           (long long)vocab, (unsigned long long *)counts, (unsigned long long *)totals);
+        KVQ_HIP(hipGetLastError());
+    }
+    return KVQ_OK;
+}
+
+extern "C" int kvq_features_controller(const float *logits, int64_t n, int64_t vocab, const int32_t *token_ids,
+                                       int64_t *counts, int64_t *totals, int32_t update_counts, const float *sum_p2,
+                                       const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp, kvq_cache *cache,
+                                       const int32_t *seq_ids, float *feats_out, uint8_t *bits_out, float *logits_out,
+                                       void *stream)
+{
+    if (n < 0 || vocab < 1) { set_error("n or vocab out of range"); return KVQ_ERR_INVALID_ARG; }
+    MlpArgs M;
+    const int rc0 = mlp_args_from(mlp, &M, nullptr);
+    if (rc0 != KVQ_OK) return rc0;
+    if (n == 0) return KVQ_OK;
+    if (!logits || !token_ids || !counts || !totals || !sum_p2 || !attn_len || !feats_out || !bits_out) {
+        set_error("NULL argument");
+        return KVQ_ERR_INVALID_ARG;
+    }
+    if (n_q_heads < 1) { set_error("n_q_heads must be positive"); return KVQ_ERR_INVALID_ARG; }
+    if (n > 65535) { set_error("n above 65535 rows per call is not supported"); return KVQ_ERR_UNSUPPORTED; }
+    if (cache && n > cache->desc.max_seqs) { set_error("n %lld exceeds the cache's max_seqs", (long long)n); return KVQ_ERR_INVALID_ARG; }
+    FrontArgs F;
+    F.logits = logits;
+    F.token_ids = token_ids;
+    F.counts = (const long long *)counts;
+    F.totals = (const long long *)totals;
+    F.sum_p2 = sum_p2;
+    F.attn_len = attn_len;
+    F.seq_ids = seq_ids;
+    F.feats = feats_out;
+    F.vocab = vocab;
+    F.slices = pick_slices(n, vocab);                             // the slicing of kvq_features: same rounding, same values
+    F.Hq = n_q_heads;
+    F.advance = cache ? 1 : 0;
+    M.feats = feats_out;
+    M.bits = bits_out;
+    M.logits = logits_out;
+    M.n = n;
+    CacheView cv = {};
+    if (cache) {
+        cv = cache->view;
+        cache->len_bound += 1;
+        if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const int stage_floats = mlp_stage_floats(M);
+    const int staged = stage_floats <= kMlpStageMaxFloats;
+    const size_t lds = staged ? (size_t)stage_floats * sizeof(float) : 0;
+    if (lds > 48 * 1024)
+        KVQ_HIP(hipFuncSetAttribute((const void *)k_front, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(k_front, dim3((unsigned)n), dim3(kFrontGroups * kFeatThreads), lds, st, F, M, cv, staged);
     KVQ_HIP(hipGetLastError());
     if (update_counts) {
         hipLaunchKernelGGL(k_counts_update, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, token_ids, (long long)n,

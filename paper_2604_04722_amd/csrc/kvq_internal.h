@@ -95,4 +95,41 @@ __device__ __forceinline__ size_t block_offset(const CacheView &cv, int cls, int
            (((size_t)page * cv.Hkv + kvh) * cv.blocks_per_page + blk_in_page) * (size_t)class_block_bytes(cls);
 }
 
+// Bucket bookkeeping of ONE new token of `seq` by a single thread: the same state changes as the bookkeeping
+// kernel makes for T = 1 (slot = the class's count, a page popped from the class's free stack when the slot opens
+// a page, bits and slot logged, counts advanced, flags raised on a full context, an empty pool or a bad width).
+// `pre` holds the sequence's five counters as read earlier by the same thread (so that the reads overlap other work).
+__device__ __forceinline__ void advance_one_token(const CacheView &cv, int seq, int b, const int (&pre)[5])
+{
+    if (seq < 0 || seq >= cv.max_seqs) { atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL); return; }
+    int32_t *cnt = cv.counts + (size_t)seq * 5;
+    const int len = pre[4];
+    if ((int64_t)len + 1 > (int64_t)cv.max_context) {
+        atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL);
+        cv.last_T[seq] = 0;
+        return;
+    }
+    if (b != 2 && b != 4 && b != 8 && b != 16) { atomicOr(cv.flags, KVQ_FLAG_BAD_BITS); b = 16; }
+    const int c = bits_to_class(b);
+    const int slot = c == 0 ? pre[0] : c == 1 ? pre[1] : c == 2 ? pre[2] : pre[3];
+    if (slot % cv.page_tokens == 0) {
+        int page;
+        const int idx = atomicSub(&cv.free_top[c], 1) - 1;
+        if (idx < 0) {
+            atomicAdd(&cv.free_top[c], 1);
+            atomicOr(cv.flags, KVQ_FLAG_POOL_EXHAUSTED);
+            page = cv.n_pages[c];                                      // sink page: in bounds, shared, garbage
+        } else {
+            page = cv.free_stack[c][idx];
+        }
+        cv.page_table[((size_t)seq * kClasses + c) * cv.max_pages_per_seq + slot / cv.page_tokens] = page;
+    }
+    const size_t pos = (size_t)seq * cv.max_context + len;
+    cv.bits_log[pos] = (uint8_t)b;
+    cv.slot_log[pos] = slot;
+    cnt[c] = slot + 1;
+    cnt[4] = len + 1;
+    cv.last_T[seq] = 1;
+}
+
 }  // namespace kvq

@@ -279,8 +279,7 @@ def test_host_side_argument_checks_change_nothing():
     bits = torch.full((2, 1), 4, dtype=torch.uint8, device=dev())
     with pytest.raises(kvq.KvqError):
         kvq.kvq_append(cache, 2, K, K, bits, None, 2, 1)          # layer out of range
-    with pytest.raises(kvq.KvqError):
-        kvq.kvq_append(cache, 0, K, K, None, None, 2, 1)          # bookkeeping call without bits
+    kvq.kvq_append(cache, 0, K, K, None, None, 2, 1)              # no bits: no bookkeeping, and nothing pending to write
     with pytest.raises(kvq.KvqError):
         kvq.kvq_append(cache, 0, K, K, bits, None, 3, 1)          # more sequences than slots
     with pytest.raises(kvq.KvqError):
