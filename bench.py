@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-events", action="store_true", help="do not bracket attention launches with events")
     ap.add_argument("--no-fused", action="store_true", help="skip the second timed loop that uses kvq_append_decode_attn")
+    ap.add_argument("--no-graph", action="store_true", help="skip the third timed loop that replays the fused step as a HIP graph")
     ap.add_argument("--trace-steps", action="store_true", help="log the mean attention time per layer of every timed step")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences of one layer the CPU oracle is timed on (0 = the whole batch)")
     return ap.parse_args()
@@ -68,7 +69,7 @@ def main():
     B, Hq, Hkv = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads
     n_steps = args.warmup + args.steps
     lens0 = wl.ragged_lengths(cfg).astype(np.int64) - 1          # prefill so that the first step reaches the context
-    max_ctx = int(cfg.context + 2 * n_steps + 16)
+    max_ctx = int(cfg.context + 3 * n_steps + 16)                  # three timed loops may run on the mixed cache
 
     # ---------------- controller + per-token precisions of the prefill -----------------------------
     if cfg.bits_kind == "controller":
@@ -102,7 +103,7 @@ def main():
         for w in (2, 4, 8, 16):
             need = 0
             for s in range(B):
-                need += math.ceil(((bits[s, :lens0[s]] == w).sum() + 2 * n_steps + 16) / 256) + 1
+                need += math.ceil(((bits[s, :lens0[s]] == w).sum() + 3 * n_steps + 16) / 256) + 1
             pools.append(int(need))
         cache = kvq.Cache(L, B, Hq, Hkv, max_ctx, pool_pages=pools)
         CH = 512
@@ -139,7 +140,7 @@ def main():
     counts_np, N, Vobs, probs_tab = wl.zipf_table(cfg)
     step_logits = [wl.logits(cfg, s, B, dev) for s in range(n_steps)]
     step_ids = [torch.from_numpy(wl.zipf_ids(cfg, probs_tab, s, B)).to(dev) for s in range(n_steps)]
-    step_len = [torch.from_numpy((lens0 + s).astype(np.int32)).to(dev) for s in range(2 * n_steps + 16)]
+    step_len = [torch.from_numpy((lens0 + s).astype(np.int32)).to(dev) for s in range(3 * n_steps + 16)]
     done_steps = {}                                          # cache id -> decode steps already run on it
     n_in = min(n_steps, 4)                                   # K/V/q of the new token: a few distinct sets, cycled
     step_k = [[wl.kv_chunk_fast(cfg, l, 5000 + s, B, 1, dev) for l in range(L)] for s in range(n_in)]
@@ -156,7 +157,7 @@ def main():
         kv = sum(n * Hkv * wl.BYTES_PER_TOKEN_HEAD[w] for n, w in zip(per_class, (2, 4, 8, 16)))
         return kv + B * Hq * 64 * (2 + 4), per_class
 
-    def run_variant(variant, timed_steps, warm_steps, events, fused=False, cache=None):
+    def run_variant(variant, timed_steps, warm_steps, events, fused=False, cache=None, graph=False):
         cache = cache or build_cache(variant)
         aws = torch.empty(kvq.kvq_decode_attn_workspace(cache, B), dtype=torch.uint8, device=dev)
         counts_d = torch.from_numpy(counts_np).to(dev)
@@ -166,7 +167,7 @@ def main():
             fixed = torch.full((B, 1), 4 if variant == "static4" else 16, dtype=torch.uint8, device=dev)
         ev_pairs, stage_ev = [], []
         base_step = done_steps.get(id(cache), 0)
-        done_steps[id(cache)] = base_step + warm_steps + timed_steps
+        done_steps[id(cache)] = base_step + warm_steps + timed_steps + (1 if graph else 0)
 
         def step(s, record):
             if record:
@@ -211,11 +212,25 @@ def main():
         c_before = cache.counts()
         # a collector pause on the host drains the launch queue and shows up as device idle time inside the event
         # brackets, so the cyclic collector is off while the steps are timed
+        replay = None
+        if graph:
+            # one decode step captured as a HIP graph (kernel launches only) and replayed: the same input buffers every
+            # time, one more token per sequence and layer each replay
+            events = False
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(warm_steps, False)
+            replay = g.replay
+            torch.cuda.synchronize()
+            c_before = cache.counts()
         gc.collect()
         gc.disable()
         t0 = time.perf_counter()
         for s in range(warm_steps, warm_steps + timed_steps):
-            step(s, events)
+            if replay is not None:
+                replay()
+            else:
+                step(s, events)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         gc.enable()
@@ -249,6 +264,9 @@ def main():
     fused = None
     if not args.no_fused:
         _, fused = run_variant("mixed", args.steps, args.warmup, not args.no_events, fused=True, cache=cache)
+    graph_res = None
+    if not args.no_fused and not args.no_graph:
+        _, graph_res = run_variant("mixed", args.steps, args.warmup, False, fused=True, cache=cache, graph=True)
 
     # measured streaming-read rate of a trivial kernel on this device (context for the 8 TB/s nominal peak)
     probe = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
@@ -358,6 +376,9 @@ def main():
             "front_us": fused.get("front_us"),
             "note": "same step through kvq_features_controller (features + controller + bookkeeping, one launch) and "
                     "kvq_append_decode_attn (append + attention, one launch per layer); `value` above is the four-call path"},
+        "graph_replay": None if graph_res is None else {
+            "us_per_step": graph_res["ms_per_step"] * 1e3,
+            "note": "the fused path's step captured once as a HIP graph and replayed (launch overhead off the host)"},
         "compare": compare,
     }
     traffic = None
