@@ -831,13 +831,17 @@ static int launch_attn(const kvq_cache *cache, int32_t layer, const void *q, con
 {
     const kvq_cache_desc &d = cache->desc;
     const long long heads = (long long)n_seq * d.n_q_heads;
-    // Split heuristic: a workgroup should keep ~16 or more units (10-16 KiB each) so that its per-class
-    // pipelines reach steady state; within that limit, aim at three or more workgroups per CU (768).
-    // len_bound is an upper bound of the longest sequence.
+    // Work distribution: two waves fit a SIMD, 2048 on the chip, and a launch whose waves are all resident at once has
+    // no second, under-filled round.  So a (sequence, query head) gets about 2048 / heads waves, but no more than one
+    // per four units (10-16 KiB each), or the per-class pipelines never reach steady state.  Up to eight of them sit
+    // in one workgroup, where their partial results merge through LDS; only beyond that is the sequence split over
+    // workgroups, which costs a second kernel for the merge.  len_bound is an upper bound of the longest sequence.
     const long long est_units = (cache->len_bound + 63) / 64;
-    long long S = (768 + heads - 1) / heads;
-    if (S > est_units / 16) S = est_units / 16;
-    if (S < 1) S = 1;
+    long long wph = 2048 / heads;
+    if (wph > est_units / 4) wph = est_units / 4;
+    if (wph < 2) wph = 2;
+    int nw_auto = wph >= 8 ? 8 : wph >= 4 ? 4 : wph >= 3 ? 3 : 2;
+    long long S = wph >= 16 ? wph / 8 : 1;
     if (S > kMaxSplits) S = kMaxSplits;
     const int forced = env_int("KVQ_ATTN_SPLITS", 0);
     if (forced >= 1 && forced <= kMaxSplits) S = forced;
@@ -870,9 +874,7 @@ static int launch_attn(const kvq_cache *cache, int32_t layer, const void *q, con
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
-    // Waves per workgroup: two waves fit a SIMD, 2048 on the chip.  A launch whose waves are all resident at once
-    // has no second, under-filled round, so large launches use two waves per workgroup.
-    const int nw = env_int("KVQ_ATTN_WAVES", heads * S >= 768 ? 2 : 4);
+    const int nw = env_int("KVQ_ATTN_WAVES", nw_auto);
     if (nw == 1) hipLaunchKernelGGL(k_decode_split<1>, dim3(grid), dim3(64), 0, st, P);
     else if (nw == 2) hipLaunchKernelGGL(k_decode_split<2>, dim3(grid), dim3(128), 0, st, P);
     else if (nw == 3) hipLaunchKernelGGL(k_decode_split<3>, dim3(grid), dim3(192), 0, st, P);
