@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--no-events", action="store_true", help="do not bracket attention launches with events")
     ap.add_argument("--no-fused", action="store_true", help="skip the second timed loop that uses kvq_append_decode_attn")
     ap.add_argument("--no-graph", action="store_true", help="skip the third timed loop that replays the fused step as a HIP graph")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the timing of the prefill-stage kernels (bulk controller, bulk append)")
     ap.add_argument("--trace-steps", action="store_true", help="log the mean attention time per layer of every timed step")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences of one layer the CPU oracle is timed on (0 = the whole batch)")
     return ap.parse_args()
@@ -88,13 +89,11 @@ def main():
             return wl.uniform_bits(cfg, B, T)
         if cfg.bits_kind == "runs":
             return np.stack([wl.run_bits(cfg, s, T) for s in range(B)])
-        out = np.empty((B, T), np.uint8)
-        for s in range(B):                                   # bulk controller launches on seeded feature draws
-            f = torch.from_numpy(wl.bulk_features(cfg, T, chunk=100 + s)).to(dev)
-            b = torch.empty(T, dtype=torch.uint8, device=dev)
-            kvq.kvq_controller(f, mlp, b)
-            out[s] = b.cpu().numpy()
-        return out
+        # one bulk controller launch on the seeded feature draws of all sequences (sequence s draws chunk 100 + s)
+        f = torch.from_numpy(np.concatenate([wl.bulk_features(cfg, T, chunk=100 + s) for s in range(B)])).to(dev)
+        b = torch.empty(B * T, dtype=torch.uint8, device=dev)
+        kvq.kvq_controller(f, mlp, b)
+        return b.view(B, T).cpu().numpy()
 
     def build_cache(variant):
         t0 = time.time()
@@ -287,6 +286,60 @@ def main():
     torch.cuda.synchronize()
     del probe
 
+    # ---------------- prefill-stage kernels at this config's shape --------------------------------------
+    prefill = None
+    if not args.no_prefill:
+        ctx = min(int(cfg.context), 8192)
+        n_rows = B * ctx
+        f = torch.from_numpy(wl.bulk_features(cfg, n_rows, chunk=7)).to(dev)
+        bb = torch.empty(n_rows, dtype=torch.uint8, device=dev)
+        kvq.kvq_controller(f, mlp, bb)                            # warm-up
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(5):
+            kvq.kvq_controller(f, mlp, bb)
+        c1.record()
+        torch.cuda.synchronize()
+        ctrl_us = c0.elapsed_time(c1) * 1e3 / 5
+        macs = sum(int(w.numel()) for w in mlp.W)
+        if cfg.bits_kind == "uniform":
+            pb = torch.from_numpy(wl.uniform_bits(cfg, B, ctx)).to(dev)
+        elif cfg.bits_kind == "runs":
+            pb = torch.from_numpy(np.stack([wl.run_bits(cfg, s_, ctx) for s_ in range(B)])).to(dev)
+        else:
+            pb = bb.view(B, ctx)
+        Tc = min(2048, ctx)
+        nch = ctx // Tc
+        pc = kvq.Cache(2, B, Hq, Hkv, Tc * nch)
+        evs = []
+        for c in range(nch):
+            K, V = wl.kv_chunk_fast(cfg, 0, 9000 + c, B, Tc, dev)
+            bt = pb[:, c * Tc:(c + 1) * Tc].contiguous()
+            a0, a1, a2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            a0.record()
+            kvq.kvq_append(pc, 0, K, V, bt, None, B, Tc)          # bookkeeping + write
+            a1.record()
+            kvq.kvq_append(pc, 1, K, V, None, None, B, Tc)        # write only: what every further layer costs
+            a2.record()
+            evs.append((a0, a1, a2))
+            del K, V
+        torch.cuda.synchronize()
+        pflags, _ = pc.status()
+        if pflags:
+            raise RuntimeError("prefill append raised device flags %d" % pflags)
+        cnt = pc.counts()[:B, :4].to(torch.float64).sum(dim=0).tolist()
+        app_bytes = sum(n * Hkv * (256 + wl.BYTES_PER_TOKEN_HEAD[w]) for n, w in zip(cnt, (2, 4, 8, 16))) / nch
+        us0 = float(np.median([a.elapsed_time(b_) * 1e3 for a, b_, _ in evs]))
+        us1 = float(np.median([b_.elapsed_time(c_) * 1e3 for _, b_, c_ in evs]))
+        prefill = {
+            "controller": {"rows": n_rows, "us": ctrl_us, "rows_per_s": n_rows / (ctrl_us * 1e-6),
+                           "TFLOPs": 2 * macs * n_rows / (ctrl_us * 1e-6) / 1e12, "frac_of_fp32_mfma_peak": 2 * macs * n_rows / (ctrl_us * 1e-6) / 1e12 / 157.3},
+            "append": {"tokens_per_seq_per_call": Tc, "bytes_per_call": app_bytes, "us_layer0_with_bookkeeping": us0, "us_other_layers": us1,
+                       "GBps_other_layers": app_bytes / (us1 * 1e-6) / 1e9, "frac_of_hbm_peak": app_bytes / (us1 * 1e-6) / 1e9 / HBM_PEAK_GBPS},
+            "note": "bulk controller (fp32 MFMA) on batch x context rows in one call; bulk append of one layer in 2048-token chunks, "
+                    "algorithmic bytes = 256 B read + the class's bytes written per (token, kv-head)"}
+        del pc, f, bb, pb
+
     # ---------------- CPU oracle on a bounded sample -------------------------------------------------
     cpu = None
     if not args.no_cpu:
@@ -379,6 +432,7 @@ def main():
         "graph_replay": None if graph_res is None else {
             "us_per_step": graph_res["ms_per_step"] * 1e3,
             "note": "the fused path's step captured once as a HIP graph and replayed (launch overhead off the host)"},
+        "prefill": prefill,
         "compare": compare,
     }
     traffic = None
