@@ -383,10 +383,34 @@ def main():
             dt = time.perf_counter() - c0
             best = dt if best is None else min(best, dt)
         scale = (float(lens0.sum()) / float(lens_h.sum())) * L
-        cpu = {"value": best * scale * 1e6, "unit": "us/step", "cores": nthr, "kind": "oracle",
-               "sample": "decode attention of %d of %d sequences of one layer at full context (%.2f s on %d threads), "
-                         "scaled by tokens to the batch and by %d layers; features, controller and append not included"
-                         % (ns, B, best, nthr, L)}
+        # the rest of the step, once each: features (explicit attention rows of the final layer: the oracle takes the
+        # literal two-pass variance), controller, and the quantize-and-append of one token per sequence and layer
+        rng_c = np.random.default_rng(1)
+        lg = step_logits[0].cpu().numpy()
+        ids_h = step_ids[0].cpu().numpy()
+        ld = int(lens_h.max())
+        probs = rng_c.random((B, Hq, ld))
+        probs /= probs.sum(axis=2, keepdims=True)
+        c0 = time.perf_counter()
+        f_h = oracle.features(lg, ids_h, counts_np, N, Vobs, probs, np.full(B, ld, np.int32))
+        oracle.counts_update(ids_h, counts_np, N, Vobs)
+        t_feat = time.perf_counter() - c0
+        c0 = time.perf_counter()
+        b_h, _ = oracle.controller(f_h, Ws, bs)
+        t_ctrl = time.perf_counter() - c0
+        k1 = step_k[0][0][0].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)   # [B,1,Hkv,64]
+        v1 = step_k[0][0][1].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        c0 = time.perf_counter()
+        for s_ in range(B):
+            oracle.append(k1[s_], v1[s_], np.asarray(b_h[s_:s_ + 1], np.uint8))
+        t_app = (time.perf_counter() - c0) * L
+        del probs
+        total = best * scale + t_feat + t_ctrl + t_app
+        cpu = {"value": total * 1e6, "unit": "us/step", "cores": nthr, "kind": "oracle",
+               "sample": "decode attention of %d of %d sequences of ONE layer at full context (min of 3 runs, %.2f s each on %d "
+                         "threads), scaled by tokens to the batch and by %d layers = %.2f s; plus, timed once: features of the "
+                         "batch %.3f s, controller %.4f s, quantize-and-append of one token per sequence x %d layers %.3f s "
+                         "(these three single-threaded)" % (ns, B, best, nthr, L, best * scale, t_feat, t_ctrl, L, t_app)}
     cache.destroy()
     del cache
     torch.cuda.empty_cache()
