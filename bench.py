@@ -338,6 +338,25 @@ def main():
                        "GBps_other_layers": app_bytes / (us1 * 1e-6) / 1e9, "frac_of_hbm_peak": app_bytes / (us1 * 1e-6) / 1e9 / HBM_PEAK_GBPS},
             "note": "bulk controller (fp32 MFMA) on batch x context rows in one call; bulk append of one layer in 2048-token chunks, "
                     "algorithmic bytes = 256 B read + the class's bytes written per (token, kv-head)"}
+        # the controller's training step (Sec. 3.8, Algorithm 1) on mini-batches of labelled feature rows
+        tr = {}
+        hp = kvq.make_train_hparams(1.0, 0.3, 0.7, [0.2, 0.35, 0.6, 1.0], [0.55, 0.8, 0.95, 1.0], lr=1e-3)
+        tw = kvq.MlpWeights([w.clone() for w in mlp.W], [b_.clone() for b_ in mlp.b])
+        tm = kvq.MlpWeights([torch.zeros_like(w) for w in mlp.W], [torch.zeros_like(b_) for b_ in mlp.b])
+        tv = kvq.MlpWeights([torch.zeros_like(w) for w in mlp.W], [torch.zeros_like(b_) for b_ in mlp.b])
+        for nb in (256, 4096):
+            tws = torch.empty(kvq.kvq_controller_train_workspace(tw, nb), dtype=torch.uint8, device=dev)
+            for t_ in range(1, 4):
+                kvq.kvq_controller_train_step(f[:nb], bb[:nb], tw, tm, tv, hp, t_, tws)
+            t0_, t1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0_.record()
+            for t_ in range(4, 24):
+                kvq.kvq_controller_train_step(f[:nb], bb[:nb], tw, tm, tv, hp, t_, tws)
+            t1_.record()
+            torch.cuda.synchronize()
+            us_ = t0_.elapsed_time(t1_) * 1e3 / 20
+            tr["batch_%d" % nb] = {"us_per_step": us_, "GFLOPs": 6 * macs * nb / (us_ * 1e-6) / 1e9}
+        prefill["train_step"] = tr
         del pc, f, bb, pb
 
     # ---------------- CPU oracle on a bounded sample -------------------------------------------------

@@ -241,6 +241,37 @@ int kvq_append_decode_attn(kvq_cache *cache, int32_t layer, const void *k, const
                            float *sum_p2_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Training step of the controller (Sec. 3.8 and the inner loop of Algorithm 1) on one mini-batch:
+ *   o = f_theta(s), p = Softmax(o), y = {2,4,8,16} -> {0,1,2,3} of the label,
+ *   L_ce = mean_i -log p_{i,y_i},  L_lat = mean_i sum_k p_ik c_k,  L_qual = 1 - mean_i sum_k p_ik q_k,
+ *   L = alpha L_ce + beta L_lat + gamma L_qual,  theta <- Adam(theta, dL/dtheta).
+ * The paper gives no values for c, q, alpha, beta, gamma or Adam's constants: all are arguments.  The derivative of
+ * ReLU at 0 is 0.  Adam: m <- b1 m + (1-b1) g, v <- b2 v + (1-b2) g^2,
+ * theta <- theta - lr (m / (1-b1^t)) / (sqrt(v / (1-b2^t)) + eps), no weight decay.  fp32 throughout.
+ *   feats       device fp32 [n][4];  label_bits  device uint8 [n], values 2/4/8/16 (anything else counts as 16)
+ *   mlp         host struct; its device weights and biases are UPDATED IN PLACE (hidden widths up to 128)
+ *   adam_m/v    host structs of the same shape whose W/b pointers are the device first/second moment buffers,
+ *               updated in place (zero them before step 1)
+ *   step        t, counted from 1
+ *   losses_out  device fp32 [4] = L, L_ce, L_lat, L_qual of the mini-batch before the update, or NULL
+ *   grads_out   device fp32 [kvq_controller_param_count] in the order W1, b1, W2, b2, (W3, b3), or NULL
+ *   workspace   device, at least kvq_controller_train_workspace(mlp, n) bytes, 16-byte aligned
+ * Two launches, no allocation, no synchronization; the result does not depend on scheduling (no atomics).
+ * ------------------------------------------------------------------------------------------- */
+typedef struct kvq_train_hparams {
+    float alpha, beta, gamma;       /* weights of the three loss terms */
+    float c[4];                     /* latency cost per class */
+    float q[4];                     /* quality score per class */
+    float lr, beta1, beta2, eps;    /* Adam */
+} kvq_train_hparams;
+int64_t kvq_controller_param_count(const kvq_mlp *mlp);
+size_t kvq_controller_train_workspace(const kvq_mlp *mlp, int64_t n);
+int kvq_controller_train_step(const float *feats, const uint8_t *label_bits, int64_t n, const kvq_mlp *mlp,
+                              const kvq_mlp *adam_m, const kvq_mlp *adam_v, const kvq_train_hparams *hp,
+                              int64_t step, float *losses_out, float *grads_out, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement helpers (not part of the method): a streaming read-reduce and a plain copy of `bytes`
  * bytes (a multiple of 16), used to measure the attainable HBM rate next to the kernels above and to
  * calibrate hardware byte counters against a transfer of known size.

@@ -24,7 +24,8 @@ EXPORT_REC = 128
 EXPORTED_SYMBOLS = (
     "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
     "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_export",
-    "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_features_controller", "kvq_append", "kvq_decode_attn_workspace",
+    "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_features_controller", "kvq_controller_param_count", "kvq_controller_train_workspace",
+    "kvq_controller_train_step", "kvq_append", "kvq_decode_attn_workspace",
     "kvq_decode_attn", "kvq_append_decode_attn", "kvq_probe_read", "kvq_probe_copy",
 )
 
@@ -47,6 +48,12 @@ class CacheDesc(ctypes.Structure):
 class Mlp(ctypes.Structure):
     _fields_ = [("n_linear", ctypes.c_int32), ("dims", ctypes.c_int32 * 5),
                 ("W", ctypes.c_void_p * 4), ("b", ctypes.c_void_p * 4)]
+
+
+class TrainHparams(ctypes.Structure):
+    _fields_ = [("alpha", ctypes.c_float), ("beta", ctypes.c_float), ("gamma", ctypes.c_float),
+                ("c", ctypes.c_float * 4), ("q", ctypes.c_float * 4),
+                ("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float)]
 
 
 _lib: Optional[ctypes.CDLL] = None
@@ -79,6 +86,12 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_controller.argtypes = [vp, i64, ctypes.POINTER(Mlp), vp, vp, vp]
     lib.kvq_features_controller.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, i32, ctypes.POINTER(Mlp), vp, vp, vp, vp,
                                             vp, vp]
+    lib.kvq_controller_param_count.restype = i64
+    lib.kvq_controller_param_count.argtypes = [ctypes.POINTER(Mlp)]
+    lib.kvq_controller_train_workspace.restype = sz
+    lib.kvq_controller_train_workspace.argtypes = [ctypes.POINTER(Mlp), i64]
+    lib.kvq_controller_train_step.argtypes = [vp, vp, i64, ctypes.POINTER(Mlp), ctypes.POINTER(Mlp), ctypes.POINTER(Mlp),
+                                              ctypes.POINTER(TrainHparams), i64, vp, vp, vp, sz, vp]
     lib.kvq_append.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, vp]
     lib.kvq_decode_attn_workspace.restype = sz
     lib.kvq_decode_attn_workspace.argtypes = [vp, i32]
@@ -245,6 +258,36 @@ def kvq_controller(feats: torch.Tensor, mlp: MlpWeights, bits_out: torch.Tensor,
     _check(load_library().kvq_controller(_ptr(feats, torch.float32, "feats"), n, ctypes.byref(mlp.c),
                                          _ptr(bits_out, torch.uint8, "bits_out"),
                                          _ptr(logits_out, torch.float32, "logits_out"), _stream(stream)))
+
+
+def make_train_hparams(alpha: float, beta: float, gamma: float, c: Sequence[float], q: Sequence[float], lr: float = 1e-3,
+                       beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> TrainHparams:
+    hp = TrainHparams()
+    hp.alpha, hp.beta, hp.gamma, hp.lr, hp.beta1, hp.beta2, hp.eps = alpha, beta, gamma, lr, beta1, beta2, eps
+    for k in range(4):
+        hp.c[k], hp.q[k] = c[k], q[k]
+    return hp
+
+
+def kvq_controller_param_count(mlp: MlpWeights) -> int:
+    return int(load_library().kvq_controller_param_count(ctypes.byref(mlp.c)))
+
+
+def kvq_controller_train_workspace(mlp: MlpWeights, n: int) -> int:
+    return int(load_library().kvq_controller_train_workspace(ctypes.byref(mlp.c), n))
+
+
+def kvq_controller_train_step(feats: torch.Tensor, label_bits: torch.Tensor, mlp: MlpWeights, adam_m: MlpWeights,
+                              adam_v: MlpWeights, hp: TrainHparams, step: int, workspace: torch.Tensor,
+                              losses_out: Optional[torch.Tensor] = None, grads_out: Optional[torch.Tensor] = None,
+                              stream=None) -> None:
+    """Updates mlp's weights and the Adam moments (adam_m, adam_v: MlpWeights of the same shape) in place."""
+    n = feats.shape[0]
+    _check(load_library().kvq_controller_train_step(
+        _ptr(feats, torch.float32, "feats"), _ptr(label_bits, torch.uint8, "label_bits"), n, ctypes.byref(mlp.c),
+        ctypes.byref(adam_m.c), ctypes.byref(adam_v.c), ctypes.byref(hp), step, _ptr(losses_out, torch.float32, "losses_out"),
+        _ptr(grads_out, torch.float32, "grads_out"), _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+        _stream(stream)))
 
 
 def kvq_append(cache: Cache, layer: int, k: torch.Tensor, v: torch.Tensor, bits: Optional[torch.Tensor],

@@ -28,7 +28,7 @@ __global__ __launch_bounds__(kRowThreads) void k_mlp_row(MlpArgs A, int staged)
     if (staged) mlp_stage_weights(A, stage, tid, kRowThreads);
     if (tid < A.dims[0]) act[0][tid] = A.feats[row * A.dims[0] + tid];
     __syncthreads();
-    const int cur = mlp_row_forward(A, act, tid, staged ? stage : nullptr);
+    const int cur = staged ? mlp_row_forward<true>(A, act, tid, stage) : mlp_row_forward<false>(A, act, tid, nullptr);
     if (tid == 0) emit_decision(act[cur], A.dims[A.n_linear], row, A.bits, A.logits);
 }
 
@@ -196,8 +196,11 @@ __global__ __launch_bounds__(256) void k_mlp_mfma(MlpArgs A, long long ntiles)
 template <int T1, int T2> static int launch_mfma(const MlpArgs &A, hipStream_t st)
 {
     const size_t lds = mfma_lds_floats(T1, T2) * sizeof(float);
-    if (lds > 48 * 1024)
-        KVQ_HIP(hipFuncSetAttribute((const void *)k_mlp_mfma<T1, T2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    {
+        static size_t granted = 0;                 // one per instantiation
+        const int rc_lds = ensure_dynamic_lds((const void *)k_mlp_mfma<T1, T2>, lds, &granted);
+        if (rc_lds != KVQ_OK) return rc_lds;
+    }
     const long long ntiles = (A.n + 31) / 32;
     // persistent: one workgroup per compute unit stages the weights once and walks over the row tiles
     static int n_cu = 0;
@@ -280,8 +283,11 @@ extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp,
         const int stage_floats = mlp_stage_floats(A);
         const int staged = stage_floats <= kMlpStageMaxFloats;
         const size_t lds = staged ? (size_t)stage_floats * sizeof(float) : 0;
-        if (lds > 48 * 1024)
-            KVQ_HIP(hipFuncSetAttribute((const void *)k_mlp_row, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        {
+        static size_t granted = 0;
+        const int rc_lds = ensure_dynamic_lds((const void *)k_mlp_row, lds, &granted);
+        if (rc_lds != KVQ_OK) return rc_lds;
+    }
         hipLaunchKernelGGL(k_mlp_row, dim3((unsigned)n), dim3(kRowThreads), lds, st, A, staged);
     } else if (mfma_width(A.dims[1]) && (A.n_linear == 2 || mfma_width(A.dims[2])) && ((uintptr_t)feats & 15) == 0 &&
                !getenv("KVQ_CONTROLLER_NO_MFMA")) {
@@ -292,8 +298,11 @@ extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp,
         const long long blocks = (n + kBulkThreads - 1) / kBulkThreads;
         if (blocks > 0x7fffffffLL) { set_error("n too large for one launch"); return KVQ_ERR_CAPACITY; }
         const size_t lds = (size_t)2 * maxw * kBulkThreads * sizeof(float);
-        if (lds > 48 * 1024)
-            KVQ_HIP(hipFuncSetAttribute((const void *)k_mlp_bulk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        {
+        static size_t granted = 0;
+        const int rc_lds = ensure_dynamic_lds((const void *)k_mlp_bulk, lds, &granted);
+        if (rc_lds != KVQ_OK) return rc_lds;
+    }
         hipLaunchKernelGGL(k_mlp_bulk, dim3((unsigned)blocks), dim3(kBulkThreads), lds, st, A, maxw);
     }
     KVQ_HIP(hipGetLastError());

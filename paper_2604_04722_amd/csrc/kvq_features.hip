@@ -322,7 +322,7 @@ __global__ __launch_bounds__(kFrontGroups * kFeatThreads) void k_front(FrontArgs
         f[0] = act[0][0]; f[1] = act[0][1]; f[2] = act[0][2]; f[3] = act[0][3];
     }
     __syncthreads();
-    const int cur = mlp_row_forward(M, act, tid, staged ? stage : nullptr);
+    const int cur = staged ? mlp_row_forward<true>(M, act, tid, stage) : mlp_row_forward<false>(M, act, tid, nullptr);
     if (tid == 0) {
         const int b = emit_decision(act[cur], 4, row, M.bits, M.logits);
         if (F.advance) advance_one_token(cv, seq, b, pre);
@@ -457,8 +457,11 @@ extern "C" int kvq_features_controller(const float *logits, int64_t n, int64_t v
     const int stage_floats = mlp_stage_floats(M);
     const int staged = stage_floats <= kMlpStageMaxFloats;
     const size_t lds = staged ? (size_t)stage_floats * sizeof(float) : 0;
-    if (lds > 48 * 1024)
-        KVQ_HIP(hipFuncSetAttribute((const void *)k_front, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    {
+        static size_t granted = 0;
+        const int rc_lds = ensure_dynamic_lds((const void *)k_front, lds, &granted);
+        if (rc_lds != KVQ_OK) return rc_lds;
+    }
     hipLaunchKernelGGL(k_front, dim3((unsigned)n), dim3(kFrontGroups * kFeatThreads), lds, st, F, M, cv, staged);
     KVQ_HIP(hipGetLastError());
     if (update_counts) {

@@ -85,6 +85,18 @@ int check_hip(hipError_t e, const char *what);
         if (_rc != KVQ_OK) return _rc;                             \
     } while (0)
 
+// Raises a kernel's dynamic-LDS limit when `bytes` needs it (above 48 KiB) and exceeds what this process has already
+// set for that kernel (`*granted`, a static of the call site): the runtime call is not free on the host, and the
+// per-step entry points would otherwise repeat it on every call.
+inline int ensure_dynamic_lds(const void *kernel, size_t bytes, size_t *granted)
+{
+    if (bytes <= 48 * 1024 || bytes <= *granted) return KVQ_OK;
+    const int rc = check_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes),
+                             "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+    if (rc == KVQ_OK) *granted = bytes;
+    return rc;
+}
+
 // ---- small device helpers -------------------------------------------------------------------
 
 __device__ __forceinline__ int bits_to_class(int b) { return b == 2 ? 0 : b == 4 ? 1 : b == 8 ? 2 : 3; }

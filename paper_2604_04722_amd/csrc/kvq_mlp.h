@@ -46,7 +46,10 @@ constexpr int kMlpStageMaxFloats = 18432;       // 72 KiB: 4-128-128-4 needs 17 
 __device__ __forceinline__ void mlp_stage_weights(const MlpArgs &A, float *stage, int tid, int nthreads)
 {
     int base = 0;
-    for (int l = 0; l < A.n_linear; ++l) {
+    // compile-time layer indices: a weight pointer picked from the array at run time would lose its address space
+#pragma unroll
+    for (int l = 0; l < 3; ++l) {
+        if (l >= A.n_linear) break;
         const int in = A.dims[l], outw = A.dims[l + 1], row = in + 1, total = in * outw;
         const float *W = A.W[l];
         if ((in & 3) == 0 && ((uintptr_t)W & 15) == 0) {
@@ -83,25 +86,42 @@ __device__ __forceinline__ void mlp_stage_weights(const MlpArgs &A, float *stage
 // Every thread of the workgroup calls this with the features in act[0][0..dims[0]) and a barrier behind them (and
 // behind mlp_stage_weights if stage != nullptr; with stage == nullptr the weights are read from global memory).
 // Returns the index (0 or 1) of the act row that holds the logits; a barrier has been passed when it returns.
+// Staged selects the weights' address space at compile time (LDS `stage`, or global memory): a pointer that may be
+// either would be a generic one, and every weight read a flat load.
+template <bool Staged>
 __device__ __forceinline__ int mlp_row_forward(const MlpArgs &A, float (*act)[kMaxWidth], int tid, const float *stage)
 {
     int cur = 0, base = 0;
-    for (int l = 0; l < A.n_linear; ++l) {
+#pragma unroll
+    for (int l = 0; l < 3; ++l) {
+        if (l >= A.n_linear) break;
         const int in = A.dims[l], outw = A.dims[l + 1];
         if (tid < outw) {
             float a = A.b[l][tid];
-            const float *w = stage ? stage + base + tid * (in + 1) : A.W[l] + (size_t)tid * in;
             const float *h = act[cur];
             int i = 0;
             // eight weights and activations are fetched before their FMAs: one read latency per eight terms
-            for (; i + 8 <= in; i += 8) {
-                float wv[8], hv[8];
+            if constexpr (Staged) {
+                const float *w = stage + base + tid * (in + 1);
+                for (; i + 8 <= in; i += 8) {
+                    float wv[8], hv[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) { wv[u] = w[i + u]; hv[u] = h[i + u]; }
+                    for (int u = 0; u < 8; ++u) { wv[u] = w[i + u]; hv[u] = h[i + u]; }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) a = fmaf(wv[u], hv[u], a);
+                    for (int u = 0; u < 8; ++u) a = fmaf(wv[u], hv[u], a);
+                }
+                for (; i < in; ++i) a = fmaf(w[i], h[i], a);
+            } else {
+                const float *w = A.W[l] + (size_t)tid * in;
+                for (; i + 8 <= in; i += 8) {
+                    float wv[8], hv[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) { wv[u] = w[i + u]; hv[u] = h[i + u]; }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) a = fmaf(wv[u], hv[u], a);
+                }
+                for (; i < in; ++i) a = fmaf(w[i], h[i], a);
             }
-            for (; i < in; ++i) a = fmaf(w[i], h[i], a);
             if (l + 1 < A.n_linear) a = fmaxf(a, 0.f);
             act[cur ^ 1][tid] = a;
         }
