@@ -186,6 +186,72 @@ def test_degenerate_vectors_constant_tiny_huge_and_signed_zero():
         assert_export_equals(cache, 0, 0, oc)
 
 
+def tie_vectors(shape, seed):
+    """fp16 vectors whose quotients (x - min) / scale sit on, or within a few ulp of, half-integers: each vector holds its
+    minimum 0, a maximum that fixes an exactly representable scale, and otherwise values (k + 1/2) * scale nudged by
+    0, +-1 or +-2 fp16 ulps; a second family uses scales that are NOT exact in fp16 (the stored scale is rounded)."""
+    rng = np.random.default_rng(seed)
+    n = int(np.prod(shape[:-1]))
+    out = np.zeros((n, 64), np.float16)
+    for v in range(n):
+        levels = (3, 15, 255)[v % 3]
+        if v % 2 == 0:
+            scale = np.float16(2.0 ** rng.integers(-6, 3))                 # exact: quotients are exact half-integers
+        else:
+            scale = np.float16(rng.uniform(0.01, 1.5))                      # max / levels rounds when stored
+        k = rng.integers(0, levels, 64)
+        x = ((k + 0.5) * np.float32(scale)).astype(np.float16)
+        nudge = rng.integers(-2, 3, 64)
+        x = (x.view(np.uint16).astype(np.int32) + nudge).astype(np.uint16).view(np.float16)
+        x[0] = 0.0
+        x[1] = np.float16(np.float32(scale) * levels)
+        out[v] = x[rng.permutation(64)]
+    return out.reshape(shape)
+
+
+@pytest.mark.parametrize("T", [8, 100])          # the wave-per-vector kernel, then the lane-per-token bulk kernel
+def test_quotients_on_and_next_to_rounding_ties_are_bit_exact(T):
+    say("append with quotients on / next to ties, T=%d" % T)
+    B, Hq, Hkv = 2, 4, 4
+    K = tie_vectors((B, T, Hkv, 64), 300 + T)
+    V = tie_vectors((B, T, Hkv, 64), 400 + T)
+    bits = np.tile(np.array([2, 4, 8, 16, 8, 4, 2, 2], np.uint8), (B, (T + 7) // 8))[:, :T].copy()
+    cache = kvq.Cache(1, B, Hq, Hkv, T)
+    oc = OracleCache(B, Hkv)
+    kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+    for b in range(B):
+        oc.append(b, K[b], V[b], bits[b])
+        assert_export_equals(cache, 0, b, oc)
+
+
+def test_bulk_append_degenerate_vectors_and_all_layers_in_one_call():
+    say("bulk append (T=70, layer=-1): constant, sub-resolution, +-65504, signed-zero vectors, ragged tile tail")
+    B, T, Hq, Hkv, L = 2, 70, 2, 2, 3
+    rng = np.random.default_rng(9)
+    K = np.stack([make_kv((B, T, Hkv, 64), 500 + l, outlier=l % 2 == 0) for l in range(L)])
+    V = np.stack([make_kv((B, T, Hkv, 64), 600 + l, outlier=False) for l in range(L)])
+    K[:, 0, 0] = np.float16(1.5)
+    V[:, 0, 0] = np.float16(-0.0)
+    K[:, 0, 1] = 0.0
+    K[:, 0, 1, :, 3] = np.uint16(1).view(np.float16)
+    K[:, 1, 2, :, ::2] = np.float16(65504.0)
+    K[:, 1, 2, :, 1::2] = np.float16(-65504.0)
+    V[:, 1, 3] = np.abs(V[:, 1, 3])
+    V[:, 1, 3, :, 5] = np.float16(-0.0)
+    V[:, 1, 3, :, 6] = np.float16(0.0)
+    K[:, 0, 69] = (rng.standard_normal((L, Hkv, 64)) * 1e-6).astype(np.float16)
+    bits = rng.choice([2, 4, 8, 16], (B, T)).astype(np.uint8)
+    bits[:, :4] = np.array([2, 4, 8, 16], np.uint8)
+    cache = kvq.Cache(L, B, Hq, Hkv, T)
+    kvq.kvq_append(cache, -1, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+    for l in range(L):
+        oc = OracleCache(B, Hkv)
+        for b in range(B):
+            oc.append(b, K[l, b], V[l, b], bits[b])
+            assert_export_equals(cache, l, b, oc)
+    assert cache.status()[0] == 0
+
+
 def test_student_t_heavy_tailed_channels_and_long_mixed_context():
     say("heavy-tailed channels, ctx 3000, mix 40/30/20/10, 15q/5kv")
     B, T, Hq, Hkv = 2, 3000, 15, 5
