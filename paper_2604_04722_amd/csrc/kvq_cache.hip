@@ -141,22 +141,28 @@ __global__ void k_free_seqs(CacheView cv, const int32_t *seq_ids, int n_seq)
     if (threadIdx.x == 0) cv.last_T[seq] = 0;
 }
 
-// Bucket bookkeeping for T new tokens of each listed sequence: one wavefront per sequence walks the
-// tokens 64 at a time; a ballot per class gives every token its rank inside its class.
-__global__ __launch_bounds__(64) void k_advance(CacheView cv, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T)
+// Bucket bookkeeping for T new tokens of each listed sequence: one workgroup of 1 to 16 wavefronts per sequence walks
+// the tokens 64 per wavefront at a time.  A ballot per class gives every token its rank among its wavefront's tokens of
+// that class; the wavefronts' class counts go through LDS, and their exclusive prefix (a scan over at most 16 entries)
+// turns the rank into the token's slot.  With one wavefront this is the decode-step shape; with 16 it allocates the
+// slots of a long prompt 1024 tokens per pass.
+constexpr int kAdvanceMaxWaves = 16;
+
+__global__ __launch_bounds__(64 * kAdvanceMaxWaves) void k_advance(CacheView cv, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T)
 {
+    __shared__ int wave_count[kAdvanceMaxWaves][kClasses];
     const int si = blockIdx.x;
     if (si >= n_seq) return;
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
     const int seq = seq_ids ? seq_ids[si] : si;
     if (seq < 0 || seq >= cv.max_seqs) {
-        if (lane == 0) atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL);
+        if (tid == 0) atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL);
         return;
     }
     int32_t *cnt = cv.counts + (size_t)seq * 5;
     const int len = cnt[4];
     if ((int64_t)len + T > (int64_t)cv.max_context) {
-        if (lane == 0) {
+        if (tid == 0) {
             atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL);
             cv.last_T[seq] = 0;
         }
@@ -164,40 +170,53 @@ __global__ __launch_bounds__(64) void k_advance(CacheView cv, const uint8_t *bit
     }
     int cc[kClasses] = {cnt[0], cnt[1], cnt[2], cnt[3]};
     bool bad = false;
-    for (int t0 = 0; t0 < T; t0 += 64) {
-        const int t = t0 + lane;
+    for (int t0 = 0; t0 < T; t0 += 64 * n_waves) {
+        const int t = t0 + tid;
         const bool valid = t < T;
         int b = valid ? (int)bits[(size_t)si * T + t] : 0;
         if (valid && b != 2 && b != 4 && b != 8 && b != 16) { bad = true; b = 16; }
         const int cls = bits_to_class(b);
+        int rank = 0;
 #pragma unroll
         for (int c = 0; c < kClasses; ++c) {
-            const bool mine = valid && cls == c;
-            const unsigned long long mask = __ballot(mine);
-            if (mine) {
-                const int rank = __popcll(mask & ((1ull << lane) - 1ull));
-                const int slot = cc[c] + rank;
-                if (slot % cv.page_tokens == 0) {
-                    int page;
-                    const int idx = atomicSub(&cv.free_top[c], 1) - 1;
-                    if (idx < 0) {
-                        atomicAdd(&cv.free_top[c], 1);
-                        atomicOr(cv.flags, KVQ_FLAG_POOL_EXHAUSTED);
-                        page = cv.n_pages[c];                          // sink page: in bounds, shared, garbage
-                    } else {
-                        page = cv.free_stack[c][idx];
-                    }
-                    cv.page_table[((size_t)seq * kClasses + c) * cv.max_pages_per_seq + slot / cv.page_tokens] = page;
-                }
-                const size_t pos = (size_t)seq * cv.max_context + len + t;
-                cv.bits_log[pos] = (uint8_t)b;
-                cv.slot_log[pos] = slot;
-            }
-            cc[c] += __popcll(mask);
+            const unsigned long long mask = __ballot(valid && cls == c);
+            if (cls == c) rank = __popcll(mask & ((1ull << lane) - 1ull));
+            if (lane == 0) wave_count[wave][c] = __popcll(mask);
         }
+        __syncthreads();
+        int before = 0, total[kClasses] = {0, 0, 0, 0};
+        for (int w = 0; w < n_waves; ++w) {
+#pragma unroll
+            for (int c = 0; c < kClasses; ++c) {
+                const int n = wave_count[w][c];
+                if (w < wave && c == cls) before += n;
+                total[c] += n;
+            }
+        }
+        if (valid) {
+            const int slot = (cls == 0 ? cc[0] : cls == 1 ? cc[1] : cls == 2 ? cc[2] : cc[3]) + before + rank;
+            if (slot % cv.page_tokens == 0) {
+                int page;
+                const int idx = atomicSub(&cv.free_top[cls], 1) - 1;
+                if (idx < 0) {
+                    atomicAdd(&cv.free_top[cls], 1);
+                    atomicOr(cv.flags, KVQ_FLAG_POOL_EXHAUSTED);
+                    page = cv.n_pages[cls];                            // sink page: in bounds, shared, garbage
+                } else {
+                    page = cv.free_stack[cls][idx];
+                }
+                cv.page_table[((size_t)seq * kClasses + cls) * cv.max_pages_per_seq + slot / cv.page_tokens] = page;
+            }
+            const size_t pos = (size_t)seq * cv.max_context + len + t;
+            cv.bits_log[pos] = (uint8_t)b;
+            cv.slot_log[pos] = slot;
+        }
+#pragma unroll
+        for (int c = 0; c < kClasses; ++c) cc[c] += total[c];
+        __syncthreads();                                               // wave_count is rewritten by the next pass
     }
     if (__ballot(bad) != 0ull && lane == 0) atomicOr(cv.flags, KVQ_FLAG_BAD_BITS);
-    if (lane == 0) {
+    if (tid == 0) {
         cnt[0] = cc[0]; cnt[1] = cc[1]; cnt[2] = cc[2]; cnt[3] = cc[3];
         cnt[4] = len + T;
         cv.last_T[seq] = T;
@@ -580,7 +599,9 @@ extern "C" int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t s
 // launches the bookkeeping kernel for T new tokens per listed sequence (internal; arguments already validated)
 int kvq_append_bookkeeping(kvq_cache *cache, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T, void *stream)
 {
-    hipLaunchKernelGGL(k_advance, dim3(n_seq), dim3(64), 0, (hipStream_t)stream, cache->view, bits, seq_ids, n_seq, T);
+    int waves = (T + 63) / 64;
+    if (waves > kAdvanceMaxWaves) waves = kAdvanceMaxWaves;
+    hipLaunchKernelGGL(k_advance, dim3(n_seq), dim3(64 * waves), 0, (hipStream_t)stream, cache->view, bits, seq_ids, n_seq, T);
     KVQ_HIP(hipGetLastError());
     cache->len_bound += T;
     if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;
