@@ -134,6 +134,7 @@ struct AttnParams {
     const int32_t *seq_ids;
     float *out, *lse, *p2, *ws;
     int32_t layer, n_seq, S;
+    int32_t longest_first;      // ragged batches over more than one round of workgroups: see k_decode_split
 };
 
 // Register budget: two waves per SIMD (256 VGPRs each).  The four-buffer ring, 64 accumulators and the per-class
@@ -619,10 +620,31 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     const int g = r % G; r /= G;
     const int s = r % S; r /= S;
     const int kvh = r % cv.Hkv;
-    const int si = r / cv.Hkv;
+    int si = r / cv.Hkv;
     const int qh = kvh * G + g;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (P.longest_first) {
+        // A launch with more workgroups than fit at once is list scheduling in workgroup order: with the sequences in
+        // arbitrary order the last round may start a long one (ragged batch: makespan up to 1.3x the mean).  So the
+        // position si in the launch order takes the sequence of that RANK by length, longest first, dealt to the XCDs
+        // in turn (an XCD's k-th position has rank 8k + xcd).  Every workgroup ranks the (at most 64) lengths itself:
+        // lane = sequence, 64 lane reads.
+        const int q8 = P.n_seq >> 3;
+        const int want = (si % q8) * 8 + si / q8;
+        int my_len = -1;
+        if (lane < P.n_seq) {
+            const int sq = P.seq_ids ? P.seq_ids[lane] : lane;
+            my_len = (sq >= 0 && sq < cv.max_seqs) ? cv.counts[(size_t)sq * 5 + 4] : 0;
+        }
+        int rank = 0;
+        for (int j = 0; j < P.n_seq; ++j) {
+            const int lj = __builtin_amdgcn_readlane(my_len, j);
+            rank += (lj > my_len || (lj == my_len && j < lane)) ? 1 : 0;
+        }
+        const unsigned long long hit = __ballot(lane < P.n_seq && rank == want);
+        si = (int)__builtin_ctzll(hit);
+    }
     int seq = P.seq_ids ? P.seq_ids[si] : si;
     const bool seq_ok = seq >= 0 && seq < cv.max_seqs;
     if (!seq_ok) seq = 0;
@@ -875,6 +897,8 @@ static int launch_attn(const kvq_cache *cache, int32_t layer, const void *q, con
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
     const int nw = env_int("KVQ_ATTN_WAVES", nw_auto);
+    P.longest_first = env_int("KVQ_ATTN_LONGEST_FIRST", (n_seq <= 64 && n_seq % 8 == 0 && heads * S * nw > 2048) ? 1 : 0);
+    if (n_seq > 64 || n_seq % 8 != 0) P.longest_first = 0;
     if (nw == 1) hipLaunchKernelGGL(k_decode_split<1>, dim3(grid), dim3(64), 0, st, P);
     else if (nw == 2) hipLaunchKernelGGL(k_decode_split<2>, dim3(grid), dim3(128), 0, st, P);
     else if (nw == 3) hipLaunchKernelGGL(k_decode_split<3>, dim3(grid), dim3(192), 0, st, P);

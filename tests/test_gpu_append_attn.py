@@ -162,6 +162,53 @@ def test_ragged_lengths_empty_sequence_and_seq_ids():
         np.testing.assert_allclose(lse[i], want_lse, rtol=1e-4, atol=1e-4)
 
 
+@pytest.mark.parametrize("B,fused", [(8, False), (16, False), (16, True), (64, False)])
+def test_longest_first_launch_order_on_a_ragged_batch(B, fused):
+    say("longest-first launch order, ragged batch of %d, fused=%s" % (B, fused))
+    Hq, Hkv, max_ctx = 4, 2, 512
+    rng = np.random.default_rng(100 + B)
+    lens = rng.integers(0, 400, B)
+    lens[1] = lens[5] = 77                                       # equal lengths: ranks break the tie by position
+    lens[2] = 0
+    cache = kvq.Cache(1, B, Hq, Hkv, max_ctx)
+    oc = OracleCache(B, Hkv)
+    for s_, n in enumerate(lens):
+        if n == 0:
+            continue
+        bits = rng.choice([2, 4, 8, 16], (1, n)).astype(np.uint8)
+        K, V = make_kv((1, n, Hkv, 64), 700 + s_), make_kv((1, n, Hkv, 64), 800 + s_)
+        ids = torch.tensor([s_], dtype=torch.int32, device=dev())
+        kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), ids, 1, n)
+        oc.append(s_, K[0], V[0], bits[0])
+    order = rng.permutation(B)
+    ids = torch.from_numpy(order.astype(np.int32)).to(dev())
+    q = make_kv((B, Hq, 64), 900, outlier=False)
+    ws = torch.empty(kvq.kvq_decode_attn_workspace(cache, B), dtype=torch.uint8, device=dev())
+    out = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=dev())
+    lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
+    with env(KVQ_ATTN_LONGEST_FIRST=1):
+        if fused:
+            kn, vn = make_kv((B, 1, Hkv, 64), 901), make_kv((B, 1, Hkv, 64), 902)
+            nb = rng.choice([2, 4, 8, 16], B).astype(np.uint8)
+            kvq.kvq_append_decode_attn(cache, 0, gpu_f16(kn), gpu_f16(vn), torch.from_numpy(nb).to(dev()), gpu_f16(q), ids, B, out, ws, lse, None)
+            for i, s_ in enumerate(order):
+                oc.append(s_, kn[i], vn[i], nb[i:i + 1])
+        else:
+            kvq.kvq_decode_attn(cache, 0, gpu_f16(q), ids, B, out, ws, lse, None)
+    torch.cuda.synchronize()
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    for i, s_ in enumerate(order):
+        if len(oc.bits[s_]) == 0:
+            assert np.all(out[i] == 0) and np.all(np.isneginf(lse[i]))
+            continue
+        want, want_lse, _ = oc.attn(s_, q[i], Hq)
+        assert_attn_close(out[i], want, "slot %d seq %d" % (i, s_))
+        np.testing.assert_allclose(lse[i], want_lse, rtol=1e-4, atol=1e-4)
+    if fused:
+        for s_ in range(B):
+            assert_export_equals(cache, 0, s_, oc)
+
+
 def test_degenerate_vectors_constant_tiny_huge_and_signed_zero():
     say("degenerate vectors: constant, sub-resolution, +-65504, signed zeros")
     B, T, Hq, Hkv = 1, 8, 2, 2
