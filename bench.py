@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--no-fused", action="store_true", help="skip the second timed loop that uses kvq_append_decode_attn")
     ap.add_argument("--no-graph", action="store_true", help="skip the third timed loop that replays the fused step as a HIP graph")
     ap.add_argument("--no-prefill", action="store_true", help="skip the timing of the prefill-stage kernels (bulk controller, bulk append)")
+    ap.add_argument("--no-rotate", action="store_true", help="small configs: skip the loop over rotating copies of the cache")
     ap.add_argument("--trace-steps", action="store_true", help="log the mean attention time per layer of every timed step")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences of one layer the CPU oracle is timed on (0 = the whole batch)")
     return ap.parse_args()
@@ -70,7 +71,7 @@ def main():
     B, Hq, Hkv = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads
     n_steps = args.warmup + args.steps
     lens0 = wl.ragged_lengths(cfg).astype(np.int64) - 1          # prefill so that the first step reaches the context
-    max_ctx = int(cfg.context + 3 * n_steps + 16)                  # three timed loops may run on the mixed cache
+    max_ctx = int(cfg.context + 4 * n_steps + 16)                  # up to four timed loops run on the mixed cache
 
     # ---------------- controller + per-token precisions of the prefill -----------------------------
     if cfg.bits_kind == "controller":
@@ -102,7 +103,7 @@ def main():
         for w in (2, 4, 8, 16):
             need = 0
             for s in range(B):
-                need += math.ceil(((bits[s, :lens0[s]] == w).sum() + 3 * n_steps + 16) / 256) + 1
+                need += math.ceil(((bits[s, :lens0[s]] == w).sum() + 4 * n_steps + 16) / 256) + 1
             pools.append(int(need))
         cache = kvq.Cache(L, B, Hq, Hkv, max_ctx, pool_pages=pools)
         CH = 512
@@ -139,7 +140,7 @@ def main():
     counts_np, N, Vobs, probs_tab = wl.zipf_table(cfg)
     step_logits = [wl.logits(cfg, s, B, dev) for s in range(n_steps)]
     step_ids = [torch.from_numpy(wl.zipf_ids(cfg, probs_tab, s, B)).to(dev) for s in range(n_steps)]
-    step_len = [torch.from_numpy((lens0 + s).astype(np.int32)).to(dev) for s in range(3 * n_steps + 16)]
+    step_len = [torch.from_numpy((lens0 + s).astype(np.int32)).to(dev) for s in range(4 * n_steps + 16)]
     done_steps = {}                                          # cache id -> decode steps already run on it
     n_in = min(n_steps, 4)                                   # K/V/q of the new token: a few distinct sets, cycled
     step_k = [[wl.kv_chunk_fast(cfg, l, 5000 + s, B, 1, dev) for l in range(L)] for s in range(n_in)]
@@ -156,7 +157,7 @@ def main():
         kv = sum(n * Hkv * wl.BYTES_PER_TOKEN_HEAD[w] for n, w in zip(per_class, (2, 4, 8, 16)))
         return kv + B * Hq * 64 * (2 + 4), per_class
 
-    def run_variant(variant, timed_steps, warm_steps, events, fused=False, cache=None, graph=False):
+    def run_variant(variant, timed_steps, warm_steps, events, fused=False, cache=None, graph=False, rotate=None):
         cache = cache or build_cache(variant)
         aws = torch.empty(kvq.kvq_decode_attn_workspace(cache, B), dtype=torch.uint8, device=dev)
         counts_d = torch.from_numpy(counts_np).to(dev)
@@ -168,7 +169,11 @@ def main():
         base_step = done_steps.get(id(cache), 0)
         done_steps[id(cache)] = base_step + warm_steps + timed_steps + (1 if graph else 0)
 
+        ring = [cache] + list(rotate or [])                     # rotating copies: step s works on copy s mod len(ring)
+        main_cache = cache
+
         def step(s, record):
+            cache = ring[s % len(ring)]
             if record:
                 e0 = torch.cuda.Event(enable_timing=True); e0.record()
             if fused:
@@ -250,6 +255,7 @@ def main():
                 log("[bench] attn us/layer by step: " + " ".join("%.0f" % x for x in per))
             res["attn_us_per_layer"] = float(np.mean(attn_us))
             res["attn_us_min"] = float(np.min(attn_us))
+            res["attn_us_median"] = float(np.median(attn_us))
             res["features_us"] = float(np.mean([e0.elapsed_time(e1) * 1e3 for e0, e1, _ in stage_ev]))
             res["controller_us"] = float(np.mean([e1.elapsed_time(e2) * 1e3 for _, e1, e2 in stage_ev]))
             res["front_us"] = float(np.mean([e0.elapsed_time(e2) * 1e3 for e0, _, e2 in stage_ev]))
@@ -263,6 +269,19 @@ def main():
     fused = None
     if not args.no_fused:
         _, fused = run_variant("mixed", args.steps, args.warmup, not args.no_events, fused=True, cache=cache)
+    # small configs stay resident in the 256 MB Infinity Cache: time the same loop over rotating copies of the cache
+    rotating = None
+    total_bytes = mixed["attn_bytes_per_layer"] * L
+    if total_bytes < 256e6 and not args.no_rotate:
+        n_copies = int(min(64, math.ceil(512e6 / total_bytes)))
+        copies = [build_cache("mixed") for _ in range(n_copies - 1)]
+        _, rot = run_variant("mixed", args.steps, args.warmup, not args.no_events, cache=cache, rotate=copies)
+        rotating = {"copies": n_copies, "total_MB": n_copies * total_bytes / 1e6, "us_per_step": rot["ms_per_step"] * 1e3,
+                    "attn_us_per_layer": rot.get("attn_us_per_layer"),
+                    "note": "four-call path, step s on copy s mod copies (at most 64 copies are built)"}
+        for c_ in copies:
+            c_.destroy()
+        del copies
     graph_res = None
     if not args.no_fused and not args.no_graph:
         _, graph_res = run_variant("mixed", args.steps, args.warmup, False, fused=True, cache=cache, graph=True)
@@ -465,7 +484,8 @@ def main():
                    "mix_2_4_8_16": [round(x / tot, 4) for x in tok],
                    "expected_bits": round(sum(x * w for x, w in zip(tok, (2, 4, 8, 16))) / tot, 3)},
         "stages_us": {"features": mixed.get("features_us"), "controller": mixed.get("controller_us"),
-                      "attn_per_layer": mixed.get("attn_us_per_layer"), "attn_per_layer_min": mixed.get("attn_us_min")},
+                      "attn_per_layer": mixed.get("attn_us_per_layer"), "attn_per_layer_median": mixed.get("attn_us_median"),
+                      "attn_per_layer_min": mixed.get("attn_us_min")},
         "stream_read_GBps": stream_gbps,
         "fused_path": None if fused is None else {
             "us_per_step": fused["ms_per_step"] * 1e3, "launch_us_per_layer": fused.get("attn_us_per_layer"),
@@ -475,6 +495,7 @@ def main():
         "graph_replay": None if graph_res is None else {
             "us_per_step": graph_res["ms_per_step"] * 1e3,
             "note": "the fused path's step captured once as a HIP graph and replayed (launch overhead off the host)"},
+        "rotating_copies": rotating,
         "prefill": prefill,
         "compare": compare,
     }
