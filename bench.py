@@ -53,8 +53,8 @@ def log(*a):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus %d is not supported (batch and kv-head sharding need "
-              "no collective and are described in DESIGN.md)" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported (sequences and kv-heads are "
+              "independent units, so a larger job shards over GPUs without any exchange inside this path)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
