@@ -145,7 +145,7 @@ int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t seq, uint8_t
  *                attn_len[t] entries are used, or
  *     sum_p2     device fp32 [n][n_q_heads]: sum_j p_j^2 of each row as emitted by kvq_decode_attn
  *                (then Var = sum_p2/l - 1/l^2, because the row sums to one).
- *   attn_len   device int32 [n], each >= 1
+ *   attn_len   device int32 [n]; a value <= 0 means "no attention row yet" (a sequence's first token): V = 0
  *   workspace  device, at least kvq_features_workspace(n, vocab) bytes, 256-byte aligned
  *   feats_out  device fp32 [n][4] = H, R, V, C
  * ------------------------------------------------------------------------------------------- */

@@ -163,7 +163,7 @@ __device__ __forceinline__ float rarity_of(long long id, long long vocab, const 
 // work; the value is returned to every thread.
 __device__ __forceinline__ float variance_from_sum_p2(const float *sum_p2_row, int Hq, int l, float *red, int lt, bool active)
 {
-    const float inv_l = 1.0f / (float)l;
+    const float inv_l = l > 0 ? 1.0f / (float)l : 0.f;    // l <= 0: no attention row yet, V_t = 0
     if (active) {
         float s = 0.f;
         for (int h = lt; h < Hq; h += kFeatThreads) s += sum_p2_row[h] * inv_l - inv_l * inv_l;
@@ -199,9 +199,11 @@ __global__ __launch_bounds__(kFeatThreads) void k_features_finalize(FeatArgs A)
     __shared__ float red[kFeatThreads];
     __shared__ float red2[kFeatThreads];
     const int l = A.attn_len[t];
-    const float inv_l = 1.0f / (float)l;
+    const float inv_l = 1.0f / (float)(l > 0 ? l : 1);
     float V = 0.f;
-    if (A.attn_probs) {
+    if (l <= 0) {
+        V = 0.f;                                     // no attention row yet (a sequence's first token): V_t = 0
+    } else if (A.attn_probs) {
         // population variance of each head's row, accumulated around the expected mean 1/l so that
         // nothing cancels:  Var = sum d^2 / l - (sum d / l)^2  with d = p - 1/l
         for (int h = 0; h < A.Hq; ++h) {

@@ -354,3 +354,34 @@ def test_fused_front_end_advances_the_cache_like_a_layer0_append():
                 assert torch.equal(x, y)
     cnt = cache_a.counts().numpy()
     assert cnt[:, 4].tolist() == [n_steps] * 3 and cnt[:, :4].max() > 256
+
+
+def test_a_sequence_without_an_attention_row_yet_has_zero_variance_feature():
+    say("features with attn_len == 0 on some rows (first token of a sequence)")
+    d = dev()
+    n, vocab, Hq = 6, 4096, 5
+    logits, ids, counts, N, Vobs, lens, p2 = _front_inputs(n, vocab, Hq, 77)
+    lens = lens.copy()
+    lens[[1, 4]] = 0
+    Ws, bs = wl.calibrated_mlp(wl.CONFIGS[4])
+    mlp = kvq.MlpWeights([torch.from_numpy(w).to(d) for w in Ws], [torch.from_numpy(b).to(d) for b in bs])
+    got, _, _ = run_features(logits, ids, counts, N, Vobs, lens, Hq, sum_p2=p2)
+    feats = torch.zeros((n, 4), dtype=torch.float32, device=d)
+    bits = torch.zeros(n, dtype=torch.uint8, device=d)
+    kvq.kvq_features_controller(torch.from_numpy(logits).to(d), torch.from_numpy(ids).to(d), torch.from_numpy(counts).to(d),
+                                torch.tensor([N, Vobs], dtype=torch.int64, device=d), False, torch.from_numpy(p2).to(d),
+                                torch.from_numpy(lens).to(d), Hq, mlp, feats, bits)
+    torch.cuda.synchronize()
+    fused = feats.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), fused.view(np.uint32))
+    assert np.all(got[[1, 4], 2] == 0.0) and np.all(np.isfinite(got))
+    live = [0, 2, 3, 5]
+    want_v = (p2[live].astype(np.float64) / lens[live, None] - 1.0 / lens[live, None].astype(np.float64) ** 2).mean(axis=1)
+    np.testing.assert_allclose(got[live, 2], want_v, rtol=2e-3, atol=1e-9)
+    # with explicit rows: a zero-length row gives V = 0 too
+    probs = np.random.default_rng(3).random((n, Hq, 16))
+    probs /= probs.sum(axis=2, keepdims=True)
+    l2 = np.array([16, 0, 16, 16, 0, 16], np.int32)
+    got2, _, _ = run_features(logits, ids, counts, N, Vobs, l2, Hq, probs=probs)
+    assert np.all(got2[[1, 4], 2] == 0.0) and np.all(np.isfinite(got2))
+    np.testing.assert_allclose(got2[live, 2], probs[live].var(axis=2).mean(axis=1), rtol=1e-4)
