@@ -896,7 +896,8 @@ static int launch_attn(const kvq_cache *cache, int32_t layer, const void *q, con
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
-    const int nw = env_int("KVQ_ATTN_WAVES", nw_auto);
+    int nw = env_int("KVQ_ATTN_WAVES", 0);                      // 1, 2, 3, 4 or 8; anything else: the rule above
+    if (nw != 1 && nw != 2 && nw != 3 && nw != 4 && nw != 8) nw = nw_auto;
     P.longest_first = env_int("KVQ_ATTN_LONGEST_FIRST", (n_seq <= 64 && n_seq % 8 == 0 && heads * S * nw > 2048) ? 1 : 0);
     if (n_seq > 64 || n_seq % 8 != 0) P.longest_first = 0;
     if (nw == 1) hipLaunchKernelGGL(k_decode_split<1>, dim3(grid), dim3(64), 0, st, P);

@@ -424,9 +424,9 @@ def test_running_twice_gives_bitwise_identical_attention():
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(8, 8), (9, 3)])
-@pytest.mark.parametrize("splits", [0, 1, 3])
-def test_fused_append_attention_equals_the_oracle_and_the_two_call_path(Hq, Hkv, splits):
-    say("fused append+attention Hq=%d Hkv=%d splits=%d: decode steps from an empty cache and after a prefill" % (Hq, Hkv, splits))
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 0), (3, 0), (1, 8), (2, 8), (1, 1)])
+def test_fused_append_attention_equals_the_oracle_and_the_two_call_path(Hq, Hkv, splits, waves):
+    say("fused append+attention Hq=%d Hkv=%d splits=%d waves=%d: decode steps from an empty cache and after a prefill" % (Hq, Hkv, splits, waves))
     B, L, T0, steps = 3, 2, 333, 70
     rng = np.random.default_rng(140 + Hq)
     for prefill_len in (0, T0):
@@ -452,7 +452,7 @@ def test_fused_append_attention_equals_the_oracle_and_the_two_call_path(Hq, Hkv,
                 out = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=dev())
                 lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
                 p2 = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
-                with env(KVQ_ATTN_SPLITS=splits):
+                with env(KVQ_ATTN_SPLITS=splits, KVQ_ATTN_WAVES=waves):
                     kvq.kvq_append_decode_attn(cache, l, gpu_f16(K), gpu_f16(V), bt if l == 0 else None, gpu_f16(q), None, B,
                                                out, ws, lse, p2)
                 for s in range(B):
@@ -460,7 +460,7 @@ def test_fused_append_attention_equals_the_oracle_and_the_two_call_path(Hq, Hkv,
                 if step % 23 == 0 or step == steps - 1:
                     out2 = torch.zeros_like(out)
                     kvq.kvq_append(ref, l, gpu_f16(K), gpu_f16(V), bt if l == 0 else None, None, B, 1)
-                    with env(KVQ_ATTN_SPLITS=splits):
+                    with env(KVQ_ATTN_SPLITS=splits, KVQ_ATTN_WAVES=waves):
                         kvq.kvq_decode_attn(ref, l, gpu_f16(q), None, B, out2, ws)
                     torch.cuda.synchronize()
                     o, o2 = out.cpu().numpy(), out2.cpu().numpy()
