@@ -112,6 +112,23 @@ int kvq_cache_status(kvq_cache *cache, uint32_t *flags, int64_t *free_pages, voi
  * counts is host int32[max_seqs][5] = tokens in the 2/4/8/16-bit classes and the total length. */
 int kvq_cache_counts(kvq_cache *cache, int32_t *counts, void *stream);
 
+/* Synchronizes `stream` and reports what the cache holds (Sec. 3.3: the expected bit-width E[b] = sum_x p(x) f(x),
+ * here the mean width over all cached tokens), all sequences together:
+ *   tokens[4]            cached tokens in the 2/4/8/16-bit classes
+ *   expected_bits        E[b]; 0 for an empty cache
+ *   effective_bits       bits stored per cached element with the fp16 (scale, minimum) pairs counted: 2.5/4.5/8.5/16 per class
+ *   payload_bytes        sum over tokens of {40,72,136,256}[class] * n_kv_heads * n_layers
+ *   pages_in_use[4], page_bytes_in_use   pages handed out per class and the arena bytes they occupy (all layers) */
+typedef struct kvq_cache_usage {
+    int64_t tokens[4];
+    double expected_bits;
+    double effective_bits;
+    int64_t payload_bytes;
+    int64_t pages_in_use[4];
+    int64_t page_bytes_in_use;
+} kvq_cache_usage;
+int kvq_cache_usage_of(kvq_cache *cache, kvq_cache_usage *usage, void *stream);
+
 /* Canonical dump of one (layer, sequence), in TOKEN order, for parity checks and save/restore.
  *   bits_out  device uint8 [max_tokens]                      the width b of each token
  *   codes_out device uint8 [max_tokens][Hkv][2][128]         index 0 = K, 1 = V.  b in {2,4,8}: element i

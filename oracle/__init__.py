@@ -229,3 +229,14 @@ def controller(feats, weights: Sequence[np.ndarray], biases: Sequence[np.ndarray
     logits = np.zeros((n, dims[-1]), np.float64)
     lib().kvq_oracle_controller(_p(f), ctypes.c_int64(n), ctypes.c_int(nl), _p(dims_a), Wp, bp, _p(bits), _p(logits))
     return bits, logits
+
+
+def accounting(bits, Hkv: int, layers: int):
+    """(E[b], stored bits per element, payload bytes) of a cache whose tokens have the given widths."""
+    b = _c(bits, np.uint8).ravel()
+    eb, ef, nb = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int64(0)
+    rc = lib().kvq_oracle_accounting(_p(b), ctypes.c_int64(b.shape[0]), ctypes.c_int(Hkv), ctypes.c_int(layers),
+                                     ctypes.byref(eb), ctypes.byref(ef), ctypes.byref(nb))
+    if rc != 0:
+        raise ValueError("illegal bit width")
+    return eb.value, ef.value, nb.value

@@ -446,3 +446,29 @@ void kvq_oracle_controller(const float *feats, int64_t n, int n_linear, const in
     free(cur);
     free(nxt);
 }
+
+/* ------------------------------------------------------------------------------------------ */
+/* Sec. 3.3 (expected bit-width): E[b] = sum_x p(x) f(x), here the mean of the widths assigned */
+/* to the n cached tokens; next to it the storage those widths imply under Q_b of Sec. 3.7 as   */
+/* read in this file: per (token, kv-head), K and V each store 64*b/8 code bytes plus an fp16   */
+/* scale and an fp16 minimum (b < 16), or 64 fp16 values (b = 16).                              */
+/* ------------------------------------------------------------------------------------------ */
+int kvq_oracle_accounting(const uint8_t *bits, int64_t n, int Hkv, int layers, double *expected_bits,
+                          double *effective_bits, int64_t *payload_bytes)
+{
+    double sum_b = 0.0;
+    int64_t bytes = 0;
+    for (int64_t t = 0; t < n; ++t) {
+        const int b = bits[t];
+        if (b != 2 && b != 4 && b != 8 && b != 16) return -1;
+        sum_b += (double)b;
+        const int64_t one_vector = b == 16 ? (int64_t)KVQ_D * 2 : (int64_t)KVQ_D * b / 8 + 2 + 2;
+        bytes += 2 * one_vector;                                  /* K and V */
+    }
+    bytes *= (int64_t)Hkv * layers;
+    *expected_bits = n > 0 ? sum_b / (double)n : 0.0;
+    /* bits actually stored per cached element, metadata included */
+    *effective_bits = n > 0 ? (double)bytes * 8.0 / ((double)n * Hkv * layers * 2.0 * KVQ_D) : 0.0;
+    *payload_bytes = bytes;
+    return 0;
+}

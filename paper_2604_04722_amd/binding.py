@@ -23,7 +23,7 @@ EXPORT_REC = 128
 
 EXPORTED_SYMBOLS = (
     "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
-    "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_export",
+    "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export",
     "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_features_controller", "kvq_controller_param_count", "kvq_controller_train_workspace",
     "kvq_controller_train_step", "kvq_append", "kvq_decode_attn_workspace",
     "kvq_decode_attn", "kvq_append_decode_attn", "kvq_probe_read", "kvq_probe_copy",
@@ -48,6 +48,11 @@ class CacheDesc(ctypes.Structure):
 class Mlp(ctypes.Structure):
     _fields_ = [("n_linear", ctypes.c_int32), ("dims", ctypes.c_int32 * 5),
                 ("W", ctypes.c_void_p * 4), ("b", ctypes.c_void_p * 4)]
+
+
+class CacheUsage(ctypes.Structure):
+    _fields_ = [("tokens", ctypes.c_int64 * 4), ("expected_bits", ctypes.c_double), ("effective_bits", ctypes.c_double),
+                ("payload_bytes", ctypes.c_int64), ("pages_in_use", ctypes.c_int64 * 4), ("page_bytes_in_use", ctypes.c_int64)]
 
 
 class TrainHparams(ctypes.Structure):
@@ -79,6 +84,7 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_cache_free_seqs.argtypes = [vp, vp, i32, vp]
     lib.kvq_cache_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(i64), vp]
     lib.kvq_cache_counts.argtypes = [vp, vp, vp]
+    lib.kvq_cache_usage_of.argtypes = [vp, ctypes.POINTER(CacheUsage), vp]
     lib.kvq_cache_export.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp]
     lib.kvq_features_workspace.restype = sz
     lib.kvq_features_workspace.argtypes = [i64, i64]
@@ -190,6 +196,14 @@ class Cache:
         out = torch.zeros((self.max_seqs, 5), dtype=torch.int32)
         _check(load_library().kvq_cache_counts(self.handle, out.data_ptr(), _stream(stream)))
         return out
+
+    def usage(self, stream=None) -> dict:
+        """Tokens per class, E[b], stored bits per element, payload and page bytes (host values)."""
+        u = CacheUsage()
+        _check(load_library().kvq_cache_usage_of(self.handle, ctypes.byref(u), _stream(stream)))
+        return {"tokens": [int(x) for x in u.tokens], "expected_bits": float(u.expected_bits),
+                "effective_bits": float(u.effective_bits), "payload_bytes": int(u.payload_bytes),
+                "pages_in_use": [int(x) for x in u.pages_in_use], "page_bytes_in_use": int(u.page_bytes_in_use)}
 
     def export(self, layer: int, seq: int, max_tokens: int, stream=None):
         dev = torch.device("cuda")

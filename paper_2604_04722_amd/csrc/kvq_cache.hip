@@ -579,6 +579,39 @@ extern "C" int kvq_cache_counts(kvq_cache *cache, int32_t *counts, void *stream)
     return KVQ_OK;
 }
 
+extern "C" int kvq_cache_usage_of(kvq_cache *cache, kvq_cache_usage *usage, void *stream)
+{
+    if (!cache || !usage) { set_error("cache or usage is NULL"); return KVQ_ERR_INVALID_ARG; }
+    const kvq_cache_desc &d = cache->desc;
+    int32_t *counts = new (std::nothrow) int32_t[(size_t)d.max_seqs * 5];
+    if (!counts) { set_error("host allocation failed"); return KVQ_ERR_OOM; }
+    int rc = kvq_cache_counts(cache, counts, stream);
+    int32_t top[kClasses] = {0, 0, 0, 0};
+    if (rc == KVQ_OK) rc = check_hip(hipMemcpy(top, cache->view.free_top, sizeof(top), hipMemcpyDeviceToHost), "hipMemcpy(free_top)");
+    if (rc != KVQ_OK) { delete[] counts; return rc; }
+    static const int bits_of[kClasses] = {2, 4, 8, 16};
+    kvq_cache_usage u;
+    memset(&u, 0, sizeof(u));
+    int64_t total = 0;
+    double sum_bits = 0.0;
+    for (int c = 0; c < kClasses; ++c) {
+        for (int s = 0; s < d.max_seqs; ++s) u.tokens[c] += counts[(size_t)s * 5 + c];
+        total += u.tokens[c];
+        sum_bits += (double)u.tokens[c] * bits_of[c];
+        // per (token, kv-head): K and V codes, plus the two fp16 (scale, minimum) pairs of the quantized classes
+        const int64_t per_token_head = class_block_bytes(c) / kBlockTokens;
+        u.payload_bytes += u.tokens[c] * per_token_head * d.n_kv_heads * d.n_layers;
+        const int free_now = top[c] < 0 ? 0 : top[c];
+        u.pages_in_use[c] = (int64_t)cache->view.n_pages[c] - free_now;
+        u.page_bytes_in_use += u.pages_in_use[c] * (int64_t)cache->view.blocks_per_page * class_block_bytes(c) * d.n_kv_heads * d.n_layers;
+    }
+    u.expected_bits = total > 0 ? sum_bits / (double)total : 0.0;
+    u.effective_bits = total > 0 ? (double)u.payload_bytes * 8.0 / ((double)total * d.n_kv_heads * d.n_layers * 2.0 * kD) : 0.0;
+    *usage = u;
+    delete[] counts;
+    return KVQ_OK;
+}
+
 extern "C" int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t seq, uint8_t *bits_out, uint8_t *codes_out,
                                 uint16_t *meta_out, int64_t max_tokens, void *stream)
 {

@@ -477,3 +477,35 @@ def test_fused_append_attention_equals_the_oracle_and_the_two_call_path(Hq, Hkv,
             for s in range(B):
                 assert_export_equals(cache, l, s, ocs[l])         # what the fused kernel stored is bit-exact
         assert cache.status()[0] == 0
+
+
+def test_cache_usage_reports_expected_bits_and_bytes_like_the_oracle_accounting():
+    say("cache usage: E[b], stored bits per element, payload and page bytes")
+    import oracle
+    B, Hq, Hkv, L = 3, 6, 3, 2
+    lens = [700, 0, 41]
+    cache = kvq.Cache(L, B, Hq, Hkv, 1024)
+    assert cache.usage()["expected_bits"] == 0.0 and cache.usage()["payload_bytes"] == 0
+    rng = np.random.default_rng(61)
+    all_bits = []
+    for s_, n in enumerate(lens):
+        if n == 0:
+            continue
+        bits = rng.choice([2, 4, 8, 16], (1, n), p=[0.5, 0.25, 0.15, 0.1]).astype(np.uint8)
+        all_bits.append(bits[0])
+        ids = torch.tensor([s_], dtype=torch.int32, device=dev())
+        for l in range(L):
+            K, V = make_kv((1, n, Hkv, 64), 50 + s_ + 10 * l), make_kv((1, n, Hkv, 64), 60 + s_ + 10 * l)
+            kvq.kvq_append(cache, l, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()) if l == 0 else None, ids, 1, n)
+    u = cache.usage()
+    cat = np.concatenate(all_bits)
+    eb, ef, nb = oracle.accounting(cat, Hkv, L)
+    assert u["tokens"] == [int((cat == w).sum()) for w in (2, 4, 8, 16)]
+    assert u["expected_bits"] == pytest.approx(eb, rel=1e-14) and u["effective_bits"] == pytest.approx(ef, rel=1e-14)
+    assert u["payload_bytes"] == nb
+    # pages: one per started 256 slots of a class and sequence; a page holds 256 tokens of every layer and kv-head
+    pt = 256
+    pages = [sum(-(-int((b == w).sum()) // pt) for b in all_bits) for w in (2, 4, 8, 16)]
+    assert u["pages_in_use"] == pages
+    assert u["page_bytes_in_use"] == sum(p * pt * per * Hkv * L for p, per in zip(pages, (40, 72, 136, 256)))
+    assert u["page_bytes_in_use"] >= u["payload_bytes"]

@@ -293,3 +293,29 @@ def test_threaded_append_wrapper_equals_the_plain_loop():
     a = oracle.append(K.view(np.uint16), V.view(np.uint16), bits)
     b = oracle.append(K.view(np.uint16), V.view(np.uint16), bits, parallel=True)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_accounting_closed_forms_and_the_bytes_the_canonical_arrays_really_hold():
+    # uniform widths: E[b] = b; stored bits per element = b + 32/64 for b < 16 (an fp16 scale and minimum per 64 codes)
+    for b, eff, per in ((2, 2.5, 40), (4, 4.5, 72), (8, 8.5, 136), (16, 16.0, 256)):
+        eb, ef, nb = oracle.accounting(np.full(1000, b, np.uint8), Hkv=3, layers=5)
+        assert eb == b and ef == eff and nb == 1000 * per * 3 * 5
+    # the 50/25/15/10 mix of the 1.7B-shaped workload: E[b] = 0.5*2 + 0.25*4 + 0.15*8 + 0.1*16 = 4.8
+    bits = np.repeat(np.array([2, 4, 8, 16], np.uint8), [500, 250, 150, 100])
+    eb, ef, nb = oracle.accounting(bits, Hkv=32, layers=24)
+    assert eb == pytest.approx(4.8, rel=1e-15)
+    assert nb == (500 * 40 + 250 * 72 + 150 * 136 + 100 * 256) * 32 * 24
+    assert ef == pytest.approx(nb * 8 / (1000 * 32 * 24 * 128), rel=1e-15)
+    # brute force against what the quantizer writes: count the bytes a canonical record actually uses
+    rng = np.random.default_rng(8)
+    bits = rng.choice([2, 4, 8, 16], 40).astype(np.uint8)
+    K = gen_vectors("normal", 40 * 2, 31).reshape(40, 2, 64)
+    V = gen_vectors("outlier", 40 * 2, 32).reshape(40, 2, 64)
+    codes, meta = oracle.append(K.view(np.uint16), V.view(np.uint16), bits)
+    used = 0
+    for t in range(40):
+        used += 2 * 2 * (64 * int(bits[t]) // 8) + (0 if bits[t] == 16 else 2 * 2 * 4)
+        assert not codes[t, :, :, 64 * int(bits[t]) // 8:].any()            # nothing beyond the code bytes
+    assert oracle.accounting(bits, Hkv=2, layers=1)[2] == used
+    with pytest.raises(ValueError):
+        oracle.accounting(np.array([2, 3], np.uint8), 1, 1)
