@@ -141,6 +141,15 @@ int kvq_cache_usage_of(kvq_cache *cache, kvq_cache_usage *usage, void *stream);
 int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t seq, uint8_t *bits_out, uint8_t *codes_out,
                      uint16_t *meta_out, int64_t max_tokens, void *stream);
 
+/* Inverse of kvq_cache_export: appends n_tokens tokens to sequence `seq` from a canonical dump (the arrays
+ * kvq_cache_export wrote, device memory), without re-quantizing anything, so that a cache can be saved, restored,
+ * or moved to another cache or device.  As with kvq_append, the call with layer == 0 does the bucket bookkeeping
+ * from `bits` (device uint8 [n_tokens]); calls with layer >= 1 place the same tokens' codes and must follow it
+ * with the same seq and n_tokens (they ignore `bits`).  A restored sequence answers kvq_decode_attn bit for bit
+ * like the original. */
+int kvq_cache_import(kvq_cache *cache, int32_t layer, int32_t seq, const uint8_t *bits, const uint8_t *codes,
+                     const uint16_t *meta, int64_t n_tokens, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Stage 1 -- token-level saliency features s_t = [H_t, R_t, V_t, C_t]  (Sec. 3.5)
  *   H_t = -sum_v p(v) ln p(v), p = Softmax(logits row)          (entropy equation)

@@ -23,7 +23,7 @@ EXPORT_REC = 128
 
 EXPORTED_SYMBOLS = (
     "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
-    "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export",
+    "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export", "kvq_cache_import",
     "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_features_controller", "kvq_controller_param_count", "kvq_controller_train_workspace",
     "kvq_controller_train_step", "kvq_append", "kvq_decode_attn_workspace",
     "kvq_decode_attn", "kvq_append_decode_attn", "kvq_probe_read", "kvq_probe_copy",
@@ -86,6 +86,7 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_cache_counts.argtypes = [vp, vp, vp]
     lib.kvq_cache_usage_of.argtypes = [vp, ctypes.POINTER(CacheUsage), vp]
     lib.kvq_cache_export.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp]
+    lib.kvq_cache_import.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp]
     lib.kvq_features_workspace.restype = sz
     lib.kvq_features_workspace.argtypes = [i64, i64]
     lib.kvq_features.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp, sz, vp]
@@ -213,6 +214,15 @@ class Cache:
         _check(load_library().kvq_cache_export(self.handle, layer, seq, bits.data_ptr(), codes.data_ptr(),
                                                meta.data_ptr(), max_tokens, _stream(stream)))
         return bits, codes, meta
+
+
+def kvq_cache_import(cache: Cache, layer: int, seq: int, bits: Optional[torch.Tensor], codes: torch.Tensor, meta: torch.Tensor,
+                     n_tokens: int, stream=None) -> None:
+    """Appends n_tokens tokens to `seq` from the arrays Cache.export returned (device tensors)."""
+    assert codes.is_cuda and meta.is_cuda and codes.is_contiguous() and meta.is_contiguous()
+    assert codes.numel() >= n_tokens * cache.Hkv * 2 * EXPORT_REC and meta.numel() >= n_tokens * cache.Hkv * 4
+    _check(load_library().kvq_cache_import(cache.handle, layer, seq, _ptr(bits, torch.uint8, "bits"), codes.data_ptr(),
+                                           meta.data_ptr(), n_tokens, _stream(stream)))
 
 
 def kvq_features_workspace(n: int, vocab: int) -> int:

@@ -148,13 +148,13 @@ __global__ void k_free_seqs(CacheView cv, const int32_t *seq_ids, int n_seq)
 // slots of a long prompt 1024 tokens per pass.
 constexpr int kAdvanceMaxWaves = 16;
 
-__global__ __launch_bounds__(64 * kAdvanceMaxWaves) void k_advance(CacheView cv, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T)
+__global__ __launch_bounds__(64 * kAdvanceMaxWaves) void k_advance(CacheView cv, const uint8_t *bits, const int32_t *seq_ids, int seq0, int n_seq, int T)
 {
     __shared__ int wave_count[kAdvanceMaxWaves][kClasses];
     const int si = blockIdx.x;
     if (si >= n_seq) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
-    const int seq = seq_ids ? seq_ids[si] : si;
+    const int seq = seq_ids ? seq_ids[si] : seq0 + si;
     if (seq < 0 || seq >= cv.max_seqs) {
         if (tid == 0) atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL);
         return;
@@ -469,6 +469,47 @@ __global__ __launch_bounds__(256) void k_export(CacheView cv, int layer, int seq
     if (h == 0 && lane == 0) bits_out[t] = (uint8_t)b;
 }
 
+// Inverse of k_export for tokens that the bookkeeping kernel has just logged: one wavefront per (token, kv-head),
+// lane = element.  The codes of the canonical record are moved into the cache's word layout, nothing is re-quantized.
+__global__ __launch_bounds__(256) void k_import(CacheView cv, int layer, int seq, const uint8_t *codes_in, const uint16_t *meta_in,
+                                                long long T)
+{
+    const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (wave >= T * cv.Hkv) return;
+    const int lastT = cv.last_T[seq];
+    if ((long long)lastT != T) return;                            // the bookkeeping call skipped this sequence
+    const int h = (int)(wave % cv.Hkv);
+    const long long t = wave / cv.Hkv;
+    const int len = cv.counts[(size_t)seq * 5 + 4];
+    const size_t pos = (size_t)seq * cv.max_context + (len - lastT + t);
+    const int b = cv.bits_log[pos];
+    const int slot = cv.slot_log[pos];
+    const int cls = bits_to_class(b);
+    const int page = cv.page_table[((size_t)seq * kClasses + cls) * cv.max_pages_per_seq + slot / cv.page_tokens];
+    const int blk = (slot % cv.page_tokens) / kBlockTokens;
+    const int tok = slot % kBlockTokens;
+    uint8_t *base = cv.pool[cls] + block_offset(cv, cls, layer, page, h, blk);
+    const int meta_bytes = class_meta_bytes(cls);
+    const size_t region = (size_t)class_chunks(cls) * kBlockTokens * 16;
+    const int per = 32 / b;
+    const int w = lane / per, r = lane % per;
+    const uint32_t mask = b == 16 ? 0xffffu : ((1u << b) - 1u);
+    for (int which = 0; which < 2; ++which) {
+        const uint32_t *rec = (const uint32_t *)(codes_in + (((size_t)t * cv.Hkv + h) * 2 + which) * KVQ_EXPORT_REC);
+        const int bit = lane * b;                                 // element i at bits [i*b, i*b+b) of the record
+        const uint32_t code = (rec[bit >> 5] >> (bit & 31)) & mask;
+        const uint32_t word = group_or(code << (b * (r >> 1) + 16 * (r & 1)), per);
+        uint8_t *codes = base + meta_bytes + which * region;
+        if (r == 0) *(uint32_t *)(codes + (size_t)(w >> 2) * (kBlockTokens * 16) + tok * 16 + (w & 3) * 4) = word;
+        if (lane == 0 && cls != 3) {
+            const uint16_t *m = meta_in + (((size_t)t * cv.Hkv + h) * 2 + which) * 2;
+            uint16_t *dst = (uint16_t *)(base + tok * 8 + which * 4);
+            dst[0] = m[0]; dst[1] = m[1];
+        }
+    }
+}
+
 }  // namespace kvq
 
 using namespace kvq;
@@ -629,12 +670,39 @@ extern "C" int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t s
     return KVQ_OK;
 }
 
+extern "C" int kvq_cache_import(kvq_cache *cache, int32_t layer, int32_t seq, const uint8_t *bits, const uint8_t *codes,
+                                const uint16_t *meta, int64_t n_tokens, void *stream)
+{
+    if (!cache || !codes || !meta) { set_error("cache, codes or meta is NULL"); return KVQ_ERR_INVALID_ARG; }
+    const kvq_cache_desc &d = cache->desc;
+    if (layer < 0 || layer >= d.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
+    if (seq < 0 || seq >= d.max_seqs) { set_error("seq %d out of range", seq); return KVQ_ERR_INVALID_ARG; }
+    if (n_tokens < 0) { set_error("n_tokens negative"); return KVQ_ERR_INVALID_ARG; }
+    if (n_tokens > d.max_context) { set_error("n_tokens %lld exceeds max_context", (long long)n_tokens); return KVQ_ERR_CAPACITY; }
+    if (layer == 0 && !bits) { set_error("bits is NULL on the bookkeeping call (layer 0)"); return KVQ_ERR_INVALID_ARG; }
+    if (n_tokens == 0) return KVQ_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (layer == 0) {
+        int waves = (int)((n_tokens + 63) / 64);
+        if (waves > kAdvanceMaxWaves) waves = kAdvanceMaxWaves;
+        hipLaunchKernelGGL(k_advance, dim3(1), dim3(64 * waves), 0, st, cache->view, bits, (const int32_t *)nullptr, seq, 1, (int)n_tokens);
+        KVQ_HIP(hipGetLastError());
+        cache->len_bound += n_tokens;
+        if (cache->len_bound > d.max_context) cache->len_bound = d.max_context;
+    }
+    const long long waves = (long long)n_tokens * d.n_kv_heads;
+    hipLaunchKernelGGL(k_import, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer, seq, codes, meta,
+                       (long long)n_tokens);
+    KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+}
+
 // launches the bookkeeping kernel for T new tokens per listed sequence (internal; arguments already validated)
 int kvq_append_bookkeeping(kvq_cache *cache, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T, void *stream)
 {
     int waves = (T + 63) / 64;
     if (waves > kAdvanceMaxWaves) waves = kAdvanceMaxWaves;
-    hipLaunchKernelGGL(k_advance, dim3(n_seq), dim3(64 * waves), 0, (hipStream_t)stream, cache->view, bits, seq_ids, n_seq, T);
+    hipLaunchKernelGGL(k_advance, dim3(n_seq), dim3(64 * waves), 0, (hipStream_t)stream, cache->view, bits, seq_ids, 0, n_seq, T);
     KVQ_HIP(hipGetLastError());
     cache->len_bound += T;
     if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;

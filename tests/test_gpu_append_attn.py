@@ -509,3 +509,58 @@ def test_cache_usage_reports_expected_bits_and_bytes_like_the_oracle_accounting(
     assert u["pages_in_use"] == pages
     assert u["page_bytes_in_use"] == sum(p * pt * per * Hkv * L for p, per in zip(pages, (40, 72, 136, 256)))
     assert u["page_bytes_in_use"] >= u["payload_bytes"]
+
+
+def test_export_import_roundtrip_restores_a_cache_bit_for_bit():
+    say("save / restore: export every (layer, sequence), import into a fresh cache, compare exports and attention")
+    B, Hq, Hkv, L = 3, 6, 3, 2
+    lens = [333, 0, 70]
+    rng = np.random.default_rng(71)
+    src = kvq.Cache(L, B, Hq, Hkv, 512)
+    ocs = [OracleCache(B, Hkv) for _ in range(L)]
+    for s_, n in enumerate(lens):
+        if n == 0:
+            continue
+        bits = rng.choice([2, 4, 8, 16], (1, n)).astype(np.uint8)
+        ids = torch.tensor([s_], dtype=torch.int32, device=dev())
+        for l in range(L):
+            K, V = make_kv((1, n, Hkv, 64), 150 + s_ + 10 * l), make_kv((1, n, Hkv, 64), 160 + s_ + 10 * l)
+            kvq.kvq_append(src, l, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()) if l == 0 else None, ids, 1, n)
+            ocs[l].append(s_, K[0], V[0], bits[0])
+    # restore into another cache, sequences in another order and into other slots (0 -> 2, 2 -> 0)
+    dst = kvq.Cache(L, B, Hq, Hkv, 512)
+    place = {0: 2, 2: 0}
+    for s_ in (2, 0):
+        n = lens[s_]
+        for l in range(L):
+            bits_d, codes_d, meta_d = src.export(l, s_, n)
+            kvq.kvq_cache_import(dst, l, place[s_], bits_d if l == 0 else None, codes_d, meta_d, n)
+    torch.cuda.synchronize()
+    assert dst.status()[0] == 0
+    for l in range(L):
+        for s_ in (0, 2):
+            for x, y in zip(src.export(l, s_, lens[s_]), dst.export(l, place[s_], lens[s_])):
+                assert torch.equal(x, y)
+            # the restored sequence equals the oracle's canonical arrays, too
+            oc = OracleCache(B, Hkv)
+            oc.bits[place[s_]], oc.codes[place[s_]], oc.meta[place[s_]] = ocs[l].bits[s_], ocs[l].codes[s_], ocs[l].meta[s_]
+            assert_export_equals(dst, l, place[s_], oc)
+    # attention on the restored cache: bit for bit the original's
+    q = make_kv((B, Hq, 64), 170, outlier=False)
+    ws = torch.empty(kvq.kvq_decode_attn_workspace(src, B), dtype=torch.uint8, device=dev())
+    for l in range(L):
+        o1 = torch.zeros((B, Hq, 64), dtype=torch.float32, device=dev())
+        o2 = torch.zeros_like(o1)
+        kvq.kvq_decode_attn(src, l, gpu_f16(q), torch.tensor([0, 1, 2], dtype=torch.int32, device=dev()), B, o1, ws)
+        kvq.kvq_decode_attn(dst, l, gpu_f16(q), torch.tensor([2, 1, 0], dtype=torch.int32, device=dev()), B, o2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2)
+    # a restored sequence keeps growing like any other
+    K, V = make_kv((1, 1, Hkv, 64), 180), make_kv((1, 1, Hkv, 64), 181)
+    one = torch.tensor([[8]], dtype=torch.uint8, device=dev())
+    kvq.kvq_append(dst, 0, gpu_f16(K), gpu_f16(V), one, torch.tensor([2], dtype=torch.int32, device=dev()), 1, 1)
+    assert int(dst.counts()[2, 4]) == lens[0] + 1
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_cache_import(dst, 0, 1, None, codes_d, meta_d, 5)        # layer 0 needs the widths
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_cache_import(dst, 0, 7, bits_d, codes_d, meta_d, 5)      # no such sequence slot
