@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+EVENT_EVERY = 5        # timed steps between two steps whose launches are bracketed by events
 
 
 def parse():
@@ -234,7 +235,9 @@ def main():
             if replay is not None:
                 replay()
             else:
-                step(s, events)
+                # event brackets on every EVENT_EVERY-th timed step only: an event record costs ~3 us of device time, and
+                # bracketing every launch of every step would inflate the step by 5 %
+                step(s, events and (s - warm_steps) % EVENT_EVERY == EVENT_EVERY // 2)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         gc.enable()
@@ -251,7 +254,7 @@ def main():
         if events:
             attn_us = [a0.elapsed_time(a1) * 1e3 for a0, a1 in ev_pairs]
             if args.trace_steps:
-                per = np.array(attn_us).reshape(timed_steps, L).mean(axis=1)
+                per = np.array(attn_us).reshape(-1, L).mean(axis=1)
                 log("[bench] attn us/layer by step: " + " ".join("%.0f" % x for x in per))
             res["attn_us_per_layer"] = float(np.mean(attn_us))
             res["attn_us_min"] = float(np.min(attn_us))
