@@ -100,7 +100,7 @@ __host__ __device__ constexpr size_t mfma_lds_floats(int T1, int T2)
 }
 
 template <int T1, int T2>       // hidden widths 32*T1 and 32*T2; T2 == 0: one hidden layer
-__global__ __launch_bounds__(256) void k_mlp_mfma(MlpArgs A, long long ntiles)
+__global__ __launch_bounds__(256, 2) void k_mlp_mfma(MlpArgs A, long long ntiles)
 {
     extern __shared__ float lds[];
     constexpr int TL = T2 ? T2 : T1;
@@ -121,11 +121,28 @@ __global__ __launch_bounds__(256) void k_mlp_mfma(MlpArgs A, long long ntiles)
         b1p[idx] = A.b[0][32 * it + (r >> 2) * 8 + hh * 4 + (r & 3)];
     }
     if constexpr (T2 > 0) {
+        // W2 is read in memory order, four consecutive inputs per load and eight loads in flight per thread; each
+        // element then goes to the (tile, k-step, lane) slot that the MFMA loop reads it from
         const float *W2 = A.W[1];
-        for (int idx = tid; idx < T2 * T1 * 1024; idx += 256) {
-            const int l = idx & 63, r = (idx >> 6) & 15, rest = idx >> 10;
-            const int it = rest % T1, ot = rest / T1;
-            w2p[idx] = W2[(size_t)(32 * ot + (l & 31)) * (32 * T1) + 32 * it + (r >> 2) * 8 + (l >> 5) * 4 + (r & 3)];
+        constexpr int K = 32 * T1, N4 = T2 * 32 * K / 4;
+        for (int e0 = tid; e0 < N4; e0 += 8 * 256) {
+            f32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e4 = e0 + u * 256;
+                v[u] = ((const f32x4 *)W2)[e4 < N4 ? e4 : e0];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e4 = e0 + u * 256;
+                if (e4 < N4) {
+                    const int j = (e4 * 4) / K, i = (e4 * 4) % K;          // output unit, first of four inputs
+                    const int ot = j >> 5, it = i >> 5, rem = i & 31;
+                    const int r0 = (rem >> 3) * 4, l = ((rem >> 2) & 1) * 32 + (j & 31);
+                    float *d = w2p + ((ot * T1 + it) * 16 + r0) * 64 + l;
+                    d[0] = v[u][0]; d[64] = v[u][1]; d[128] = v[u][2]; d[192] = v[u][3];
+                }
+            }
         }
         for (int idx = tid; idx < T2 * 32; idx += 256) {
             const int hh = idx & 1, r = (idx >> 1) & 15, it = idx >> 5;
@@ -156,41 +173,83 @@ __global__ __launch_bounds__(256) void k_mlp_mfma(MlpArgs A, long long ntiles)
                 h1[it] = __builtin_amdgcn_mfma_f32_32x32x2f32(w1p[(it * 2 + s) * 64 + lane], xb[s], h1[it], 0, 0, 0);
 #pragma unroll
             for (int r = 0; r < 16; ++r) h1[it][r] = fmaxf(h1[it][r], 0.f);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        f32x16 h2[T2 ? T2 : 1];
+        // Second hidden layer two output tiles at a time, each pair folded into the 4-output layer as soon as it is
+        // complete: 32 accumulator registers live instead of 16 * T2, which leaves room for two waves per SIMD (one
+        // wave's MFMAs cover the other's LDS reads and vector work).  The 4-output layer is a short vector dot product:
+        // each lane sums over the units it holds, the two halves of a token are added at the end.
+        float o[4] = {0.f, 0.f, 0.f, 0.f};
         if constexpr (T2 > 0) {
+            constexpr int GO = T2 >= 2 ? 2 : 1;
 #pragma unroll
-            for (int ot = 0; ot < T2; ++ot)
+            for (int o0 = 0; o0 < T2; o0 += GO) {
+                f32x16 h2[GO];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) h2[ot][r] = b2p[(ot * 16 + r) * 2 + hh];
+                for (int g = 0; g < GO; ++g)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) h2[g][r] = b2p[((o0 + g) * 16 + r) * 2 + hh];
+                // k-steps in chunks of four; the next chunk's A operands are read from LDS while this chunk's MFMAs run, and
+                // a scheduling fence per chunk keeps the compiler from hoisting every LDS read of the layer to the top
+                constexpr int NCH = T1 * 4;
+                float a_cur[4][GO], a_nxt[4][GO];
+#pragma unroll
+                for (int s_ = 0; s_ < 4; ++s_)
+#pragma unroll
+                    for (int g = 0; g < GO; ++g) a_cur[s_][g] = w2p[((o0 + g) * T1 * 16 + s_) * 64 + lane];
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    if (c + 1 < NCH) {
+#pragma unroll
+                        for (int s_ = 0; s_ < 4; ++s_)
+#pragma unroll
+                            for (int g = 0; g < GO; ++g) a_nxt[s_][g] = w2p[((o0 + g) * T1 * 16 + (c + 1) * 4 + s_) * 64 + lane];
+                    }
+#pragma unroll
+                    for (int s_ = 0; s_ < 4; ++s_) {
+                        const int st_ = c * 4 + s_;                 // k-step = (input tile, register)
+#pragma unroll
+                        for (int g = 0; g < GO; ++g)
+                            h2[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[s_][g], h1[st_ / 16][st_ % 16], h2[g], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int s_ = 0; s_ < 4; ++s_)
+#pragma unroll
+                        for (int g = 0; g < GO; ++g) a_cur[s_][g] = a_nxt[s_][g];
+                }
+#pragma unroll
+                for (int g = 0; g < GO; ++g)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float h = fmaxf(h2[g][r], 0.f);
+                        const f32x4 w = *(const f32x4 *)(wfp + (((o0 + g) * 16 + r) * 2 + hh) * 4);
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) o[k] = fmaf(h, w[k], o[k]);
+                    }
+            }
+        } else {
 #pragma unroll
             for (int it = 0; it < T1; ++it)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
+                for (int r = 0; r < 16; ++r) {
+                    const f32x4 w = *(const f32x4 *)(wfp + ((it * 16 + r) * 2 + hh) * 4);
 #pragma unroll
-                    for (int ot = 0; ot < T2; ++ot)
-                        h2[ot] = __builtin_amdgcn_mfma_f32_32x32x2f32(w2p[((ot * T1 + it) * 16 + r) * 64 + lane], h1[it][r], h2[ot], 0, 0, 0);
-#pragma unroll
-            for (int ot = 0; ot < T2; ++ot)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) h2[ot][r] = fmaxf(h2[ot][r], 0.f);
+                    for (int k = 0; k < 4; ++k) o[k] = fmaf(h1[it][r], w[k], o[k]);
+                    if (r % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+                }
         }
-        // 4-output layer: each lane sums over the 16*TL units it holds, the two halves of a token are then added
-        float o[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int it = 0; it < TL; ++it)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const f32x4 w = *(const f32x4 *)(wfp + ((it * 16 + r) * 2 + hh) * 4);
-                float h;
-                if constexpr (T2 > 0) h = h2[it][r]; else h = h1[it][r];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) o[k] = fmaf(h, w[k], o[k]);
-            }
 #pragma unroll
         for (int k = 0; k < 4; ++k) o[k] = (o[k] + __shfl_xor(o[k], 32, 64)) + bfp[k];
         if (live && hh == 0) emit_decision(o, 4, row, A.bits, A.logits);
     }
+}
+
+static int env_per_cu()
+{
+    const char *e = getenv("KVQ_CONTROLLER_WG_PER_CU");
+    const int v = e ? atoi(e) : 2;
+    return v >= 1 && v <= 4 ? v : 2;
 }
 
 template <int T1, int T2> static int launch_mfma(const MlpArgs &A, hipStream_t st)
@@ -210,8 +269,10 @@ template <int T1, int T2> static int launch_mfma(const MlpArgs &A, hipStream_t s
         KVQ_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (n_cu < 1) n_cu = 1;
     }
+    // two workgroups per compute unit (two waves per SIMD: one wave's MFMAs cover the other's LDS reads and vector work)
+    const int per_cu = env_per_cu();
     long long blocks = (ntiles + 3) / 4;
-    if (blocks > n_cu) blocks = n_cu;
+    if (blocks > (long long)per_cu * n_cu) blocks = (long long)per_cu * n_cu;
     hipLaunchKernelGGL((k_mlp_mfma<T1, T2>), dim3((unsigned)blocks), dim3(256), lds, st, A, ntiles);
     return KVQ_OK;
 }
