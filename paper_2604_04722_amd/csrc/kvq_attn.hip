@@ -686,18 +686,21 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     // is not read from the cache.  It is quantized in registers from k_new / v_new, joins the softmax as one extra
     // partial result, and the workgroup with s == 0, g == 0 stores it for later steps.
     bool has_new = false;
-    int new_bits = 16, new_cls = 3, new_slot = 0;
-    if (P.k_new != nullptr && seq_ok && cv.last_T[seq] == 1) {
-        const size_t pos = (size_t)seq * cv.max_context + (cv.counts[(size_t)seq * 5 + 4] - 1);
-        new_bits = cv.bits_log[pos];
-        new_slot = cv.slot_log[pos];
-        new_cls = bits_to_class(new_bits);
-        has_new = true;
+    int new_bits = 16, new_cls = 3, new_slot = 0, new_page = 0;
+    if (P.k_new != nullptr && seq_ok) {
+        const int4 rec = *(const int4 *)(cv.last_rec + (size_t)seq * 4);     // {last_T, bits, slot, page} of the newest token
+        if (rec.x == 1) {
+            new_bits = rec.y;
+            new_slot = rec.z;
+            new_page = rec.w;
+            new_cls = bits_to_class(new_bits);
+            has_new = true;
+        }
     }
     float new_score = -INFINITY, new_v = 0.f;
     if (has_new && s == 0 && wave == 0) {
         const size_t src = ((size_t)si * cv.Hkv + kvh) * kD + lane;
-        const int page = cv.page_table[((size_t)seq * kClasses + new_cls) * cv.max_pages_per_seq + new_slot / cv.page_tokens];
+        const int page = new_page;
         const int blk = (new_slot % cv.page_tokens) / kBlockTokens, tok = new_slot % kBlockTokens;
         uint8_t *base = cv.pool[new_cls] + block_offset(cv, new_cls, P.layer, page, kvh, blk);
         const size_t region = (size_t)class_chunks(new_cls) * kBlockTokens * 16;

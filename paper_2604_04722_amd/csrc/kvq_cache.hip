@@ -62,6 +62,8 @@ static size_t plan_arena(const kvq_cache_desc &d, CacheView *v, uint8_t *base)
     off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs * 5);
     cv.last_T = (int32_t *)(base + off);
     off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs);
+    cv.last_rec = (int32_t *)(base + off);
+    off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs * 4);
     cv.bits_log = base + off;
     off = align256(off + (size_t)d.max_seqs * d.max_context);
     cv.slot_log = (int32_t *)(base + off);
@@ -114,6 +116,7 @@ __global__ void k_reset(CacheView cv)
     }
     for (int64_t i = tid; i < (int64_t)cv.max_seqs * 5; i += stride) cv.counts[i] = 0;
     for (int64_t i = tid; i < cv.max_seqs; i += stride) cv.last_T[i] = 0;
+    for (int64_t i = tid; i < (int64_t)cv.max_seqs * 4; i += stride) cv.last_rec[i] = 0;
     if (tid < kClasses) cv.free_top[tid] = cv.n_pages[tid];
     if (tid == 0) *cv.flags = 0;
 }
@@ -138,7 +141,7 @@ __global__ void k_free_seqs(CacheView cv, const int32_t *seq_ids, int n_seq)
     }
     __syncthreads();
     if (threadIdx.x < 5) cnt[threadIdx.x] = 0;
-    if (threadIdx.x == 0) cv.last_T[seq] = 0;
+    if (threadIdx.x == 0) { cv.last_T[seq] = 0; cv.last_rec[(size_t)seq * 4] = 0; }
 }
 
 // Bucket bookkeeping for T new tokens of each listed sequence: one workgroup of 1 to 16 wavefronts per sequence walks
@@ -165,11 +168,13 @@ __global__ __launch_bounds__(64 * kAdvanceMaxWaves) void k_advance(CacheView cv,
         if (tid == 0) {
             atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL);
             cv.last_T[seq] = 0;
+            cv.last_rec[(size_t)seq * 4] = 0;
         }
         return;
     }
     int cc[kClasses] = {cnt[0], cnt[1], cnt[2], cnt[3]};
     bool bad = false;
+    int newest_b = 0, newest_cls = 0, newest_slot = -1;            // set by the thread that handles the call's last token
     for (int t0 = 0; t0 < T; t0 += 64 * n_waves) {
         const int t = t0 + tid;
         const bool valid = t < T;
@@ -210,6 +215,7 @@ __global__ __launch_bounds__(64 * kAdvanceMaxWaves) void k_advance(CacheView cv,
             const size_t pos = (size_t)seq * cv.max_context + len + t;
             cv.bits_log[pos] = (uint8_t)b;
             cv.slot_log[pos] = slot;
+            if (t == T - 1) { newest_b = b; newest_cls = cls; newest_slot = slot; }
         }
 #pragma unroll
         for (int c = 0; c < kClasses; ++c) cc[c] += total[c];
@@ -220,6 +226,13 @@ __global__ __launch_bounds__(64 * kAdvanceMaxWaves) void k_advance(CacheView cv,
         cnt[0] = cc[0]; cnt[1] = cc[1]; cnt[2] = cc[2]; cnt[3] = cc[3];
         cnt[4] = len + T;
         cv.last_T[seq] = T;
+    }
+    if (newest_slot >= 0) {
+        // the page-table entry may have been written by another thread of this workgroup: the barriers of the loop
+        // above order that write before this read
+        const int page = cv.page_table[((size_t)seq * kClasses + newest_cls) * cv.max_pages_per_seq + newest_slot / cv.page_tokens];
+        int32_t *rec = cv.last_rec + (size_t)seq * 4;
+        rec[0] = T; rec[1] = newest_b; rec[2] = newest_slot; rec[3] = page;
     }
 }
 
@@ -240,14 +253,22 @@ __global__ __launch_bounds__(256) void k_append_write(CacheView cv, int layer, c
     const int L = layer < 0 ? li : layer;
     const int seq = seq_ids ? seq_ids[si] : si;
     if (seq < 0 || seq >= cv.max_seqs) return;
-    const int lastT = cv.last_T[seq];
-    if (lastT != T || t >= lastT) return;                          // the bookkeeping call skipped this sequence
-    const int len = cv.counts[(size_t)seq * 5 + 4];
-    const size_t pos = (size_t)seq * cv.max_context + (len - lastT + t);
-    const int b = cv.bits_log[pos];
-    const int slot = cv.slot_log[pos];
+    int b, slot, page;
+    if (T == 1) {
+        // the decode step: everything about the new token in one 16-byte read
+        const int4 rec = *(const int4 *)(cv.last_rec + (size_t)seq * 4);
+        if (rec.x != 1) return;                                    // the bookkeeping call skipped this sequence
+        b = rec.y; slot = rec.z; page = rec.w;
+    } else {
+        const int lastT = cv.last_T[seq];
+        if (lastT != T || t >= lastT) return;
+        const int len = cv.counts[(size_t)seq * 5 + 4];
+        const size_t pos = (size_t)seq * cv.max_context + (len - lastT + t);
+        b = cv.bits_log[pos];
+        slot = cv.slot_log[pos];
+        page = cv.page_table[((size_t)seq * kClasses + bits_to_class(b)) * cv.max_pages_per_seq + slot / cv.page_tokens];
+    }
     const int cls = bits_to_class(b);
-    const int page = cv.page_table[((size_t)seq * kClasses + cls) * cv.max_pages_per_seq + slot / cv.page_tokens];
     const int blk = (slot % cv.page_tokens) / kBlockTokens;
     const int tok = slot % kBlockTokens;
     uint8_t *base = cv.pool[cls] + block_offset(cv, cls, L, page, h, blk);

@@ -49,6 +49,8 @@ struct CacheView {
     int32_t *page_table;               // [max_seqs][4][max_pages_per_seq]
     int32_t *counts;                   // [max_seqs][5]: tokens per class, total length
     int32_t *last_T;                   // [max_seqs]: tokens accepted by the latest bookkeeping append
+    int32_t *last_rec;                 // [max_seqs][4]: {last_T, bits, slot, page} of the newest token, one 16-byte read
+                                       // for the single-token writers instead of four dependent ones
     uint8_t *bits_log;                 // [max_seqs][max_context]
     int32_t *slot_log;                 // [max_seqs][max_context]
     int32_t *free_stack[kClasses];     // [n_pages[c]] ids of free pages
@@ -119,6 +121,7 @@ __device__ __forceinline__ void advance_one_token(const CacheView &cv, int seq, 
     if ((int64_t)len + 1 > (int64_t)cv.max_context) {
         atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL);
         cv.last_T[seq] = 0;
+        cv.last_rec[(size_t)seq * 4] = 0;
         return;
     }
     if (b != 2 && b != 4 && b != 8 && b != 16) { atomicOr(cv.flags, KVQ_FLAG_BAD_BITS); b = 16; }
@@ -142,6 +145,9 @@ __device__ __forceinline__ void advance_one_token(const CacheView &cv, int seq, 
     cnt[c] = slot + 1;
     cnt[4] = len + 1;
     cv.last_T[seq] = 1;
+    const int page_now = cv.page_table[((size_t)seq * kClasses + c) * cv.max_pages_per_seq + slot / cv.page_tokens];
+    int32_t *rec = cv.last_rec + (size_t)seq * 4;
+    rec[0] = 1; rec[1] = b; rec[2] = slot; rec[3] = page_now;
 }
 
 }  // namespace kvq
