@@ -80,6 +80,7 @@ def main():
     else:
         Ws, bs = wl.xavier_mlp(cfg)
     mlp = kvq.MlpWeights([torch.from_numpy(w).to(dev) for w in Ws], [torch.from_numpy(b).to(dev) for b in bs])
+    rule = kvq.make_rule(*wl.calibrated_rule(cfg)) if cfg.bits_kind == "controller" else None
 
     def prefill_bits(variant):
         T = int(lens0.max())
@@ -87,6 +88,11 @@ def main():
             return np.full((B, T), 4, np.uint8)
         if variant == "fp16":
             return np.full((B, T), 16, np.uint8)
+        if variant == "rule":
+            f = torch.from_numpy(np.concatenate([wl.bulk_features(cfg, T, chunk=100 + s) for s in range(B)])).to(dev)
+            b = torch.empty(B * T, dtype=torch.uint8, device=dev)
+            kvq.kvq_rule_policy(f, rule, b)
+            return b.view(B, T).cpu().numpy()
         if cfg.bits_kind == "uniform":
             return wl.uniform_bits(cfg, B, T)
         if cfg.bits_kind == "runs":
@@ -164,7 +170,7 @@ def main():
         counts_d = torch.from_numpy(counts_np).to(dev)
         totals_d = torch.tensor([N, Vobs], dtype=torch.int64, device=dev)
         fixed = None
-        if variant != "mixed":
+        if variant in ("static4", "fp16"):
             fixed = torch.full((B, 1), 4 if variant == "static4" else 16, dtype=torch.uint8, device=dev)
         ev_pairs, stage_ev = [], []
         base_step = done_steps.get(id(cache), 0)
@@ -189,7 +195,10 @@ def main():
                 kvq.kvq_features(step_logits[s % n_steps], step_ids[s % n_steps], counts_d, totals_d, True, step_len[base_step + s], Hq, feats, fws, sum_p2=sum_p2)
                 if record:
                     e1 = torch.cuda.Event(enable_timing=True); e1.record()
-                kvq.kvq_controller(feats, mlp, step_bits.view(-1))
+                if variant == "rule":
+                    kvq.kvq_rule_policy(feats, rule, step_bits.view(-1))
+                else:
+                    kvq.kvq_controller(feats, mlp, step_bits.view(-1))
                 if record:
                     e2 = torch.cuda.Event(enable_timing=True); e2.record()
                     stage_ev.append((e0, e1, e2))
@@ -459,7 +468,7 @@ def main():
     # ---------------- comparison caches built by the same library ------------------------------------
     compare = {}
     if not args.no_compare:
-        for variant in ("static4", "fp16"):
+        for variant in ("static4", "fp16") + (("rule",) if rule is not None else ()):
             c2, r2 = run_variant(variant, max(3, args.steps // 4), 2, not args.no_events)
             c2.destroy()
             del c2

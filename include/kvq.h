@@ -195,6 +195,22 @@ int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp, uint8_t *b
                    float *logits_out, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Comparison policy: a stand-in for the "rule-based dynamic KV policy" baseline of Sec. 4.  The paper only says that
+ * baseline uses hand-crafted heuristics and never states them, so this rule is NOT the paper's: an importance score
+ * linear in the features, cut by three ascending thresholds,
+ *   score = bias + sum_i w[i] * s[i],   class = #{k : score > thr[k]},   bits = {2,4,8,16}[class]
+ * (fp32, the products added in feature order).  Same role and output as kvq_controller.
+ *   feats      device fp32 [n][4];  rule  host struct (thr ascending);  bits_out  device uint8 [n]
+ *   score_out  device fp32 [n] or NULL
+ * ------------------------------------------------------------------------------------------- */
+typedef struct kvq_rule {
+    float w[4];
+    float bias;
+    float thr[3];
+} kvq_rule;
+int kvq_rule_policy(const float *feats, int64_t n, const kvq_rule *rule, uint8_t *bits_out, float *score_out, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Stages 1 + 2 in one launch, for the decode step (Sec. 3.4: saliency profiling, then the controller's decision,
  * then the token's place in the mixed-precision cache): the features of kvq_features in its sum_p2 form, the
  * decision of kvq_controller on them, and -- if `cache` is given -- the bucket bookkeeping that

@@ -240,3 +240,15 @@ def accounting(bits, Hkv: int, layers: int):
     if rc != 0:
         raise ValueError("illegal bit width")
     return eb.value, ef.value, nb.value
+
+
+def rule_policy(feats, w, bias: float, thr):
+    """(bits, score) of the stand-in rule-based policy: score = bias + w . s, class = number of thresholds exceeded."""
+    f = _c(feats, np.float32)
+    wv, tv = _c(w, np.float32), _c(thr, np.float32)
+    assert f.ndim == 2 and f.shape[1] == 4 and wv.shape == (4,) and tv.shape == (3,) and np.all(np.diff(tv) >= 0)
+    n = f.shape[0]
+    bits = np.zeros(n, np.uint8)
+    score = np.zeros(n, np.float64)
+    lib().kvq_oracle_rule_policy(_p(f), ctypes.c_int64(n), _p(wv), ctypes.c_float(bias), _p(tv), _p(bits), _p(score))
+    return bits, score

@@ -472,3 +472,24 @@ int kvq_oracle_accounting(const uint8_t *bits, int64_t n, int Hkv, int layers, d
     *payload_bytes = bytes;
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------ */
+/* Stand-in for the "rule-based dynamic KV policy" baseline of Sec. 4 (the paper only says it   */
+/* uses hand-crafted heuristics; its rules are not given, so this rule is this build's own):    */
+/* an importance score linear in the features, cut by three ascending thresholds.               */
+/*   score = bias + sum_i w_i s_i (fp64 on the fp32 inputs), class = #{k : score > thr_k},      */
+/*   bits = {2,4,8,16}[class].                                                                  */
+/* ------------------------------------------------------------------------------------------ */
+void kvq_oracle_rule_policy(const float *feats, int64_t n, const float *w, float bias, const float *thr, uint8_t *bits,
+                            double *score)
+{
+    static const uint8_t index_to_bit[4] = {2, 4, 8, 16};
+    for (int64_t t = 0; t < n; ++t) {
+        double u = (double)bias;
+        for (int i = 0; i < 4; ++i) u += (double)w[i] * (double)feats[t * 4 + i];
+        int cls = 0;
+        for (int k = 0; k < 3; ++k) if (u > (double)thr[k]) cls += 1;
+        bits[t] = index_to_bit[cls];
+        if (score) score[t] = u;
+    }
+}

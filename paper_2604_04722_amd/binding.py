@@ -24,7 +24,7 @@ EXPORT_REC = 128
 EXPORTED_SYMBOLS = (
     "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
     "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export", "kvq_cache_import",
-    "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_features_controller", "kvq_controller_param_count", "kvq_controller_train_workspace",
+    "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_features_controller", "kvq_rule_policy", "kvq_controller_param_count", "kvq_controller_train_workspace",
     "kvq_controller_train_step", "kvq_append", "kvq_decode_attn_workspace",
     "kvq_decode_attn", "kvq_append_decode_attn", "kvq_probe_read", "kvq_probe_copy",
 )
@@ -53,6 +53,10 @@ class Mlp(ctypes.Structure):
 class CacheUsage(ctypes.Structure):
     _fields_ = [("tokens", ctypes.c_int64 * 4), ("expected_bits", ctypes.c_double), ("effective_bits", ctypes.c_double),
                 ("payload_bytes", ctypes.c_int64), ("pages_in_use", ctypes.c_int64 * 4), ("page_bytes_in_use", ctypes.c_int64)]
+
+
+class Rule(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_float * 4), ("bias", ctypes.c_float), ("thr", ctypes.c_float * 3)]
 
 
 class TrainHparams(ctypes.Structure):
@@ -93,6 +97,7 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_controller.argtypes = [vp, i64, ctypes.POINTER(Mlp), vp, vp, vp]
     lib.kvq_features_controller.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, i32, ctypes.POINTER(Mlp), vp, vp, vp, vp,
                                             vp, vp]
+    lib.kvq_rule_policy.argtypes = [vp, i64, ctypes.POINTER(Rule), vp, vp, vp]
     lib.kvq_controller_param_count.restype = i64
     lib.kvq_controller_param_count.argtypes = [ctypes.POINTER(Mlp)]
     lib.kvq_controller_train_workspace.restype = sz
@@ -282,6 +287,23 @@ def kvq_controller(feats: torch.Tensor, mlp: MlpWeights, bits_out: torch.Tensor,
     _check(load_library().kvq_controller(_ptr(feats, torch.float32, "feats"), n, ctypes.byref(mlp.c),
                                          _ptr(bits_out, torch.uint8, "bits_out"),
                                          _ptr(logits_out, torch.float32, "logits_out"), _stream(stream)))
+
+
+def make_rule(w: Sequence[float], bias: float, thr: Sequence[float]) -> Rule:
+    r = Rule()
+    for i in range(4):
+        r.w[i] = w[i]
+    r.bias = bias
+    for k in range(3):
+        r.thr[k] = thr[k]
+    return r
+
+
+def kvq_rule_policy(feats: torch.Tensor, rule: Rule, bits_out: torch.Tensor, score_out: Optional[torch.Tensor] = None,
+                    stream=None) -> None:
+    _check(load_library().kvq_rule_policy(_ptr(feats, torch.float32, "feats"), feats.shape[0], ctypes.byref(rule),
+                                          _ptr(bits_out, torch.uint8, "bits_out"), _ptr(score_out, torch.float32, "score_out"),
+                                          _stream(stream)))
 
 
 def make_train_hparams(alpha: float, beta: float, gamma: float, c: Sequence[float], q: Sequence[float], lr: float = 1e-3,

@@ -289,6 +289,23 @@ template <int T1> static int launch_mfma_t2(int t2, const MlpArgs &A, hipStream_
 
 static bool mfma_width(int w) { return w == 32 || w == 64 || w == 128; }
 
+// stand-in rule-based policy: thread = row
+struct RuleArgs { float w[4], bias, thr[3]; };
+
+__global__ __launch_bounds__(256) void k_rule_policy(const float *feats, long long n, RuleArgs R, uint8_t *bits, float *score)
+{
+    const long long row = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (row >= n) return;
+    float u = R.bias;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) u = fmaf(R.w[i], feats[row * 4 + i], u);
+    int cls = 0;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) cls += u > R.thr[k] ? 1 : 0;
+    bits[row] = (uint8_t)(2 << cls);
+    if (score) score[row] = u;
+}
+
 }  // namespace kvq
 
 using namespace kvq;
@@ -366,6 +383,24 @@ extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp,
     }
         hipLaunchKernelGGL(k_mlp_bulk, dim3((unsigned)blocks), dim3(kBulkThreads), lds, st, A, maxw);
     }
+    KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+}
+
+extern "C" int kvq_rule_policy(const float *feats, int64_t n, const kvq_rule *rule, uint8_t *bits_out, float *score_out, void *stream)
+{
+    if (n < 0) { set_error("n negative"); return KVQ_ERR_INVALID_ARG; }
+    if (!rule) { set_error("rule is NULL"); return KVQ_ERR_INVALID_ARG; }
+    if (!(rule->thr[0] <= rule->thr[1] && rule->thr[1] <= rule->thr[2])) { set_error("thresholds must ascend"); return KVQ_ERR_INVALID_ARG; }
+    if (n == 0) return KVQ_OK;
+    if (!feats || !bits_out) { set_error("feats or bits_out is NULL"); return KVQ_ERR_INVALID_ARG; }
+    if ((n + 255) / 256 > 0x7fffffffLL) { set_error("n too large for one launch"); return KVQ_ERR_CAPACITY; }
+    RuleArgs R;
+    for (int i = 0; i < 4; ++i) R.w[i] = rule->w[i];
+    R.bias = rule->bias;
+    for (int k = 0; k < 3; ++k) R.thr[k] = rule->thr[k];
+    hipLaunchKernelGGL(k_rule_policy, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, feats, (long long)n, R,
+                       bits_out, score_out);
     KVQ_HIP(hipGetLastError());
     return KVQ_OK;
 }

@@ -213,6 +213,15 @@ def calibration_path() -> str:
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "controller_calibration.json")
 
 
+def calibrated_rule(cfg: Config):
+    """(w, bias, thr) of the stand-in rule-based policy whose thresholds were set (offline, by the same script) at the
+    score quantiles that give the config's precision mix on `bulk_features`."""
+    import json
+    with open(calibration_path()) as f:
+        r = json.load(f)[str(cfg.index)]["rule"]
+    return np.asarray(r["w"], np.float32), float(r["bias"]), np.asarray(r["thr"], np.float32)
+
+
 def calibrated_mlp(cfg: Config):
     """Xavier weights with the output bias that was calibrated (offline, by a script next to the oracle) so that
     the controller's argmax reproduces the config's precision mix on `bulk_features`."""

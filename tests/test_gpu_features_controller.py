@@ -385,3 +385,27 @@ def test_a_sequence_without_an_attention_row_yet_has_zero_variance_feature():
     got2, _, _ = run_features(logits, ids, counts, N, Vobs, l2, Hq, probs=probs)
     assert np.all(got2[[1, 4], 2] == 0.0) and np.all(np.isfinite(got2))
     np.testing.assert_allclose(got2[live, 2], probs[live].var(axis=2).mean(axis=1), rtol=1e-4)
+
+
+@pytest.mark.parametrize("n", [1, 257, 100000])
+def test_rule_policy_matches_the_oracle(n):
+    say("rule-based stand-in policy n=%d" % n)
+    d = dev()
+    feats = wl.bulk_features(wl.CONFIGS[4], n, chunk=11)
+    w = np.array([1.0 / math.log(wl.VOCAB), 1.0 / 14.0, 50.0, -1.0], np.float32)
+    thr = np.array([0.1, 0.45, 0.8], np.float32)
+    want_bits, want_score = oracle.rule_policy(feats, w, 0.05, thr)
+    bits = torch.zeros(n, dtype=torch.uint8, device=d)
+    score = torch.zeros(n, dtype=torch.float32, device=d)
+    kvq.kvq_rule_policy(torch.from_numpy(feats).to(d), kvq.make_rule(w, 0.05, thr), bits, score)
+    torch.cuda.synchronize()
+    got_bits, got_score = bits.cpu().numpy(), score.cpu().numpy()
+    np.testing.assert_allclose(got_score, want_score, rtol=0, atol=4e-7 * (1.0 + np.abs(want_score).max()))
+    # identical widths except where the oracle's score lies within 1e-5 of a threshold
+    near = np.min(np.abs(want_score[:, None] - thr[None, :].astype(np.float64)), axis=1) <= 1e-5
+    assert np.array_equal(got_bits[~near], want_bits[~near])
+    assert np.all(np.abs(np.log2(got_bits[near].astype(float)) - np.log2(want_bits[near].astype(float))) <= 1)
+    if n >= 1000:
+        assert len(set(got_bits.tolist())) == 4
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_rule_policy(torch.from_numpy(feats).to(d), kvq.make_rule(w, 0.0, [0.5, 0.4, 0.9]), bits)

@@ -222,3 +222,24 @@ def test_controller_relu_is_applied_to_hidden_layers_only_and_hidden_permutation
     for W, b in zip(Ws, bs):
         lin = lin @ W.astype(np.float64).T + b
     assert np.max(np.abs(lin - logits)) > 1e-2
+
+
+def test_rule_policy_counts_the_thresholds_a_linear_score_exceeds():
+    rng = np.random.default_rng(17)
+    feats = (rng.standard_normal((500, 4)) * np.array([3, 4, 1e-3, 0.3])).astype(np.float32)
+    w = np.array([0.25, 0.5, 100.0, -1.0], np.float32)
+    thr = np.array([-0.5, 0.4, 1.7], np.float32)
+    bits, score = oracle.rule_policy(feats, w, 0.125, thr)
+    want_score = 0.125 + feats.astype(np.float64) @ w.astype(np.float64)
+    np.testing.assert_allclose(score, want_score, rtol=1e-14, atol=1e-14)
+    # class = number of thresholds strictly below the score: a library binary search gives the same count
+    want_cls = np.searchsorted(thr.astype(np.float64), want_score, side="left")
+    assert np.array_equal(bits, np.array([2, 4, 8, 16], np.uint8)[want_cls])
+    # hand cases: a score equal to a threshold does not exceed it; only feature 1 matters with w = e_1
+    f = np.zeros((5, 4), np.float32)
+    f[:, 1] = [-1.0, 0.0, 0.5, 1.0, 2.5]
+    b, _ = oracle.rule_policy(f, np.array([0, 1, 0, 0], np.float32), 0.0, np.array([0.0, 0.5, 2.0], np.float32))
+    assert b.tolist() == [2, 2, 4, 8, 16]
+    # monotone in the score: raising the bias never lowers a width
+    b_hi, _ = oracle.rule_policy(feats, w, 1.0, thr)
+    assert np.all(b_hi >= bits)
