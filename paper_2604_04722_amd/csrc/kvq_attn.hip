@@ -850,9 +850,12 @@ extern "C" size_t kvq_decode_attn_workspace(const kvq_cache *cache, int32_t n_se
     return (size_t)n_seq * cache->desc.n_q_heads * kMaxSplits * kPartialFloats * sizeof(float) + 256;
 }
 
-static int launch_attn(const kvq_cache *cache, int32_t layer, const void *q, const void *k_new, const void *v_new,
-                       const int32_t *seq_ids, int32_t n_seq, float *out, float *lse_out, float *sum_p2_out,
-                       void *workspace, size_t workspace_bytes, void *stream)
+struct AttnPlan { long long S; int nw; };
+
+// Chooses the launch shape and checks the workspace against it; launches nothing, so an entry point can validate
+// everything before it changes any state.  `extra_tokens` are tokens that will have been appended by launch time.
+static int plan_attn(const kvq_cache *cache, int32_t n_seq, int extra_tokens, const void *workspace, size_t workspace_bytes,
+                     AttnPlan *plan)
 {
     const kvq_cache_desc &d = cache->desc;
     const long long heads = (long long)n_seq * d.n_q_heads;
@@ -861,11 +864,13 @@ static int launch_attn(const kvq_cache *cache, int32_t layer, const void *q, con
     // per four units (10-16 KiB each), or the per-class pipelines never reach steady state.  Up to eight of them sit
     // in one workgroup, where their partial results merge through LDS; only beyond that is the sequence split over
     // workgroups, which costs a second kernel for the merge.  len_bound is an upper bound of the longest sequence.
-    const long long est_units = (cache->len_bound + 63) / 64;
+    long long len_bound = cache->len_bound + extra_tokens;
+    if (len_bound > d.max_context) len_bound = d.max_context;
+    const long long est_units = (len_bound + 63) / 64;
     long long wph = 2048 / heads;
     if (wph > est_units / 4) wph = est_units / 4;
     if (wph < 2) wph = 2;
-    int nw_auto = wph >= 8 ? 8 : wph >= 4 ? 4 : wph >= 3 ? 3 : 2;
+    const int nw_auto = wph >= 8 ? 8 : wph >= 4 ? 4 : wph >= 3 ? 3 : 2;
     long long S = wph >= 16 ? wph / 8 : 1;
     if (S > kMaxSplits) S = kMaxSplits;
     const int forced = env_int("KVQ_ATTN_SPLITS", 0);
@@ -878,6 +883,21 @@ static int launch_attn(const kvq_cache *cache, int32_t layer, const void *q, con
             return KVQ_ERR_INVALID_ARG;
         }
     }
+    int nw = env_int("KVQ_ATTN_WAVES", 0);                      // 1, 2, 3, 4 or 8; anything else: the rule above
+    if (nw != 1 && nw != 2 && nw != 3 && nw != 4 && nw != 8) nw = nw_auto;
+    plan->S = S;
+    plan->nw = nw;
+    return KVQ_OK;
+}
+
+static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t layer, const void *q, const void *k_new,
+                       const void *v_new, const int32_t *seq_ids, int32_t n_seq, float *out, float *lse_out,
+                       float *sum_p2_out, void *workspace, void *stream)
+{
+    const kvq_cache_desc &d = cache->desc;
+    const long long heads = (long long)n_seq * d.n_q_heads;
+    const long long S = plan.S;
+    const int nw = plan.nw;
     AttnParams P;
     P.cv = cache->view;
     P.q = (const uint32_t *)q;
@@ -899,8 +919,6 @@ static int launch_attn(const kvq_cache *cache, int32_t layer, const void *q, con
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
-    int nw = env_int("KVQ_ATTN_WAVES", 0);                      // 1, 2, 3, 4 or 8; anything else: the rule above
-    if (nw != 1 && nw != 2 && nw != 3 && nw != 4 && nw != 8) nw = nw_auto;
     P.longest_first = env_int("KVQ_ATTN_LONGEST_FIRST", (n_seq <= 64 && n_seq % 8 == 0 && heads * S * nw > 2048) ? 1 : 0);
     if (n_seq > 64 || n_seq % 8 != 0) P.longest_first = 0;
     if (nw == 1) hipLaunchKernelGGL(k_decode_split<1>, dim3(grid), dim3(64), 0, st, P);
@@ -926,7 +944,10 @@ extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void
     if (layer < 0 || layer >= d.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
     if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
     if (n_seq == 0) return KVQ_OK;
-    return launch_attn(cache, layer, q, nullptr, nullptr, seq_ids, n_seq, out, lse_out, sum_p2_out, workspace, workspace_bytes, stream);
+    AttnPlan plan;
+    const int rc = plan_attn(cache, n_seq, 0, workspace, workspace_bytes, &plan);
+    if (rc != KVQ_OK) return rc;
+    return launch_attn(cache, plan, layer, q, nullptr, nullptr, seq_ids, n_seq, out, lse_out, sum_p2_out, workspace, stream);
 }
 
 extern "C" int kvq_append_decode_attn(kvq_cache *cache, int32_t layer, const void *k, const void *v, const uint8_t *bits,
@@ -938,9 +959,13 @@ extern "C" int kvq_append_decode_attn(kvq_cache *cache, int32_t layer, const voi
     if (layer < 0 || layer >= d.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
     if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
     if (n_seq == 0) return KVQ_OK;
-    if (layer == 0 && bits) {                                     // bits == NULL: done by kvq_features_controller
+    const bool bookkeeping = layer == 0 && bits;                   // bits == NULL: done by kvq_features_controller
+    AttnPlan plan;                                                 // every check comes before the first state change
+    const int rc0 = plan_attn(cache, n_seq, bookkeeping ? 1 : 0, workspace, workspace_bytes, &plan);
+    if (rc0 != KVQ_OK) return rc0;
+    if (bookkeeping) {
         const int rc = kvq_append_bookkeeping(cache, bits, seq_ids, n_seq, 1, stream);
         if (rc != KVQ_OK) return rc;
     }
-    return launch_attn(cache, layer, q, k, v, seq_ids, n_seq, out, lse_out, sum_p2_out, workspace, workspace_bytes, stream);
+    return launch_attn(cache, plan, layer, q, k, v, seq_ids, n_seq, out, lse_out, sum_p2_out, workspace, stream);
 }

@@ -450,11 +450,7 @@ extern "C" int kvq_features_controller(const float *logits, int64_t n, int64_t v
     M.logits = logits_out;
     M.n = n;
     CacheView cv = {};
-    if (cache) {
-        cv = cache->view;
-        cache->len_bound += 1;
-        if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;
-    }
+    if (cache) cv = cache->view;
     hipStream_t st = (hipStream_t)stream;
     const int stage_floats = mlp_stage_floats(M);
     const int staged = stage_floats <= kMlpStageMaxFloats;
@@ -463,6 +459,10 @@ extern "C" int kvq_features_controller(const float *logits, int64_t n, int64_t v
         static size_t granted = 0;
         const int rc_lds = ensure_dynamic_lds((const void *)k_front, lds, &granted);
         if (rc_lds != KVQ_OK) return rc_lds;
+    }
+    if (cache) {                                                   // host-side length bound: after the last check
+        cache->len_bound += 1;
+        if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;
     }
     hipLaunchKernelGGL(k_front, dim3((unsigned)n), dim3(kFrontGroups * kFeatThreads), lds, st, F, M, cv, staged);
     KVQ_HIP(hipGetLastError());

@@ -404,6 +404,9 @@ def test_host_side_argument_checks_change_nothing():
     with env(KVQ_ATTN_SPLITS=4):
         with pytest.raises(kvq.KvqError):
             kvq.kvq_decode_attn(cache, 0, K, None, 2, out, ws)    # workspace too small for 4 splits
+    with env(KVQ_ATTN_SPLITS=4):
+        with pytest.raises(kvq.KvqError):                         # the fused call checks its workspace before it books the token
+            kvq.kvq_append_decode_attn(cache, 0, K, K, bits.view(-1), K, None, 2, out, ws)
     assert int(cache.counts()[:, 4].sum()) == 0 and cache.status()[0] == 0
     with pytest.raises(kvq.KvqError):
         kvq.Cache(1, 1, 3, 2, 256)                                # Hq not a multiple of Hkv
