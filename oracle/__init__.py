@@ -252,3 +252,47 @@ def rule_policy(feats, w, bias: float, thr):
     score = np.zeros(n, np.float64)
     lib().kvq_oracle_rule_policy(_p(f), ctypes.c_int64(n), _p(wv), ctypes.c_float(bias), _p(tv), _p(bits), _p(score))
     return bits, score
+
+
+def kch_quantize_vec(x_bits, bits: int, kmin_bits, krange_bits) -> np.ndarray:
+    """Static per-channel variant for one K vector: codes uint8[128] (canonical packing)."""
+    x, mn, rg = _c(x_bits, np.uint16), _c(kmin_bits, np.uint16), _c(krange_bits, np.uint16)
+    assert x.shape == (D,) and mn.shape == (D,) and rg.shape == (D,)
+    codes = np.zeros(REC, np.uint8)
+    lib().kvq_oracle_kch_quantize_vec(_p(x), ctypes.c_int(bits), _p(mn), _p(rg), _p(codes))
+    return codes
+
+
+def kch_dequantize_vec(codes, bits: int, kmin_bits, krange_bits) -> np.ndarray:
+    c, mn, rg = _c(codes, np.uint8), _c(kmin_bits, np.uint16), _c(krange_bits, np.uint16)
+    out = np.zeros(D, np.float64)
+    lib().kvq_oracle_kch_dequantize_vec(_p(c), ctypes.c_int(bits), _p(mn), _p(rg), _p(out))
+    return out
+
+
+def append_kch(k_bits, v_bits, bits, kmin_bits, krange_bits):
+    """append() with the per-channel variant for K; kmin / krange are uint16 [Hkv, 64]."""
+    k, v, b = _c(k_bits, np.uint16), _c(v_bits, np.uint16), _c(bits, np.uint8)
+    mn, rg = _c(kmin_bits, np.uint16), _c(krange_bits, np.uint16)
+    T, Hkv, d = k.shape
+    assert d == D and v.shape == k.shape and b.shape == (T,) and mn.shape == (Hkv, D) and rg.shape == (Hkv, D)
+    codes = np.zeros((T, Hkv, 2, REC), np.uint8)
+    meta = np.zeros((T, Hkv, 2, 2), np.uint16)
+    lib().kvq_oracle_append_kch.restype = ctypes.c_int
+    rc = lib().kvq_oracle_append_kch(_p(k), _p(v), _p(b), ctypes.c_int64(T), ctypes.c_int(Hkv), _p(mn), _p(rg), _p(codes), _p(meta))
+    if rc != 0:
+        raise ValueError("illegal bit width")
+    return codes, meta
+
+
+def decode_attn_kch(q_bits, bits, codes, meta, kmin_bits, krange_bits, Hq: int):
+    """decode_attn() over a cache whose keys use the per-channel variant.  Returns (out [Hq,64], lse [Hq])."""
+    q, b, c, m = _c(q_bits, np.uint16), _c(bits, np.uint8), _c(codes, np.uint8), _c(meta, np.uint16)
+    mn, rg = _c(kmin_bits, np.uint16), _c(krange_bits, np.uint16)
+    n = b.shape[0]
+    Hkv = c.shape[1] if n else mn.shape[0]
+    out = np.zeros((Hq, D), np.float64)
+    lse = np.zeros(Hq, np.float64)
+    lib().kvq_oracle_decode_attn_kch(_p(q), _p(b), _p(c), _p(m), _p(mn), _p(rg), ctypes.c_int64(n), ctypes.c_int(Hq),
+                                     ctypes.c_int(Hkv), _p(out), _p(lse))
+    return out, lse

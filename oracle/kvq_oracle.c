@@ -493,3 +493,114 @@ void kvq_oracle_rule_policy(const float *feats, int64_t n, const float *w, float
         if (score) score[t] = u;
     }
 }
+
+/* ------------------------------------------------------------------------------------------ */
+/* Variant Q_b for keys: static per-channel quantization.  The paper leaves Q_b open (Sec. 3.7) */
+/* and cites per-channel key quantizers as related work (Sec. 2); this variant follows that     */
+/* idea in its simplest form.  The caller supplies, per (kv-head, channel c), a minimum m_c and  */
+/* a range r_c (fp16, from an offline calibration).  For a token stored at b bits:              */
+/*   step_c = fp16(fp32(r_c) / levels),  code_c = clamp(rint((x_c - m_c) / fp32(step_c)), 0,     */
+/*   levels) in IEEE binary32 (code 0 where the step is 0),  k^_c = m_c + code_c * step_c.       */
+/* Values outside [m_c, m_c + r_c] clamp.  No per-token scale or minimum is stored for K (its    */
+/* two meta entries stay 0); V and the 16-bit class are unchanged.                               */
+/* ------------------------------------------------------------------------------------------ */
+static uint16_t kch_step(uint16_t range_h, int levels)
+{
+    volatile float r = kvq_oracle_f16_to_f32(range_h);
+    volatile float st = r / (float)levels;
+    return kvq_oracle_f32_to_f16(st);
+}
+
+void kvq_oracle_kch_quantize_vec(const uint16_t *x, int bits, const uint16_t *kmin, const uint16_t *krange, uint8_t *codes)
+{
+    memset(codes, 0, KVQ_REC);
+    if (bits == 16) {
+        for (int i = 0; i < KVQ_D; ++i) {
+            codes[2 * i] = (uint8_t)(x[i] & 0xffu);
+            codes[2 * i + 1] = (uint8_t)(x[i] >> 8);
+        }
+        return;
+    }
+    const int levels = (1 << bits) - 1;
+    for (int i = 0; i < KVQ_D; ++i) {
+        volatile float s = kvq_oracle_f16_to_f32(kch_step(krange[i], levels));
+        if (s == 0.0f) continue;
+        volatile float d = kvq_oracle_f16_to_f32(x[i]) - kvq_oracle_f16_to_f32(kmin[i]);
+        volatile float t = d / s;
+        float r = rintf(t);
+        if (r < 0.0f) r = 0.0f;
+        if (r > (float)levels) r = (float)levels;
+        uint32_t c = (uint32_t)r;
+        int bit = i * bits;
+        codes[bit >> 3] |= (uint8_t)(c << (bit & 7));
+    }
+}
+
+void kvq_oracle_kch_dequantize_vec(const uint8_t *codes, int bits, const uint16_t *kmin, const uint16_t *krange, double *out)
+{
+    if (bits == 16) {
+        kvq_oracle_dequantize_vec(codes, 0, 0, 16, out);
+        return;
+    }
+    const int levels = (1 << bits) - 1;
+    for (int i = 0; i < KVQ_D; ++i)
+        out[i] = (double)kvq_oracle_f16_to_f32(kmin[i]) +
+                 (double)unpack_code(codes, bits, i) * (double)kvq_oracle_f16_to_f32(kch_step(krange[i], levels));
+}
+
+/* kvq_oracle_append with the per-channel variant for K: kmin, krange are [Hkv][64] */
+int kvq_oracle_append_kch(const uint16_t *k, const uint16_t *v, const uint8_t *bits, int64_t T, int Hkv,
+                          const uint16_t *kmin, const uint16_t *krange, uint8_t *codes, uint16_t *meta)
+{
+    for (int64_t t = 0; t < T; ++t) {
+        int b = bits[t];
+        if (b != 2 && b != 4 && b != 8 && b != 16) return -1;
+        for (int h = 0; h < Hkv; ++h) {
+            int64_t vec = t * Hkv + h;
+            kvq_oracle_kch_quantize_vec(k + vec * KVQ_D, b, kmin + h * KVQ_D, krange + h * KVQ_D, codes + (vec * 2 + 0) * KVQ_REC);
+            meta[(vec * 2 + 0) * 2] = 0;
+            meta[(vec * 2 + 0) * 2 + 1] = 0;
+            kvq_oracle_quantize_vec(v + vec * KVQ_D, b, codes + (vec * 2 + 1) * KVQ_REC,
+                                    meta + (vec * 2 + 1) * 2, meta + (vec * 2 + 1) * 2 + 1);
+        }
+    }
+    return 0;
+}
+
+/* kvq_oracle_decode_attn (Sec. 3.2) over a cache whose keys use the per-channel variant */
+void kvq_oracle_decode_attn_kch(const uint16_t *q, const uint8_t *bits, const uint8_t *codes, const uint16_t *meta,
+                                const uint16_t *kmin, const uint16_t *krange, int64_t len, int Hq, int Hkv,
+                                double *out, double *lse)
+{
+    const int group = Hq / Hkv;
+    const double inv_sqrt_d = 1.0 / sqrt((double)KVQ_D);
+    double *score = (double *)malloc(sizeof(double) * (size_t)(len > 0 ? len : 1));
+    for (int h = 0; h < Hq; ++h) {
+        const int kvh = h / group;
+        double qd[KVQ_D], kd[KVQ_D], vd[KVQ_D];
+        for (int c = 0; c < KVQ_D; ++c) qd[c] = (double)kvq_oracle_f16_to_f32(q[h * KVQ_D + c]);
+        double mx = -INFINITY;
+        for (int64_t j = 0; j < len; ++j) {
+            int64_t vec = j * Hkv + kvh;
+            kvq_oracle_kch_dequantize_vec(codes + (vec * 2 + 0) * KVQ_REC, bits[j], kmin + kvh * KVQ_D, krange + kvh * KVQ_D, kd);
+            double dot = 0.0;
+            for (int c = 0; c < KVQ_D; ++c) dot += qd[c] * kd[c];
+            score[j] = dot * inv_sqrt_d;
+            if (score[j] > mx) mx = score[j];
+        }
+        double denom = 0.0;
+        for (int64_t j = 0; j < len; ++j) denom += exp(score[j] - mx);
+        double acc[KVQ_D];
+        for (int c = 0; c < KVQ_D; ++c) acc[c] = 0.0;
+        for (int64_t j = 0; j < len; ++j) {
+            double p = exp(score[j] - mx) / denom;
+            int64_t vec = j * Hkv + kvh;
+            kvq_oracle_dequantize_vec(codes + (vec * 2 + 1) * KVQ_REC, meta[(vec * 2 + 1) * 2],
+                                      meta[(vec * 2 + 1) * 2 + 1], bits[j], vd);
+            for (int c = 0; c < KVQ_D; ++c) acc[c] += p * vd[c];
+        }
+        for (int c = 0; c < KVQ_D; ++c) out[h * KVQ_D + c] = acc[c];
+        if (lse) lse[h] = (len > 0) ? mx + log(denom) : -INFINITY;
+    }
+    free(score);
+}

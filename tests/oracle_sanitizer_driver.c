@@ -21,6 +21,11 @@ void kvq_oracle_features(const float *logits, int64_t n, int64_t vocab, const in
 void kvq_oracle_counts_update(const int32_t *ids, int64_t n, int64_t *counts, int64_t *totals);
 void kvq_oracle_controller(const float *feats, int64_t n, int n_linear, const int32_t *dims, const float *const *W,
                            const float *const *bvec, uint8_t *bits, double *logits);
+int kvq_oracle_append_kch(const uint16_t *k, const uint16_t *v, const uint8_t *bits, int64_t T, int Hkv, const uint16_t *kmin,
+                          const uint16_t *krange, uint8_t *codes, uint16_t *meta);
+void kvq_oracle_decode_attn_kch(const uint16_t *q, const uint8_t *bits, const uint8_t *codes, const uint16_t *meta,
+                                const uint16_t *kmin, const uint16_t *krange, int64_t len, int Hq, int Hkv, double *out, double *lse);
+void kvq_oracle_rule_policy(const float *feats, int64_t n, const float *w, float bias, const float *thr, uint8_t *bits, double *score);
 int kvq_oracle_accounting(const uint8_t *bits, int64_t n, int Hkv, int layers, double *expected_bits, double *effective_bits,
                           int64_t *payload_bytes);
 
@@ -81,7 +86,15 @@ int main(void)
     double eb, ef;
     int64_t nb;
     if (kvq_oracle_accounting(bits, B * T, HKV, 2, &eb, &ef, &nb) != 0) return 5;
+    uint16_t *kmin = malloc(sizeof(uint16_t) * HKV * 64), *krange = malloc(sizeof(uint16_t) * HKV * 64);
+    for (int i = 0; i < HKV * 64; ++i) { kmin[i] = kvq_oracle_f32_to_f16(-9.0f); krange[i] = kvq_oracle_f32_to_f16(18.0f); }
+    if (kvq_oracle_append_kch(k, v, bits, T, HKV, kmin, krange, codes, meta) != 0) return 6;
+    kvq_oracle_decode_attn_kch(q, bits, codes, meta, kmin, krange, T, HQ, HKV, out, lse);
+    const float rw[4] = {0.1f, 0.07f, 50.0f, -1.0f}, rthr[3] = {0.1f, 0.4f, 0.9f};
+    double rscore[N];
+    kvq_oracle_rule_policy(feats, N, rw, 0.0f, rthr, dec, rscore);
     printf("ok %.3f %.3f %lld %d\n", eb, ef, (long long)nb, (int)dec[0]);
+    free(kmin); free(krange);
     free(k); free(v); free(bits); free(codes); free(meta); free(q); free(out); free(lse); free(p2); free(probs);
     free(logits); free(counts); free(ap); free(W0); free(W1); free(W2);
     return 0;
