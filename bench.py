@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (4 = SmolLM-1.7B-shaped, the metric's config)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (profiling runs only)")
-    ap.add_argument("--no-compare", action="store_true", help="skip the static-4-bit and FP16 caches")
+    ap.add_argument("--no-compare", action="store_true", help="skip the static-4-bit, FP16, rule-policy and per-channel-key caches")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-events", action="store_true", help="do not bracket attention launches with events")
     ap.add_argument("--no-fused", action="store_true", help="skip the second timed loop that uses kvq_append_decode_attn")
@@ -113,6 +113,10 @@ def main():
                 need += math.ceil(((bits[s, :lens0[s]] == w).sum() + 4 * n_steps + 16) / 256) + 1
             pools.append(int(need))
         cache = kvq.Cache(L, B, Hq, Hkv, max_ctx, pool_pages=pools)
+        if variant == "kchannel":
+            # static per-channel key quantizer, calibrated offline as +-4 sigma of each channel of the synthetic keys
+            sig = torch.stack([wl.channel_multipliers(cfg, l_, 0) for l_ in range(L)])
+            cache.set_k_channel_quant((-4.0 * sig).to(torch.float16).to(dev), (8.0 * sig).to(torch.float16).to(dev))
         CH = 512
         Tmax = int(lens0.max())
         lens_d = torch.from_numpy(lens0).to(dev)
@@ -468,7 +472,7 @@ def main():
     # ---------------- comparison caches built by the same library ------------------------------------
     compare = {}
     if not args.no_compare:
-        for variant in ("static4", "fp16") + (("rule",) if rule is not None else ()):
+        for variant in ("static4", "fp16") + (("rule",) if rule is not None else ()) + ("kchannel",):
             c2, r2 = run_variant(variant, max(3, args.steps // 4), 2, not args.no_events)
             c2.destroy()
             del c2

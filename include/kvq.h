@@ -141,6 +141,18 @@ int kvq_cache_usage_of(kvq_cache *cache, kvq_cache_usage *usage, void *stream);
 int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t seq, uint8_t *bits_out, uint8_t *codes_out,
                      uint16_t *meta_out, int64_t max_tokens, void *stream);
 
+/* Variant Q_b for keys (the paper leaves Q_b open in Sec. 3.7 and cites per-channel key quantizers as related
+ * work): static per-channel quantization.  kmin and krange are device fp16 [n_layers][n_kv_heads][64]: per channel a
+ * minimum m_c and a range r_c from an offline calibration.  A key stored at b bits then uses
+ *   step_c = fp16(fp32(r_c) / (2^b - 1)),  code_c = clamp(rint((x_c - m_c) / fp32(step_c)), 0, 2^b - 1)  (IEEE binary32,
+ *   code 0 where the step is 0),  k^_c = m_c + code_c * step_c,
+ * values outside [m_c, m_c + r_c] clamp, and no per-token scale or minimum is stored for K (the export shows 0 for
+ * them).  Values, the 16-bit class, and every entry point's signature are unchanged; the attention kernel folds the
+ * steps into q once per class instead of reading a scale and a minimum per token.  Choose the quantizer while the
+ * cache is empty (after create or reset); kmin == krange == NULL returns to the per-token quantizer.  Appends with
+ * many tokens per call take the wave-per-vector kernel in this mode. */
+int kvq_cache_set_k_channel_quant(kvq_cache *cache, const void *kmin, const void *krange, void *stream);
+
 /* Inverse of kvq_cache_export: appends n_tokens tokens to sequence `seq` from a canonical dump (the arrays
  * kvq_cache_export wrote, device memory), without re-quantizing anything, so that a cache can be saved, restored,
  * or moved to another cache or device.  As with kvq_append, the call with layer == 0 does the bucket bookkeeping

@@ -23,7 +23,7 @@ EXPORT_REC = 128
 
 EXPORTED_SYMBOLS = (
     "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
-    "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export", "kvq_cache_import",
+    "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export", "kvq_cache_import", "kvq_cache_set_k_channel_quant",
     "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_features_controller", "kvq_rule_policy", "kvq_controller_param_count", "kvq_controller_train_workspace",
     "kvq_controller_train_step", "kvq_append", "kvq_decode_attn_workspace",
     "kvq_decode_attn", "kvq_append_decode_attn", "kvq_probe_read", "kvq_probe_copy",
@@ -91,6 +91,7 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_cache_usage_of.argtypes = [vp, ctypes.POINTER(CacheUsage), vp]
     lib.kvq_cache_export.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp]
     lib.kvq_cache_import.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp]
+    lib.kvq_cache_set_k_channel_quant.argtypes = [vp, vp, vp, vp]
     lib.kvq_features_workspace.restype = sz
     lib.kvq_features_workspace.argtypes = [i64, i64]
     lib.kvq_features.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp, sz, vp]
@@ -202,6 +203,14 @@ class Cache:
         out = torch.zeros((self.max_seqs, 5), dtype=torch.int32)
         _check(load_library().kvq_cache_counts(self.handle, out.data_ptr(), _stream(stream)))
         return out
+
+    def set_k_channel_quant(self, kmin: Optional[torch.Tensor], krange: Optional[torch.Tensor], stream=None) -> None:
+        """Static per-channel key quantizer: fp16 device tensors [n_layers, Hkv, 64] (None, None: back to per-token)."""
+        for t in (kmin, krange):
+            assert t is None or (t.is_cuda and t.dtype == torch.float16 and t.is_contiguous() and
+                                 tuple(t.shape) == (self.desc.n_layers, self.Hkv, 64))
+        _check(load_library().kvq_cache_set_k_channel_quant(self.handle, kmin.data_ptr() if kmin is not None else None,
+                                                            krange.data_ptr() if krange is not None else None, _stream(stream)))
 
     def usage(self, stream=None) -> dict:
         """Tokens per class, E[b], stored bits per element, payload and page bytes (host values)."""

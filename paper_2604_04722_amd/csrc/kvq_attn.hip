@@ -252,48 +252,78 @@ __device__ __forceinline__ void softmax_step(float (&sc)[U], WaveState &st, floa
         BODY(l_, 0, 1) BODY(l_, 1, 0) BODY(r_, 0, 3) BODY(r_, 1, 2)   \
     }
 
+// With static per-channel keys (LO = true) the query carries the channel steps, and the fp16 pairs q2 alone would lose
+// 2^-12 of every term: q2l holds the rounding remainders, scaled by 2^12 (kLoScale) so that they stay normal numbers;
+// their dot products run in accumulators of their own and join with the inverse factor.
+constexpr float kLoScale = 4096.0f, kLoInv = 1.0f / 4096.0f;
+
 // sum_t M_t (q . h)_t of one 2-bit vector (one chunk)
-__device__ __forceinline__ float dot_2bit(const uint4 &k, const uint32_t (&q2)[32], const Consts &cs)
+template <bool LO = false>
+__device__ __forceinline__ float dot_2bit(const uint4 &k, const uint32_t (&q2)[32], const uint32_t (&q2l)[32], const Consts &cs)
 {
-    float d[3] = {0.f, 0.f, 0.f};
+    float d[3] = {0.f, 0.f, 0.f}, e[3] = {0.f, 0.f, 0.f};
 #pragma unroll
     for (int wi = 0; wi < 4; ++wi) {
-#define KVQ_BODY(X, T, P) d[T] = __builtin_amdgcn_fdot2(as_h2(and_or(X, cs.m2[T], cs.one)), as_h2(q2[wi * 8 + (P)]), d[T], false);
+#define KVQ_BODY(X, T, P)                                                                            \
+    {                                                                                                \
+        const half2_t h = as_h2(and_or(X, cs.m2[T], cs.one));                                        \
+        d[T] = __builtin_amdgcn_fdot2(h, as_h2(q2[wi * 8 + (P)]), d[T], false);                      \
+        if constexpr (LO) e[T] = __builtin_amdgcn_fdot2(h, as_h2(q2l[wi * 8 + (P)]), e[T], false);   \
+    }
         KVQ_FOR_PAIRS_2BIT(word_of(k, wi), KVQ_BODY)
 #undef KVQ_BODY
+    }
+    if constexpr (LO) {
+#pragma unroll
+        for (int t = 0; t < 3; ++t) d[t] = fmaf(e[t], kLoInv, d[t]);
     }
     return fmaf(KVQ_M0_2, d[2], fmaf(KVQ_M0_1, d[1], KVQ_M0_0 * d[0]));
 }
 
 // sum_t M_t (q . h)_t of one 4-bit vector (two chunks)
-__device__ __forceinline__ float dot_4bit(const Stage &k, const uint32_t (&q2)[32], const Consts &cs)
+template <bool LO = false>
+__device__ __forceinline__ float dot_4bit(const Stage &k, const uint32_t (&q2)[32], const uint32_t (&q2l)[32], const Consts &cs)
 {
-    float d[2] = {0.f, 0.f};
+    float d[2] = {0.f, 0.f}, e[2] = {0.f, 0.f};
 #pragma unroll
     for (int ch = 0; ch < 2; ++ch)
 #pragma unroll
         for (int wi = 0; wi < 4; ++wi) {
-#define KVQ_BODY(X, T, P) d[T] = __builtin_amdgcn_fdot2(as_h2(and_or(X, cs.m4[T], cs.one)), as_h2(q2[(ch * 4 + wi) * 4 + (P)]), d[T], false);
+#define KVQ_BODY(X, T, P)                                                                                    \
+    {                                                                                                        \
+        const half2_t h = as_h2(and_or(X, cs.m4[T], cs.one));                                                \
+        d[T] = __builtin_amdgcn_fdot2(h, as_h2(q2[(ch * 4 + wi) * 4 + (P)]), d[T], false);                   \
+        if constexpr (LO) e[T] = __builtin_amdgcn_fdot2(h, as_h2(q2l[(ch * 4 + wi) * 4 + (P)]), e[T], false); \
+    }
             KVQ_FOR_PAIRS_4BIT(word_of(k.v[ch], wi), KVQ_BODY)
 #undef KVQ_BODY
         }
+    if constexpr (LO) { d[0] = fmaf(e[0], kLoInv, d[0]); d[1] = fmaf(e[1], kLoInv, d[1]); }
     return fmaf(KVQ_M1_1, d[1], KVQ_M1_0 * d[0]);
 }
 
 // (q . h) over chunks 2*PART, 2*PART+1 of an 8-bit vector: bytes 0 and 2, then bytes 1 and 3 of each word,
 // each under the exponent byte 0x64 (h = 1024 + c)
-template <int PART> __device__ __forceinline__ float dot_8bit(const Stage &k, const uint32_t (&q2)[32], float d)
+template <int PART, bool LO = false>
+__device__ __forceinline__ float dot_8bit(const Stage &k, const uint32_t (&q2)[32], const uint32_t (&q2l)[32], float d)
 {
-    float d0 = d, d1 = 0.f;
+    float d0 = d, d1 = 0.f, e0 = 0.f, e1 = 0.f;
 #pragma unroll
     for (int ch = 0; ch < 2; ++ch)
 #pragma unroll
         for (int wi = 0; wi < 4; ++wi) {
             const uint32_t w = word_of(k.v[ch], wi);
             const int m = ((2 * PART + ch) * 4 + wi) * 2;
-            d0 = __builtin_amdgcn_fdot2(as_h2(__builtin_amdgcn_perm(0x64646464u, w, 0x04020400u)), as_h2(q2[m]), d0, false);
-            d1 = __builtin_amdgcn_fdot2(as_h2(__builtin_amdgcn_perm(0x64646464u, w, 0x04030401u)), as_h2(q2[m + 1]), d1, false);
+            const half2_t h0 = as_h2(__builtin_amdgcn_perm(0x64646464u, w, 0x04020400u));
+            const half2_t h1 = as_h2(__builtin_amdgcn_perm(0x64646464u, w, 0x04030401u));
+            d0 = __builtin_amdgcn_fdot2(h0, as_h2(q2[m]), d0, false);
+            d1 = __builtin_amdgcn_fdot2(h1, as_h2(q2[m + 1]), d1, false);
+            if constexpr (LO) {
+                e0 = __builtin_amdgcn_fdot2(h0, as_h2(q2l[m]), e0, false);
+                e1 = __builtin_amdgcn_fdot2(h1, as_h2(q2l[m + 1]), e1, false);
+            }
         }
+    if constexpr (LO) return fmaf(e0 + e1, kLoInv, d0 + d1);
     return d0 + d1;
 }
 
@@ -375,7 +405,9 @@ template <int PART> __device__ __forceinline__ void acc_fp16(const Stage &v, flo
 }
 
 // scores of a unit -> softmax weights -> V multipliers and constant-part accumulators (quantized classes)
-template <int C>
+// KCH: the keys use the static per-channel variant.  Then q already carries the channel steps and qc.qs the constant
+// q . min, so every token has "scale 1, minimum 1" and the stored per-token key metadata is not looked at.
+template <int C, bool KCH = false>
 __device__ __forceinline__ void finish_k(const float (&dot)[Cls<C>::U], const uint2 (&meta)[Cls<C>::U], int ntok, int lane,
                                          const QConst &qc, WaveState &st, float (&a)[Cls<C>::U][Cls<C>::NT])
 {
@@ -383,7 +415,7 @@ __device__ __forceinline__ void finish_k(const float (&dot)[Cls<C>::U], const ui
     float sc[U], p[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const float kscale = half_lo(meta[u].x), kmin = half_hi(meta[u].x);
+        const float kscale = KCH ? 1.0f : half_lo(meta[u].x), kmin = KCH ? 1.0f : half_hi(meta[u].x);
         // q.k^ * kScoreScale = min*qs + scale*(kScoreScale * sum_t M_t d_t - qm)
         const float s = fmaf(kmin, qc.qs, kscale * fmaf(dot[u], kScoreScale, -qc.qm[C]));
         sc[u] = (u * kBlockTokens + lane < ntok) ? s : -INFINITY;
@@ -435,9 +467,9 @@ template <int C> __device__ __forceinline__ int unit_ntok(const ClassWalk &w, in
 
 // Units k0, k0+step, ... < k1 of the 2-bit (two blocks per unit) or 4-bit (one block per unit) class: two
 // stages per unit, K(n) -> b0/b2 and V(n) -> b1/b3 for even/odd n; each buffer is reloaded right after use.
-template <int C>
+template <int C, bool KCH = false>
 __device__ __forceinline__ void run_low(const ClassWalk &w, int k0, int k1, int step, int lane, const uint32_t (&q2)[32],
-                                        const QConst &qc, const Consts &cs, WaveState &st)
+                                        const uint32_t (&q2l)[32], const QConst &qc, const Consts &cs, WaveState &st)
 {
     if (k0 >= k1) return;
     constexpr int U = Cls<C>::U, NT = Cls<C>::NT;
@@ -458,9 +490,9 @@ __device__ __forceinline__ void run_low(const ClassWalk &w, int k0, int k1, int 
     }
     auto k_stage = [&](const Stage &b, const uint2 (&m)[U], int ntok, float (&a)[U][NT]) {
         float dot[U];
-        if constexpr (C == 0) { dot[0] = dot_2bit(b.v[0], q2, cs); dot[1] = dot_2bit(b.v[1], q2, cs); }
-        else dot[0] = dot_4bit(b, q2, cs);
-        finish_k<C>(dot, m, ntok, lane, qc, st, a);
+        if constexpr (C == 0) { dot[0] = dot_2bit<KCH>(b.v[0], q2, q2l, cs); dot[1] = dot_2bit<KCH>(b.v[1], q2, q2l, cs); }
+        else dot[0] = dot_4bit<KCH>(b, q2, q2l, cs);
+        finish_k<C, KCH>(dot, m, ntok, lane, qc, st, a);
     };
     auto v_stage = [&](const Stage &b, const float (&a)[U][NT]) {
         if constexpr (C == 0) { acc_2bit(b.v[0], a[0], cs, st); acc_2bit(b.v[1], a[1], cs, st); }
@@ -498,8 +530,9 @@ __device__ __forceinline__ void run_low(const ClassWalk &w, int k0, int k1, int 
 }
 
 // Blocks of the 8-bit class: stages K01, K23, V01, V23 (chunk pairs) -> b0..b3.
+template <bool KCH = false>
 __device__ __forceinline__ void run_8bit(const ClassWalk &w, int k0, int k1, int step, int lane, const uint32_t (&q2)[32],
-                                         const QConst &qc, WaveState &st)
+                                         const uint32_t (&q2l)[32], const QConst &qc, WaveState &st)
 {
     if (k0 >= k1) return;
     Stage b0, b1, b2, b3;
@@ -519,15 +552,15 @@ __device__ __forceinline__ void run_8bit(const ClassWalk &w, int k0, int k1, int
         const int nn = more ? unit_ntok<2>(w, ui + step) : 0;
         float dot[1], a[1][1];
         KVQ_FENCE();
-        dot[0] = dot_8bit<0>(b0, q2, 0.f);
+        dot[0] = dot_8bit<0, KCH>(b0, q2, q2l, 0.f);
         KVQ_FENCE();
         issue_stage<2, false, 0>(b0, bn, nn, lane);
         KVQ_FENCE();
-        dot[0] = dot_8bit<1>(b1, q2, dot[0]);
+        dot[0] = dot_8bit<1, KCH>(b1, q2, q2l, dot[0]);
         KVQ_FENCE();
         issue_stage<2, false, 1>(b1, bn, nn, lane);
         KVQ_FENCE();
-        finish_k<2>(dot, m0, unit_ntok<2>(w, ui), lane, qc, st, a);
+        finish_k<2, KCH>(dot, m0, unit_ntok<2>(w, ui), lane, qc, st, a);
         KVQ_FENCE();
         issue_meta<2>(m0, bn, nn, lane);
         KVQ_FENCE();
@@ -603,7 +636,49 @@ __device__ __forceinline__ void run_fp16(const ClassWalk &w, int k0, int k1, int
 
 __device__ __forceinline__ int ceil_div_pos(long long a, int b) { return (int)((a + b - 1) / b); }
 
-template <int NW>
+// Static per-channel keys, class C: q' = q (.) step_C as fp16 pairs q2 plus the fp16 remainders q2l (scaled by
+// kLoScale; the product of two fp16 numbers is exact in fp32, so q2 + q2l / kLoScale carries it to ~2^-22), read back
+// lane by lane into scalars; the constant q . min; and the class's mantissa-offset correction formed from the SAME
+// rounded pairs that the packed dot products will use.  lane = channel while this runs.  Products beyond the fp16 range
+// saturate.
+template <int C>
+__device__ __forceinline__ void kch_prepare(const AttnParams &P, int si, int qh, int kvh, int lane, uint32_t (&q2)[32],
+                                            uint32_t (&q2l)[32], QConst &qc)
+{
+    const CacheView &cv = P.cv;
+    const float qf = __half2float(((const __half *)P.q)[((size_t)si * cv.Hq + qh) * kD + lane]);
+    const size_t ti = ((size_t)P.layer * cv.Hkv + kvh) * kD + lane;
+    const float stp = __half2float(cv.kch_step[(size_t)C * cv.n_layers * cv.Hkv * kD + ti]);
+    const float mn = __half2float(cv.kch_min[ti]);
+    const float prod = fminf(fmaxf(qf * stp, -65504.0f), 65504.0f);
+    const __half hi = __float2half_rn(prod);
+    const __half lo = __float2half_rn((prod - __half2float(hi)) * kLoScale);
+    const uint32_t mine = (uint32_t)__half_as_ushort(hi) | ((uint32_t)__half_as_ushort(lo) << 16);      // {hi, lo} of this channel
+    const uint32_t other = (uint32_t)__shfl_xor((int)mine, 1, 64);
+    const uint32_t even = (lane & 1) ? other : mine, odd = (lane & 1) ? mine : other;
+    const uint32_t packed_hi = (even & 0xffffu) | (odd << 16), packed_lo = (even >> 16) | (odd & 0xffff0000u);
+    float qsum = 0.f, t0[3] = {0.f, 0.f, 0.f}, t1[2] = {0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        q2[i] = (uint32_t)__builtin_amdgcn_readlane((int)packed_hi, 2 * i);
+        {
+            // the remainders live in vector registers (every lane the same value): the scalar file cannot hold 64 query
+            // words next to the walk's pointers, and the vector file has the room
+            const uint32_t t = (uint32_t)__builtin_amdgcn_readlane((int)packed_lo, 2 * i);
+            asm volatile("v_mov_b32 %0, %1" : "=v"(q2l[i]) : "s"(t));
+        }
+        const float v = fmaf(half_lo(q2l[i]) + half_hi(q2l[i]), kLoInv, half_lo(q2[i]) + half_hi(q2[i]));
+        qsum += v;
+        t0[target0(i % 8)] += v;
+        t1[target1(i % 4)] += v;
+    }
+    qc.qs = wave_sum(qf * mn) * kScoreScale;
+    qc.qm[0] = (KVQ_M0_0 * t0[0] + KVQ_M0_1 * t0[1] + KVQ_M0_2 * t0[2]) * kScoreScale;
+    qc.qm[1] = (KVQ_M1_0 * t1[0] + KVQ_M1_1 * t1[1]) * kScoreScale;
+    qc.qm[2] = KVQ_OFF2 * qsum * kScoreScale;
+}
+
+template <int NW, bool KCH>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAVES_PER_EU, KVQ_WAVES_PER_EU))) void k_decode_split(AttnParams P)
 {
     const CacheView &cv = P.cv;
@@ -707,7 +782,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         const int mb = class_meta_bytes(new_cls);
         __half *meta = (__half *)(base + tok * 8);
         const bool writer = g == 0;
-        const float khat = quantize_store(P.k_new[src], new_bits, lane, tok, base + mb, meta, writer);
+        float khat;
+        if (KCH && new_bits != 16) {
+            const size_t ti = ((size_t)P.layer * cv.Hkv + kvh) * kD + lane;
+            khat = quantize_store_kch(P.k_new[src], new_bits, __half2float(cv.kch_min[ti]),
+                                      __half2float(cv.kch_step[(size_t)new_cls * cv.n_layers * cv.Hkv * kD + ti]), lane, tok, base + mb, meta, writer);
+        } else {
+            khat = quantize_store(P.k_new[src], new_bits, lane, tok, base + mb, meta, writer);
+        }
         new_v = quantize_store(P.v_new[src], new_bits, lane, tok, base + mb + region, meta + 2, writer);
         const float qf = __half2float(((const __half *)P.q)[((size_t)si * cv.Hq + qh) * kD + lane]);
         new_score = wave_sum(qf * khat) * kScoreScale;
@@ -741,10 +823,20 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     w.pt = cv.page_table + ((size_t)seq * kClasses + (C)) * cv.max_pages_per_seq;                \
     w.pool = cv.pool[C] + (size_t)P.layer * cv.layer_stride[C];                                  \
     w.cnt = cnt[C];
-    KVQ_WALK(0) run_low<0>(w, first[0], last[0], step, lane, q2, qc, cs, st);
-    KVQ_WALK(1) run_low<1>(w, first[1], last[1], step, lane, q2, qc, cs, st);
-    KVQ_WALK(2) run_8bit(w, first[2], last[2], step, lane, q2, qc, st);
-    KVQ_WALK(3) run_fp16(w, first[3], last[3], step, lane, q2, st);
+    if constexpr (!KCH) {
+        KVQ_WALK(0) run_low<0>(w, first[0], last[0], step, lane, q2, q2, qc, cs, st);
+        KVQ_WALK(1) run_low<1>(w, first[1], last[1], step, lane, q2, q2, qc, cs, st);
+        KVQ_WALK(2) run_8bit(w, first[2], last[2], step, lane, q2, q2, qc, st);
+        KVQ_WALK(3) run_fp16(w, first[3], last[3], step, lane, q2, st);
+    } else {
+        // the FP16 class first, with q as it is; then each quantized class that this wave meets, with q scaled by the
+        // class's channel steps (the scalars that held q are reused: the softmax does not care about the order)
+        KVQ_WALK(3) run_fp16(w, first[3], last[3], step, lane, q2, st);
+        uint32_t q2l[32];
+        if (first[0] < last[0]) { kch_prepare<0>(P, si, qh, kvh, lane, q2, q2l, qc); KVQ_WALK(0) run_low<0, true>(w, first[0], last[0], step, lane, q2, q2l, qc, cs, st); }
+        if (first[1] < last[1]) { kch_prepare<1>(P, si, qh, kvh, lane, q2, q2l, qc); KVQ_WALK(1) run_low<1, true>(w, first[1], last[1], step, lane, q2, q2l, qc, cs, st); }
+        if (first[2] < last[2]) { kch_prepare<2>(P, si, qh, kvh, lane, q2, q2l, qc); KVQ_WALK(2) run_8bit<true>(w, first[2], last[2], step, lane, q2, q2l, qc, st); }
+    }
 #undef KVQ_WALK
 
     // ---- sum the 64 lanes: a transposing butterfly leaves channel c's total in lane c ----------------
@@ -921,11 +1013,19 @@ static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t lay
     hipStream_t st = (hipStream_t)stream;
     P.longest_first = env_int("KVQ_ATTN_LONGEST_FIRST", (n_seq <= 64 && n_seq % 8 == 0 && heads * S * nw > 2048) ? 1 : 0);
     if (n_seq > 64 || n_seq % 8 != 0) P.longest_first = 0;
-    if (nw == 1) hipLaunchKernelGGL(k_decode_split<1>, dim3(grid), dim3(64), 0, st, P);
-    else if (nw == 2) hipLaunchKernelGGL(k_decode_split<2>, dim3(grid), dim3(128), 0, st, P);
-    else if (nw == 3) hipLaunchKernelGGL(k_decode_split<3>, dim3(grid), dim3(192), 0, st, P);
-    else if (nw == 8) hipLaunchKernelGGL(k_decode_split<8>, dim3(grid), dim3(512), 0, st, P);
-    else hipLaunchKernelGGL(k_decode_split<4>, dim3(grid), dim3(256), 0, st, P);
+    if (!cache->view.k_channel) {
+        if (nw == 1) hipLaunchKernelGGL((k_decode_split<1, false>), dim3(grid), dim3(64), 0, st, P);
+        else if (nw == 2) hipLaunchKernelGGL((k_decode_split<2, false>), dim3(grid), dim3(128), 0, st, P);
+        else if (nw == 3) hipLaunchKernelGGL((k_decode_split<3, false>), dim3(grid), dim3(192), 0, st, P);
+        else if (nw == 8) hipLaunchKernelGGL((k_decode_split<8, false>), dim3(grid), dim3(512), 0, st, P);
+        else hipLaunchKernelGGL((k_decode_split<4, false>), dim3(grid), dim3(256), 0, st, P);
+    } else {
+        if (nw == 1) hipLaunchKernelGGL((k_decode_split<1, true>), dim3(grid), dim3(64), 0, st, P);
+        else if (nw == 2) hipLaunchKernelGGL((k_decode_split<2, true>), dim3(grid), dim3(128), 0, st, P);
+        else if (nw == 3) hipLaunchKernelGGL((k_decode_split<3, true>), dim3(grid), dim3(192), 0, st, P);
+        else if (nw == 8) hipLaunchKernelGGL((k_decode_split<8, true>), dim3(grid), dim3(512), 0, st, P);
+        else hipLaunchKernelGGL((k_decode_split<4, true>), dim3(grid), dim3(256), 0, st, P);
+    }
     KVQ_HIP(hipGetLastError());
     if (S > 1) {
         hipLaunchKernelGGL(k_decode_combine, dim3((unsigned)((heads + 3) / 4)), dim3(256), 0, st, (const float *)workspace,

@@ -74,6 +74,10 @@ static size_t plan_arena(const kvq_cache_desc &d, CacheView *v, uint8_t *base)
     }
     cv.free_top = (int32_t *)(base + off);
     off = align256(off + sizeof(int32_t) * kClasses);
+    cv.kch_min = (__half *)(base + off);
+    off = align256(off + sizeof(__half) * (size_t)d.n_layers * d.n_kv_heads * kD);
+    cv.kch_step = (__half *)(base + off);
+    off = align256(off + sizeof(__half) * 3 * (size_t)d.n_layers * d.n_kv_heads * kD);
     cv.flags = (uint32_t *)(base + off);
     off = align256(off + sizeof(uint32_t));
     if (v) *v = cv;
@@ -276,8 +280,26 @@ __global__ __launch_bounds__(256) void k_append_write(CacheView cv, int layer, c
     const int meta_bytes = class_meta_bytes(cls);
     const size_t region = (size_t)class_chunks(cls) * kBlockTokens * 16;
     __half *meta = (__half *)(base + tok * 8);
-    quantize_store(k[src], b, lane, tok, base + meta_bytes, meta);
+    if (cv.k_channel && b != 16) {
+        const size_t ti = ((size_t)L * cv.Hkv + h) * kD + lane;
+        const float mn = __half2float(cv.kch_min[ti]);
+        const float st = __half2float(cv.kch_step[(size_t)cls * cv.n_layers * cv.Hkv * kD + ti]);
+        quantize_store_kch(k[src], b, mn, st, lane, tok, base + meta_bytes, meta);
+    } else {
+        quantize_store(k[src], b, lane, tok, base + meta_bytes, meta);
+    }
     quantize_store(v[src], b, lane, tok, base + meta_bytes + region, meta + 2);
+}
+
+// per-class steps of the static per-channel key quantizer: step = fp16(range / levels), IEEE binary32 division
+__global__ void k_set_kch(CacheView cv, const __half *kmin, const __half *krange, long long n)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    cv.kch_min[i] = kmin[i];
+    const float r = __half2float(krange[i]);
+#pragma unroll
+    for (int c = 0; c < 3; ++c) cv.kch_step[(size_t)c * n + i] = __float2half_rn(r / (float)((1 << class_bits(c)) - 1));
 }
 
 // ---- bulk (prefill) append: lane = token ------------------------------------------------------------------
@@ -718,6 +740,20 @@ extern "C" int kvq_cache_import(kvq_cache *cache, int32_t layer, int32_t seq, co
     return KVQ_OK;
 }
 
+extern "C" int kvq_cache_set_k_channel_quant(kvq_cache *cache, const void *kmin, const void *krange, void *stream)
+{
+    if (!cache) { set_error("cache is NULL"); return KVQ_ERR_INVALID_ARG; }
+    if ((kmin == nullptr) != (krange == nullptr)) { set_error("kmin and krange must both be given or both be NULL"); return KVQ_ERR_INVALID_ARG; }
+    if (cache->len_bound != 0) { set_error("the key quantizer can only be chosen while the cache is empty (create or reset it first)"); return KVQ_ERR_INVALID_ARG; }
+    if (!kmin) { cache->view.k_channel = 0; return KVQ_OK; }
+    const long long n = (long long)cache->desc.n_layers * cache->desc.n_kv_heads * kD;
+    hipLaunchKernelGGL(k_set_kch, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, cache->view,
+                       (const __half *)kmin, (const __half *)krange, n);
+    KVQ_HIP(hipGetLastError());
+    cache->view.k_channel = 1;
+    return KVQ_OK;
+}
+
 // launches the bookkeeping kernel for T new tokens per listed sequence (internal; arguments already validated)
 int kvq_append_bookkeeping(kvq_cache *cache, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T, void *stream)
 {
@@ -749,9 +785,10 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
         const int rc = kvq_append_bookkeeping(cache, bits, seq_ids, n_seq, T, stream);
         if (rc != KVQ_OK) return rc;
     }
-    // many tokens per sequence: the lane-per-token kernel (needs 16-byte aligned vectors); else a wave per vector
+    // many tokens per sequence: the lane-per-token kernel (needs 16-byte aligned vectors; per-token quantizer only);
+    // else a wave per vector
     static const int bulk_min_T = getenv("KVQ_APPEND_BULK_MIN_T") ? atoi(getenv("KVQ_APPEND_BULK_MIN_T")) : 32;
-    if (T >= bulk_min_T && (((uintptr_t)k | (uintptr_t)v) & 15) == 0) {
+    if (T >= bulk_min_T && (((uintptr_t)k | (uintptr_t)v) & 15) == 0 && !cache->view.k_channel) {
         const int tiles = (T + kBlockTokens - 1) / kBlockTokens;
         const long long waves = nl * n_seq * (long long)tiles * d.n_kv_heads;
         hipLaunchKernelGGL(k_append_bulk, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer,

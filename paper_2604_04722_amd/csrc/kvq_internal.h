@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -53,6 +54,10 @@ struct CacheView {
                                        // for the single-token writers instead of four dependent ones
     uint8_t *bits_log;                 // [max_seqs][max_context]
     int32_t *slot_log;                 // [max_seqs][max_context]
+    // static per-channel key quantizer (a variant Q_b, off unless k_channel != 0): per (layer, kv-head, channel) the
+    // minimum, and per quantized class the step fp16(range / levels)
+    __half *kch_min;                   // [n_layers][Hkv][64]
+    __half *kch_step;                  // [3][n_layers][Hkv][64]
     int32_t *free_stack[kClasses];     // [n_pages[c]] ids of free pages
     int32_t *free_top;                 // [4] number of free pages
     uint32_t *flags;                   // [1] sticky KVQ_FLAG_*
@@ -60,6 +65,7 @@ struct CacheView {
     int32_t n_layers, max_seqs, Hq, Hkv;
     int32_t page_tokens, blocks_per_page, max_pages_per_seq;
     int32_t max_context;
+    int32_t k_channel;                 // keys use the static per-channel variant
 };
 
 }  // namespace kvq

@@ -77,4 +77,28 @@ __device__ __forceinline__ float quantize_store(__half xh, int b, int lane, int 
     return deq;
 }
 
+// Static per-channel variant for a key vector (lane = channel): the channel's minimum mn and step s are given (fp16
+// values as floats), code = clamp(rint((x - mn) / s), 0, levels) in IEEE binary32, code 0 where s == 0; no per-token
+// scale or minimum is stored.  Packing and return value as quantize_store.
+__device__ __forceinline__ float quantize_store_kch(__half xh, int b, float mn, float s, int lane, int tok, uint8_t *codes, __half *meta,
+                                                    bool store = true)
+{
+    // the token's own (scale, minimum) entry is unused by this variant: it is stored as zero, not left as it was
+    if (store && lane == 0) *(uint32_t *)meta = 0u;
+    const float levels = (float)((1 << b) - 1);
+    float code = 0.0f;
+    if (s != 0.0f) {
+        code = rintf((__half2float(xh) - mn) / s);                  // IEEE division, ties to even
+        code = fminf(fmaxf(code, 0.0f), levels);
+    }
+    const int per = 32 / b;
+    const int r = lane % per;
+    const uint32_t word = group_or((uint32_t)code << (b * (r >> 1) + 16 * (r & 1)), per);
+    if (store && r == 0) {
+        const int w = lane / per;
+        *(uint32_t *)(codes + (size_t)(w >> 2) * (kBlockTokens * 16) + tok * 16 + (w & 3) * 4) = word;
+    }
+    return fmaf(code, s, mn);
+}
+
 }  // namespace kvq
