@@ -241,6 +241,26 @@ int kvq_features_controller(const float *logits, int64_t n, int64_t vocab, const
                             void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * The same two calls for logits that the model emits in a 16-bit type (Sec. 3.5 defines the features on the
+ * distribution p_t; a narrow logit is widened exactly, so the result is that of kvq_features / kvq_features_controller
+ * on the widened row, and a row costs half the bytes).
+ *   logits        device [n][vocab] of the type named by logits_dtype, aligned to its element size
+ *   logits_dtype  KVQ_DTYPE_F32 (then identical to the untyped calls), KVQ_DTYPE_F16 or KVQ_DTYPE_BF16
+ * Every other argument, the workspace and the error behaviour are those of the untyped call.
+ * ------------------------------------------------------------------------------------------- */
+enum { KVQ_DTYPE_F32 = 0, KVQ_DTYPE_F16 = 1, KVQ_DTYPE_BF16 = 2 };
+int kvq_features_typed(const void *logits, int32_t logits_dtype, int64_t n, int64_t vocab, const int32_t *token_ids,
+                       int64_t *counts, int64_t *totals, int32_t update_counts,
+                       const float *attn_probs, const float *sum_p2, const int32_t *attn_len,
+                       int32_t n_q_heads, int64_t ld, float *feats_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+int kvq_features_controller_typed(const void *logits, int32_t logits_dtype, int64_t n, int64_t vocab,
+                                  const int32_t *token_ids, int64_t *counts, int64_t *totals, int32_t update_counts,
+                                  const float *sum_p2, const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp,
+                                  kvq_cache *cache, const int32_t *seq_ids, float *feats_out, uint8_t *bits_out,
+                                  float *logits_out, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Stage 3 -- quantize and append (Sec. 3.7: k^ = Q_b(k), v^ = Q_b(v); Sec. 3.2: K <- Concat(K, k)).
  * Q_b for b in {2,4,8}, per (token, kv-head) vector x of 64 fp16 values, every step in IEEE binary32
  * round-to-nearest-even:  levels = 2^b - 1;  scale = fp16((max x - min x) / levels);  the stored

@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvq.so")
 
 KVQ_OK = 0
+KVQ_ERR_INVALID_ARG, KVQ_ERR_CAPACITY, KVQ_ERR_UNSUPPORTED, KVQ_ERR_DEVICE, KVQ_ERR_OOM = 1, 2, 3, 4, 5
 FLAG_POOL_EXHAUSTED = 1
 FLAG_CONTEXT_FULL = 2
 FLAG_BAD_BITS = 4
@@ -24,7 +25,7 @@ EXPORT_REC = 128
 EXPORTED_SYMBOLS = (
     "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
     "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export", "kvq_cache_import", "kvq_cache_set_k_channel_quant",
-    "kvq_features_workspace", "kvq_features", "kvq_controller", "kvq_features_controller", "kvq_rule_policy", "kvq_controller_param_count", "kvq_controller_train_workspace",
+    "kvq_features_workspace", "kvq_features", "kvq_features_typed", "kvq_controller", "kvq_features_controller", "kvq_features_controller_typed", "kvq_rule_policy", "kvq_controller_param_count", "kvq_controller_train_workspace",
     "kvq_controller_train_step", "kvq_append", "kvq_decode_attn_workspace",
     "kvq_decode_attn", "kvq_append_decode_attn", "kvq_probe_read", "kvq_probe_copy",
 )
@@ -95,6 +96,9 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_features_workspace.restype = sz
     lib.kvq_features_workspace.argtypes = [i64, i64]
     lib.kvq_features.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp, sz, vp]
+    lib.kvq_features_typed.argtypes = [vp, i32, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp, sz, vp]
+    lib.kvq_features_controller_typed.argtypes = [vp, i32, i64, i64, vp, vp, vp, i32, vp, vp, i32, ctypes.POINTER(Mlp), vp, vp, vp, vp,
+                                                  vp, vp]
     lib.kvq_controller.argtypes = [vp, i64, ctypes.POINTER(Mlp), vp, vp, vp]
     lib.kvq_features_controller.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, i32, ctypes.POINTER(Mlp), vp, vp, vp, vp,
                                             vp, vp]
@@ -265,6 +269,47 @@ def kvq_features_controller(logits: torch.Tensor, token_ids: torch.Tensor, count
     n, vocab = logits.shape
     _check(load_library().kvq_features_controller(
         _ptr(logits, torch.float32, "logits"), n, vocab, _ptr(token_ids, torch.int32, "token_ids"),
+        _ptr(counts, torch.int64, "counts"), _ptr(totals, torch.int64, "totals"), int(bool(update_counts)),
+        _ptr(sum_p2, torch.float32, "sum_p2"), _ptr(attn_len, torch.int32, "attn_len"), n_q_heads,
+        ctypes.byref(mlp.c), cache.handle if cache is not None else None, _ptr(seq_ids, torch.int32, "seq_ids"),
+        _ptr(feats_out, torch.float32, "feats_out"), _ptr(bits_out, torch.uint8, "bits_out"),
+        _ptr(logits_out, torch.float32, "logits_out"), _stream(stream)))
+
+
+DTYPE_F32, DTYPE_F16, DTYPE_BF16 = 0, 1, 2
+
+
+def _logits_dtype(logits: torch.Tensor) -> int:
+    codes = {torch.float32: DTYPE_F32, torch.float16: DTYPE_F16, torch.bfloat16: DTYPE_BF16}
+    if logits.dtype not in codes:
+        raise ValueError("logits must be float32, float16 or bfloat16, got %s" % logits.dtype)
+    return codes[logits.dtype]
+
+
+def kvq_features_typed(logits: torch.Tensor, token_ids: torch.Tensor, counts: torch.Tensor, totals: torch.Tensor,
+                       update_counts: bool, attn_len: torch.Tensor, n_q_heads: int, feats_out: torch.Tensor,
+                       workspace: torch.Tensor, attn_probs: Optional[torch.Tensor] = None,
+                       sum_p2: Optional[torch.Tensor] = None, stream=None) -> None:
+    """kvq_features for float32, float16 or bfloat16 logits (the type code is taken from the tensor)."""
+    n, vocab = logits.shape
+    ld = attn_probs.shape[-1] if attn_probs is not None else 0
+    _check(load_library().kvq_features_typed(
+        _ptr(logits, None, "logits"), _logits_dtype(logits), n, vocab, _ptr(token_ids, torch.int32, "token_ids"),
+        _ptr(counts, torch.int64, "counts"), _ptr(totals, torch.int64, "totals"), int(bool(update_counts)),
+        _ptr(attn_probs, torch.float32, "attn_probs"), _ptr(sum_p2, torch.float32, "sum_p2"),
+        _ptr(attn_len, torch.int32, "attn_len"), n_q_heads, ld, _ptr(feats_out, torch.float32, "feats_out"),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+def kvq_features_controller_typed(logits: torch.Tensor, token_ids: torch.Tensor, counts: torch.Tensor, totals: torch.Tensor,
+                                  update_counts: bool, sum_p2: torch.Tensor, attn_len: torch.Tensor, n_q_heads: int,
+                                  mlp: "MlpWeights", feats_out: torch.Tensor, bits_out: torch.Tensor,
+                                  cache: Optional["Cache"] = None, seq_ids: Optional[torch.Tensor] = None,
+                                  logits_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """kvq_features_controller for float32, float16 or bfloat16 logits."""
+    n, vocab = logits.shape
+    _check(load_library().kvq_features_controller_typed(
+        _ptr(logits, None, "logits"), _logits_dtype(logits), n, vocab, _ptr(token_ids, torch.int32, "token_ids"),
         _ptr(counts, torch.int64, "counts"), _ptr(totals, torch.int64, "totals"), int(bool(update_counts)),
         _ptr(sum_p2, torch.float32, "sum_p2"), _ptr(attn_len, torch.int32, "attn_len"), n_q_heads,
         ctypes.byref(mlp.c), cache.handle if cache is not None else None, _ptr(seq_ids, torch.int32, "seq_ids"),

@@ -70,28 +70,55 @@ __device__ __forceinline__ void lse3_add1(Lse3 &a, float z)
     a.t = fmaf(d, e, a.t);
 }
 
-// (m, S, T) of the part of one slice of a logits row that thread `lt` of kFeatThreads takes
-__device__ __forceinline__ Lse3 thread_partial(const float *logits, long long vocab, int slices, long long row, int slice, int lt)
+// Logits come as fp32, fp16 or bf16.  The narrow types are widened exactly, so the features are those of the
+// widened row; a thread's 16-byte load then carries eight logits instead of four.
+struct Bf16 { uint16_t bits; };
+template <typename T> __device__ __forceinline__ float widen(T x);
+template <> __device__ __forceinline__ float widen<float>(float x) { return x; }
+template <> __device__ __forceinline__ float widen<__half>(__half x) { return __half2float(x); }
+template <> __device__ __forceinline__ float widen<Bf16>(Bf16 x) { return __uint_as_float((uint32_t)x.bits << 16); }
+
+template <typename T> __device__ __forceinline__ void lse3_add_vec(Lse3 &a, const uint4 &v);
+template <> __device__ __forceinline__ void lse3_add_vec<float>(Lse3 &a, const uint4 &v)
 {
-    const float *z = logits + row * vocab;
+    lse3_add4(a, __uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+template <> __device__ __forceinline__ void lse3_add_vec<__half>(Lse3 &a, const uint4 &v)
+{
+    const __half2 h0 = *(const __half2 *)&v.x, h1 = *(const __half2 *)&v.y, h2 = *(const __half2 *)&v.z, h3 = *(const __half2 *)&v.w;
+    lse3_add4(a, __low2float(h0), __high2float(h0), __low2float(h1), __high2float(h1));
+    lse3_add4(a, __low2float(h2), __high2float(h2), __low2float(h3), __high2float(h3));
+}
+template <> __device__ __forceinline__ void lse3_add_vec<Bf16>(Lse3 &a, const uint4 &v)
+{
+    lse3_add4(a, __uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+    lse3_add4(a, __uint_as_float(v.z << 16), __uint_as_float(v.z & 0xffff0000u), __uint_as_float(v.w << 16), __uint_as_float(v.w & 0xffff0000u));
+}
+
+// (m, S, T) of the part of one slice of a logits row that thread `lt` of kFeatThreads takes
+template <typename T>
+__device__ __forceinline__ Lse3 thread_partial(const T *logits, long long vocab, int slices, long long row, int slice, int lt)
+{
+    constexpr int kPer = 16 / (int)sizeof(T);             // logits per 16-byte load
+    const T *z = logits + row * vocab;
     const long long per = (vocab + slices - 1) / slices;
     long long lo = per * slice, hi = lo + per;
     if (hi > vocab) hi = vocab;
     Lse3 a = {-INFINITY, 0.f, 0.f};
     if (lo < hi) {
-        const float *p = z + lo;
+        const T *p = z + lo;
         long long n = hi - lo;
         // peel to a 16-byte boundary
-        long long head = ((16 - ((uintptr_t)p & 15)) & 15) / 4;
+        long long head = ((16 - ((uintptr_t)p & 15)) & 15) / (long long)sizeof(T);
         if (head > n) head = n;
-        if ((long long)lt < head) lse3_add1(a, p[lt]);
+        if ((long long)lt < head) lse3_add1(a, widen<T>(p[lt]));
         p += head;
         n -= head;
-        const long long n4 = n / 4;
-        const float4 *p4 = (const float4 *)p;
-        // four loads in flight per thread; the quadruples are added in ascending order
+        const long long n4 = n / kPer;
+        const uint4 *p4 = (const uint4 *)p;
+        // four loads in flight per thread; the vectors are added in ascending order
         for (long long i = lt; i < n4; i += 4 * kFeatThreads) {
-            float4 v[4];
+            uint4 v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const long long k = i + u * kFeatThreads;
@@ -99,10 +126,10 @@ __device__ __forceinline__ Lse3 thread_partial(const float *logits, long long vo
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if (i + u * kFeatThreads < n4) lse3_add4(a, v[u].x, v[u].y, v[u].z, v[u].w);
+                if (i + u * kFeatThreads < n4) lse3_add_vec<T>(a, v[u]);
         }
-        const long long tail = n - n4 * 4;
-        if ((long long)lt < tail) lse3_add1(a, p[n4 * 4 + lt]);
+        const long long tail = n - n4 * kPer;
+        if ((long long)lt < tail) lse3_add1(a, widen<T>(p[n4 * kPer + lt]));
     }
     return a;
 }
@@ -132,7 +159,8 @@ __device__ __forceinline__ void group_merge(Lse3 *sm, int lt)
     __syncthreads();
 }
 
-__global__ __launch_bounds__(kFeatThreads) void k_lse_partial(const float *logits, long long vocab, int slices, float *ws)
+template <typename T>
+__global__ __launch_bounds__(kFeatThreads) void k_lse_partial(const T *logits, long long vocab, int slices, float *ws)
 {
     __shared__ Lse3 sm[kFeatThreads];
     const long long row = blockIdx.y;
@@ -256,7 +284,7 @@ __global__ __launch_bounds__(kFeatThreads) void k_features_finalize(FeatArgs A)
 constexpr int kFrontGroups = 4;
 
 struct FrontArgs {
-    const float *logits;
+    const void *logits;
     const int32_t *token_ids;
     const long long *counts;
     const long long *totals;
@@ -268,6 +296,7 @@ struct FrontArgs {
     int slices, Hq, advance;
 };
 
+template <typename T>
 __global__ __launch_bounds__(kFrontGroups * kFeatThreads) void k_front(FrontArgs F, MlpArgs M, CacheView cv, int staged)
 {
     extern __shared__ float stage[];               // the controller's weights, fetched while the logits stream in
@@ -301,7 +330,7 @@ __global__ __launch_bounds__(kFrontGroups * kFeatThreads) void k_front(FrontArgs
         for (int r = 0; r < kRounds; ++r) {
             const int slice = s0 + r * kFrontGroups + g;
             part[r].m = -INFINITY; part[r].s = 0.f; part[r].t = 0.f;
-            if (slice < F.slices) part[r] = thread_partial(F.logits, F.vocab, F.slices, row, slice, lt);
+            if (slice < F.slices) part[r] = thread_partial((const T *)F.logits, F.vocab, F.slices, row, slice, lt);
         }
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
@@ -364,13 +393,45 @@ extern "C" size_t kvq_features_workspace(int64_t n, int64_t vocab)
     return (size_t)n * kMaxSlices * 4 * sizeof(float) + 256;
 }
 
-extern "C" int kvq_features(const float *logits, int64_t n, int64_t vocab, const int32_t *token_ids,
-                            int64_t *counts, int64_t *totals, int32_t update_counts,
-                            const float *attn_probs, const float *sum_p2, const int32_t *attn_len,
-                            int32_t n_q_heads, int64_t ld, float *feats_out,
-                            void *workspace, size_t workspace_bytes, void *stream)
+template <typename T>
+static int launch_lse_partial(const void *logits, int64_t n, int64_t vocab, int slices, float *ws, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_lse_partial<T>, dim3(slices, (unsigned)n), dim3(kFeatThreads), 0, st, (const T *)logits, (long long)vocab, slices, ws);
+    KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+}
+
+template <typename T>
+static int launch_front(const kvq::FrontArgs &F, const kvq::MlpArgs &M, const kvq::CacheView &cv, int64_t n, size_t lds, int staged, hipStream_t st)
+{
+    static size_t granted = 0;
+    const int rc_lds = ensure_dynamic_lds((const void *)k_front<T>, lds, &granted);
+    if (rc_lds != KVQ_OK) return rc_lds;
+    hipLaunchKernelGGL(k_front<T>, dim3((unsigned)n), dim3(kFrontGroups * kFeatThreads), lds, st, F, M, cv, staged);
+    KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+}
+
+static int check_logits(const void *logits, int32_t dtype)
+{
+    if (dtype != KVQ_DTYPE_F32 && dtype != KVQ_DTYPE_F16 && dtype != KVQ_DTYPE_BF16) {
+        set_error("logits_dtype %d is not one of KVQ_DTYPE_F32, KVQ_DTYPE_F16, KVQ_DTYPE_BF16", dtype);
+        return KVQ_ERR_INVALID_ARG;
+    }
+    const uintptr_t align = dtype == KVQ_DTYPE_F32 ? 4 : 2;
+    if (logits && ((uintptr_t)logits & (align - 1))) { set_error("logits pointer is not aligned to its element size"); return KVQ_ERR_INVALID_ARG; }
+    return KVQ_OK;
+}
+
+extern "C" int kvq_features_typed(const void *logits, int32_t logits_dtype, int64_t n, int64_t vocab, const int32_t *token_ids,
+                                  int64_t *counts, int64_t *totals, int32_t update_counts,
+                                  const float *attn_probs, const float *sum_p2, const int32_t *attn_len,
+                                  int32_t n_q_heads, int64_t ld, float *feats_out,
+                                  void *workspace, size_t workspace_bytes, void *stream)
 {
     if (n < 0 || vocab < 1) { set_error("n or vocab out of range"); return KVQ_ERR_INVALID_ARG; }
+    const int rc_t = check_logits(logits, logits_dtype);
+    if (rc_t != KVQ_OK) return rc_t;
     if (n == 0) return KVQ_OK;
     if (!logits || !token_ids || !counts || !totals || !attn_len || !feats_out) { set_error("NULL argument"); return KVQ_ERR_INVALID_ARG; }
     if ((attn_probs == nullptr) == (sum_p2 == nullptr)) {
@@ -388,9 +449,10 @@ extern "C" int kvq_features(const float *logits, int64_t n, int64_t vocab, const
     hipStream_t st = (hipStream_t)stream;
     const int slices = pick_slices(n, vocab);
     if (n > 65535) { set_error("n above 65535 rows per call is not supported"); return KVQ_ERR_UNSUPPORTED; }
-    hipLaunchKernelGGL(k_lse_partial, dim3(slices, (unsigned)n), dim3(kFeatThreads), 0, st, logits, (long long)vocab,
-                       slices, (float *)workspace);
-    KVQ_HIP(hipGetLastError());
+    const int rc_l = logits_dtype == KVQ_DTYPE_F32   ? launch_lse_partial<float>(logits, n, vocab, slices, (float *)workspace, st)
+                     : logits_dtype == KVQ_DTYPE_F16 ? launch_lse_partial<__half>(logits, n, vocab, slices, (float *)workspace, st)
+                                                     : launch_lse_partial<Bf16>(logits, n, vocab, slices, (float *)workspace, st);
+    if (rc_l != KVQ_OK) return rc_l;
     FeatArgs A;
     A.ws = (const float *)workspace;
     A.token_ids = token_ids;
@@ -414,13 +476,25 @@ extern "C" int kvq_features(const float *logits, int64_t n, int64_t vocab, const
     return KVQ_OK;
 }
 
-extern "C" int kvq_features_controller(const float *logits, int64_t n, int64_t vocab, const int32_t *token_ids,
-                                       int64_t *counts, int64_t *totals, int32_t update_counts, const float *sum_p2,
-                                       const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp, kvq_cache *cache,
-                                       const int32_t *seq_ids, float *feats_out, uint8_t *bits_out, float *logits_out,
-                                       void *stream)
+extern "C" int kvq_features(const float *logits, int64_t n, int64_t vocab, const int32_t *token_ids,
+                            int64_t *counts, int64_t *totals, int32_t update_counts,
+                            const float *attn_probs, const float *sum_p2, const int32_t *attn_len,
+                            int32_t n_q_heads, int64_t ld, float *feats_out,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    return kvq_features_typed(logits, KVQ_DTYPE_F32, n, vocab, token_ids, counts, totals, update_counts, attn_probs, sum_p2,
+                              attn_len, n_q_heads, ld, feats_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int kvq_features_controller_typed(const void *logits, int32_t logits_dtype, int64_t n, int64_t vocab,
+                                             const int32_t *token_ids, int64_t *counts, int64_t *totals, int32_t update_counts,
+                                             const float *sum_p2, const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp,
+                                             kvq_cache *cache, const int32_t *seq_ids, float *feats_out, uint8_t *bits_out,
+                                             float *logits_out, void *stream)
 {
     if (n < 0 || vocab < 1) { set_error("n or vocab out of range"); return KVQ_ERR_INVALID_ARG; }
+    const int rc_t = check_logits(logits, logits_dtype);
+    if (rc_t != KVQ_OK) return rc_t;
     MlpArgs M;
     const int rc0 = mlp_args_from(mlp, &M, nullptr);
     if (rc0 != KVQ_OK) return rc0;
@@ -455,21 +529,28 @@ extern "C" int kvq_features_controller(const float *logits, int64_t n, int64_t v
     const int stage_floats = mlp_stage_floats(M);
     const int staged = stage_floats <= kMlpStageMaxFloats;
     const size_t lds = staged ? (size_t)stage_floats * sizeof(float) : 0;
-    {
-        static size_t granted = 0;
-        const int rc_lds = ensure_dynamic_lds((const void *)k_front, lds, &granted);
-        if (rc_lds != KVQ_OK) return rc_lds;
-    }
-    if (cache) {                                                   // host-side length bound: after the last check
+    const int rc_f = logits_dtype == KVQ_DTYPE_F32   ? launch_front<float>(F, M, cv, n, lds, staged, st)
+                     : logits_dtype == KVQ_DTYPE_F16 ? launch_front<__half>(F, M, cv, n, lds, staged, st)
+                                                     : launch_front<Bf16>(F, M, cv, n, lds, staged, st);
+    if (rc_f != KVQ_OK) return rc_f;
+    if (cache) {                                                   // host-side length bound: the launch is queued
         cache->len_bound += 1;
         if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;
     }
-    hipLaunchKernelGGL(k_front, dim3((unsigned)n), dim3(kFrontGroups * kFeatThreads), lds, st, F, M, cv, staged);
-    KVQ_HIP(hipGetLastError());
     if (update_counts) {
         hipLaunchKernelGGL(k_counts_update, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, token_ids, (long long)n,
                            (long long)vocab, (unsigned long long *)counts, (unsigned long long *)totals);
         KVQ_HIP(hipGetLastError());
     }
     return KVQ_OK;
+}
+
+extern "C" int kvq_features_controller(const float *logits, int64_t n, int64_t vocab, const int32_t *token_ids,
+                                       int64_t *counts, int64_t *totals, int32_t update_counts, const float *sum_p2,
+                                       const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp, kvq_cache *cache,
+                                       const int32_t *seq_ids, float *feats_out, uint8_t *bits_out, float *logits_out,
+                                       void *stream)
+{
+    return kvq_features_controller_typed(logits, KVQ_DTYPE_F32, n, vocab, token_ids, counts, totals, update_counts, sum_p2, attn_len,
+                                         n_q_heads, mlp, cache, seq_ids, feats_out, bits_out, logits_out, stream);
 }

@@ -409,3 +409,87 @@ def test_rule_policy_matches_the_oracle(n):
         assert len(set(got_bits.tolist())) == 4
     with pytest.raises(kvq.KvqError):
         kvq.kvq_rule_policy(torch.from_numpy(feats).to(d), kvq.make_rule(w, 0.0, [0.5, 0.4, 0.9]), bits)
+
+
+# ---- 16-bit logits: the features are those of the exactly widened row --------------------------------------
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("n,vocab", [(1, 49152), (32, 49152), (5, 5003), (3, 4099), (2, 7), (70, 8192)])
+def test_narrow_logits_give_the_features_of_the_widened_row(dtype, n, vocab):
+    say("typed features %s n=%d vocab=%d" % (dtype, n, vocab))
+    d = dev()
+    Hq = 6
+    cfg = wl.CONFIGS[4]
+    Ws, bs = wl.calibrated_mlp(cfg)
+    mlp = kvq.MlpWeights([torch.from_numpy(w).to(d) for w in Ws], [torch.from_numpy(b).to(d) for b in bs])
+    logits, ids, counts, N, Vobs, lens, p2 = _front_inputs(n, vocab, Hq, 4000 + n + vocab)
+    # an odd vocabulary makes rows of a 16-bit type start at 2-byte (not 16-byte) boundaries: the peel is exercised
+    t_narrow = torch.from_numpy(logits).to(dtype).to(d)
+    widened = t_narrow.to(torch.float32).cpu().numpy()              # exact: what the kernel is asked to score
+    t = lambda a: torch.from_numpy(a).to(d)
+    t_ids, t_len, t_p2 = t(ids), t(lens), t(p2)
+    var = (p2.astype(np.float64) / lens[:, None] - 1.0 / lens[:, None].astype(np.float64) ** 2).mean(axis=1)
+    # the oracle's attention-variance input is a probability row; here the kernels take sum_p2, so the oracle scores
+    # H, R, C and the variance column is checked against the closed form
+    want = oracle.features(widened, ids, counts, N, Vobs, np.full((n, Hq, 1), 1.0), np.ones(n, np.int32))
+
+    c_a, tot_a = t(counts), torch.tensor([N, Vobs], dtype=torch.int64, device=d)
+    ws = torch.empty(kvq.kvq_features_workspace(n, vocab), dtype=torch.uint8, device=d)
+    feats = torch.full((n, 4), float("nan"), dtype=torch.float32, device=d)
+    kvq.kvq_features_typed(t_narrow, t_ids, c_a, tot_a, True, t_len, Hq, feats, ws, sum_p2=t_p2)
+    bits = torch.zeros(n, dtype=torch.uint8, device=d)
+    lg = torch.zeros((n, 4), dtype=torch.float32, device=d)
+    kvq.kvq_controller(feats, mlp, bits, lg)
+    torch.cuda.synchronize()
+    got = feats.cpu().numpy()
+    for col in (0, 1, 3):
+        np.testing.assert_allclose(got[:, col], want[:, col], rtol=F_RTOL, atol=F_ATOL)
+    np.testing.assert_allclose(got[:, 2], var, rtol=2e-3, atol=1e-9)
+    wc, wN, wV = oracle.counts_update(ids, counts, N, Vobs)
+    assert np.array_equal(c_a.cpu().numpy(), wc) and list(tot_a.cpu().numpy()) == [wN, wV]
+
+    # the fused call on the same narrow logits: bit-identical features, logits and decisions
+    c_b, tot_b = t(counts), torch.tensor([N, Vobs], dtype=torch.int64, device=d)
+    feats2 = torch.full((n, 4), float("nan"), dtype=torch.float32, device=d)
+    bits2 = torch.zeros(n, dtype=torch.uint8, device=d)
+    lg2 = torch.zeros((n, 4), dtype=torch.float32, device=d)
+    kvq.kvq_features_controller_typed(t_narrow, t_ids, c_b, tot_b, True, t_p2, t_len, Hq, mlp, feats2, bits2, logits_out=lg2)
+    torch.cuda.synchronize()
+    assert np.array_equal(feats2.cpu().numpy().view(np.uint32), got.view(np.uint32))
+    assert np.array_equal(bits2.cpu().numpy(), bits.cpu().numpy())
+    assert np.array_equal(lg2.cpu().numpy().view(np.uint32), lg.cpu().numpy().view(np.uint32))
+    assert np.array_equal(c_b.cpu().numpy(), wc)
+
+    if dtype == torch.float32:
+        # type code F32 is the untyped call
+        c_c, tot_c = t(counts), torch.tensor([N, Vobs], dtype=torch.int64, device=d)
+        feats3 = torch.full((n, 4), float("nan"), dtype=torch.float32, device=d)
+        kvq.kvq_features(t_narrow, t_ids, c_c, tot_c, True, t_len, Hq, feats3, ws, sum_p2=t_p2)
+        torch.cuda.synchronize()
+        assert np.array_equal(feats3.cpu().numpy().view(np.uint32), got.view(np.uint32))
+
+
+def test_typed_logits_reject_unknown_type_codes_and_misaligned_rows():
+    say("typed features: error paths")
+    d = dev()
+    n, vocab, Hq = 2, 64, 2
+    lib = kvq.load_library()
+    z = torch.zeros((n, vocab + 1), dtype=torch.float16, device=d)
+    ids = torch.zeros(n, dtype=torch.int32, device=d)
+    counts = torch.zeros(vocab, dtype=torch.int64, device=d)
+    tot = torch.zeros(2, dtype=torch.int64, device=d)
+    lens = torch.ones(n, dtype=torch.int32, device=d)
+    p2 = torch.ones((n, Hq), dtype=torch.float32, device=d)
+    feats = torch.zeros((n, 4), dtype=torch.float32, device=d)
+    ws = torch.empty(kvq.kvq_features_workspace(n, vocab), dtype=torch.uint8, device=d)
+
+    def call(ptr, code):
+        return lib.kvq_features_typed(ptr, code, n, vocab, ids.data_ptr(), counts.data_ptr(), tot.data_ptr(), 0, None, p2.data_ptr(),
+                                      lens.data_ptr(), Hq, 0, feats.data_ptr(), ws.data_ptr(), ws.numel(), None)
+    assert call(z.data_ptr(), 7) == kvq.KVQ_ERR_INVALID_ARG
+    assert call(z.data_ptr() + 1, kvq.DTYPE_F16) == kvq.KVQ_ERR_INVALID_ARG          # odd address for a 2-byte type
+    assert call(z.data_ptr() + 2, kvq.DTYPE_F32) == kvq.KVQ_ERR_INVALID_ARG          # 2 mod 4 for a 4-byte type
+    assert call(z.data_ptr() + 2, kvq.DTYPE_F16) == kvq.KVQ_OK                       # 2-byte aligned rows are fine
+    torch.cuda.synchronize()
+    with pytest.raises(ValueError):
+        kvq.kvq_features_typed(z.to(torch.float64)[:, :vocab].contiguous(), ids, counts, tot, False, lens, Hq, feats, ws, sum_p2=p2)
