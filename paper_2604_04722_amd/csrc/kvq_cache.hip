@@ -335,20 +335,32 @@ __device__ __forceinline__ uint32_t quantize_lane(uint32_t (&p)[32], float level
     const __half sh = __float2half_rn(scale32);
     const float s = __half2float(sh);
     const float inv = s != 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f;  // s == 0: every quotient reads 0, every code is 0
+    // four elements at a time: one near-tie test (and one rarely taken branch) per group keeps the common path a
+    // straight run of independent chains.  d >= 0 always (mn is the minimum), so only the upper clamp is needed.
+    constexpr float kNearTie = 0.5f - 0x1p-12f;
+    const uint32_t ilevels = (uint32_t)levels;
 #pragma unroll
-    for (int m = 0; m < 32; ++m) {
-        const f16x2 x = __builtin_bit_cast(f16x2, p[m]);
-        uint32_t c[2];
+    for (int m = 0; m < 32; m += 2) {
+        const f16x2 x0 = __builtin_bit_cast(f16x2, p[m]), x1 = __builtin_bit_cast(f16x2, p[m + 1]);
+        const float d[4] = {(float)x0[0] - mn, (float)x0[1] - mn, (float)x1[0] - mn, (float)x1[1] - mn};
+        float r[4];
+        bool near = false;
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const float d = (float)x[e] - mn;
-            const float q = d * inv;
-            float r = rintf(q);
-            if (fabsf(q - r) > 0.5f - 0x1p-12f) r = rintf(d / s);
-            r = fminf(fmaxf(r, 0.0f), levels);
-            c[e] = (uint32_t)r;
+        for (int e = 0; e < 4; ++e) {
+            const float q = d[e] * inv;
+            r[e] = rintf(q);
+            near |= fabsf(q - r[e]) > kNearTie;
         }
+        if (near) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = rintf(d[e] / s);
+        }
+        // r is a non-negative whole number (or an overflow that the conversion saturates): clamp as an integer
+        uint32_t c[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = min((uint32_t)r[e], ilevels);
         p[m] = c[0] | (c[1] << 16);
+        p[m + 1] = c[2] | (c[3] << 16);
     }
     return (uint32_t)__half_as_ushort(sh) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
 }
