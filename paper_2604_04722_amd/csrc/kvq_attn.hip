@@ -634,7 +634,7 @@ __device__ __forceinline__ void run_fp16(const ClassWalk &w, int k0, int k1, int
     }
 }
 
-__device__ __forceinline__ int ceil_div_pos(long long a, int b) { return (int)((a + b - 1) / b); }
+__device__ __forceinline__ int ceil_div_pos(uint32_t a, uint32_t b) { return (int)((a + b - 1u) / b); }
 
 // Static per-channel keys, class C: q' = q (.) step_C as fp16 pairs q2 plus the fp16 remainders q2l (scaled by
 // kLoScale; the product of two fp16 numbers is exact in fp32, so q2 + q2l / kLoScale carries it to ~2^-22), read back
@@ -756,7 +756,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     int cnt[kClasses], nu[kClasses];
     const int *env_w = P.wgt;
     const int wgt[kClasses] = {env_w[0], env_w[1], env_w[2], env_w[3]};
-    long long wtot = 0;
+    uint32_t wtot = 0;                                       // below 2^31: the host checks units x weight before the launch
     // Fused append: the newest token of the sequence (logged by the bookkeeping kernel, slot = last of its class)
     // is not read from the cache.  It is quantized in registers from k_new / v_new, joins the softmax as one extra
     // partial result, and the workgroup with s == 0, g == 0 stores it for later steps.
@@ -799,23 +799,31 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         cnt[c] = seq_ok ? cv.counts[(size_t)seq * 5 + c] : 0;
         if (has_new && c == new_cls) cnt[c] -= 1;
         nu[c] = (cnt[c] + class_unit_blocks(c) * kBlockTokens - 1) / (class_unit_blocks(c) * kBlockTokens);
-        wtot += (long long)nu[c] * wgt[c];
+        wtot += (uint32_t)nu[c] * (uint32_t)wgt[c];
     }
     const bool strided = P.strided != 0;
     const int J = strided ? S : S * NW, j = strided ? s : s * NW + wave;
-    const long long lo_w = wtot * j / J, hi_w = wtot * (j + 1) / J;
-    long long wbase = 0;
+    // 64-bit division is a long emulated routine, and this runs before a wave's first load: 32 bits whenever
+    // wtot * J fits (it does unless a context has millions of tokens)
+    uint32_t lo_w, hi_w;
+    if (((unsigned long long)wtot * (uint32_t)J) >> 32 == 0) {
+        lo_w = wtot * (uint32_t)j / (uint32_t)J;
+        hi_w = wtot * (uint32_t)(j + 1) / (uint32_t)J;
+    } else {
+        lo_w = (uint32_t)((unsigned long long)wtot * (uint32_t)j / (uint32_t)J);
+        hi_w = (uint32_t)((unsigned long long)wtot * (uint32_t)(j + 1) / (uint32_t)J);
+    }
+    uint32_t wbase = 0;
     int first[kClasses], last[kClasses], dealt = 0;
     const int step = strided ? NW : 1;
 #pragma unroll
     for (int c = 0; c < kClasses; ++c) {
-        const long long a = lo_w - wbase, b = hi_w - wbase;
-        const int klo = min(a <= 0 ? 0 : ceil_div_pos(a, wgt[c]), nu[c]);
-        const int khi = min(b <= 0 ? 0 : ceil_div_pos(b, wgt[c]), nu[c]);
+        const int klo = min(lo_w <= wbase ? 0 : ceil_div_pos(lo_w - wbase, (uint32_t)wgt[c]), nu[c]);
+        const int khi = min(hi_w <= wbase ? 0 : ceil_div_pos(hi_w - wbase, (uint32_t)wgt[c]), nu[c]);
         first[c] = strided ? klo + ((wave + NW - (dealt % NW)) % NW) : klo;
         last[c] = khi;
         dealt += khi - klo;
-        wbase += (long long)nu[c] * wgt[c];
+        wbase += (uint32_t)nu[c] * (uint32_t)wgt[c];
     }
     ClassWalk w;
     w.Hkv = cv.Hkv; w.kvh = kvh; w.bpp = cv.blocks_per_page; w.bpp_log2 = 31 - __builtin_clz(cv.blocks_per_page);
@@ -951,6 +959,11 @@ static int plan_attn(const kvq_cache *cache, int32_t n_seq, int extra_tokens, co
 {
     const kvq_cache_desc &d = cache->desc;
     const long long heads = (long long)n_seq * d.n_q_heads;
+    // the kernel sums units x weight (at most 255) of one sequence in 32 bits
+    if ((d.max_context / kBlockTokens + 4) * 4 * 255 >= (1LL << 31)) {
+        set_error("max_context %lld is beyond what the attention kernel's unit arithmetic covers", (long long)d.max_context);
+        return KVQ_ERR_UNSUPPORTED;
+    }
     // Work distribution: two waves fit a SIMD, 2048 on the chip, and a launch whose waves are all resident at once has
     // no second, under-filled round.  So a (sequence, query head) gets about 2048 / heads waves, but no more than one
     // per four units (10-16 KiB each), or the per-class pipelines never reach steady state.  Up to eight of them sit
@@ -1008,6 +1021,7 @@ static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t lay
     // FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost VALU time for unpacking,
     // and the ratios below are the ones that equalise the finishing times of a workgroup's waves (measured).
     P.wgt[0] = env_int("KVQ_W0", 14); P.wgt[1] = env_int("KVQ_W1", 11); P.wgt[2] = env_int("KVQ_W2", 17); P.wgt[3] = env_int("KVQ_W3", 32);
+    for (int c = 0; c < 4; ++c) P.wgt[c] = P.wgt[c] < 1 ? 1 : P.wgt[c] > 255 ? 255 : P.wgt[c];
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
