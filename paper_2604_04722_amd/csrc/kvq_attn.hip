@@ -128,6 +128,7 @@ struct QConst {
 struct AttnParams {
     CacheView cv;
     int32_t wgt[4];
+    int32_t by_class;        // short ranges: whole waves per class (0 switches it off)
     int32_t strided;
     const uint32_t *q;          // [n_seq][Hq][32] fp16 pairs
     const __half *k_new, *v_new; // fused append: the new token's K/V [n_seq][Hkv][64], or nullptr
@@ -682,6 +683,16 @@ template <int NW, bool KCH>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAVES_PER_EU, KVQ_WAVES_PER_EU))) void k_decode_split(AttnParams P)
 {
     const CacheView &cv = P.cv;
+    // The arguments live in memory and the compiler would fetch each where it is first used: a dozen scalar loads,
+    // each waited for on its own, before the first byte of the cache is asked for.  Asking for them here makes them
+    // one batch behind a single wait.
+#define KVQ_FETCH_NOW(x) asm volatile("" : : "s"(x))
+    KVQ_FETCH_NOW(P.S); KVQ_FETCH_NOW(P.n_seq); KVQ_FETCH_NOW(P.longest_first); KVQ_FETCH_NOW(P.seq_ids); KVQ_FETCH_NOW(P.q);
+    KVQ_FETCH_NOW(P.k_new); KVQ_FETCH_NOW(P.layer); KVQ_FETCH_NOW(P.strided); KVQ_FETCH_NOW(P.by_class);
+    KVQ_FETCH_NOW(P.wgt[0]); KVQ_FETCH_NOW(P.wgt[1]); KVQ_FETCH_NOW(P.wgt[2]); KVQ_FETCH_NOW(P.wgt[3]);
+    KVQ_FETCH_NOW(cv.Hq); KVQ_FETCH_NOW(cv.Hkv); KVQ_FETCH_NOW(cv.max_seqs); KVQ_FETCH_NOW(cv.counts); KVQ_FETCH_NOW(cv.last_rec);
+    KVQ_FETCH_NOW(cv.page_table); KVQ_FETCH_NOW(cv.max_pages_per_seq); KVQ_FETCH_NOW(cv.blocks_per_page);
+#undef KVQ_FETCH_NOW
     const int G = cv.Hq / cv.Hkv;
     const int S = P.S;
     const int nunits = P.n_seq * cv.Hq * S;
@@ -724,6 +735,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     const bool seq_ok = seq >= 0 && seq < cv.max_seqs;
     if (!seq_ok) seq = 0;
 
+    // the sequence's class counts and newest-token record are asked for before the query, so that the three answers
+    // travel together: what follows the query (ranges, first page, first block) hangs on the counts
+    int cnt[kClasses];
+#pragma unroll
+    for (int c = 0; c < kClasses; ++c) cnt[c] = seq_ok ? cv.counts[(size_t)seq * 5 + c] : 0;
+    int4 rec = make_int4(0, 0, 0, 0);                                        // {last_T, bits, slot, page} of the newest token
+    if (P.k_new != nullptr && seq_ok) rec = *(const int4 *)(cv.last_rec + (size_t)seq * 4);
+
     // the query as 32 fp16 pairs (wave-uniform), sum(q), and the per-class target sums
     uint32_t q2[32];
     const uint32_t *qp = P.q + ((size_t)si * cv.Hq + qh) * 32;
@@ -753,7 +772,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     // This wave's share of the (sequence, kv-head)'s units: the units of the four classes form one list,
     // weighted by their cost; the S workgroups x NW waves cut the list into S*NW contiguous ranges of
     // equal weight (a unit belongs to the range that holds its start), so a wave meets one or two classes.
-    int cnt[kClasses], nu[kClasses];
+    int nu[kClasses];
     const int *env_w = P.wgt;
     const int wgt[kClasses] = {env_w[0], env_w[1], env_w[2], env_w[3]};
     uint32_t wtot = 0;                                       // below 2^31: the host checks units x weight before the launch
@@ -763,7 +782,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     bool has_new = false;
     int new_bits = 16, new_cls = 3, new_slot = 0, new_page = 0;
     if (P.k_new != nullptr && seq_ok) {
-        const int4 rec = *(const int4 *)(cv.last_rec + (size_t)seq * 4);     // {last_T, bits, slot, page} of the newest token
         if (rec.x == 1) {
             new_bits = rec.y;
             new_slot = rec.z;
@@ -796,34 +814,89 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     }
 #pragma unroll
     for (int c = 0; c < kClasses; ++c) {
-        cnt[c] = seq_ok ? cv.counts[(size_t)seq * 5 + c] : 0;
         if (has_new && c == new_cls) cnt[c] -= 1;
         nu[c] = (cnt[c] + class_unit_blocks(c) * kBlockTokens - 1) / (class_unit_blocks(c) * kBlockTokens);
         wtot += (uint32_t)nu[c] * (uint32_t)wgt[c];
     }
     const bool strided = P.strided != 0;
     const int J = strided ? S : S * NW, j = strided ? s : s * NW + wave;
-    // 64-bit division is a long emulated routine, and this runs before a wave's first load: 32 bits whenever
-    // wtot * J fits (it does unless a context has millions of tokens)
-    uint32_t lo_w, hi_w;
-    if (((unsigned long long)wtot * (uint32_t)J) >> 32 == 0) {
-        lo_w = wtot * (uint32_t)j / (uint32_t)J;
-        hi_w = wtot * (uint32_t)(j + 1) / (uint32_t)J;
-    } else {
-        lo_w = (uint32_t)((unsigned long long)wtot * (uint32_t)j / (uint32_t)J);
-        hi_w = (uint32_t)((unsigned long long)wtot * (uint32_t)(j + 1) / (uint32_t)J);
-    }
-    uint32_t wbase = 0;
-    int first[kClasses], last[kClasses], dealt = 0;
+    int first[kClasses] = {0, 0, 0, 0}, last[kClasses] = {0, 0, 0, 0};
     const int step = strided ? NW : 1;
+    // Short ranges (a few units per wave: small batches, short contexts): a wave that crosses from one class into the
+    // next pays that class's pipeline start, a full memory latency, a second time, and its workgroup waits for it.
+    // There the classes get whole waves instead, in proportion to their weight (at least one for a class that has
+    // units; what rounding leaves over goes where the load per wave is largest), and a wave's range lies inside
+    // its class.  Every wave of the (sequence, head) computes the same allocation from the same numbers, so the
+    // quotients may be reciprocal approximations: the ranges tile a class whatever their exact cut points are.
+    const uint32_t nu_tot = (uint32_t)(nu[0] + nu[1] + nu[2] + nu[3]);
+    const int nonempty = (nu[0] > 0) + (nu[1] > 0) + (nu[2] > 0) + (nu[3] > 0);
+    bool ranged = false;
+    if (!strided && P.by_class && nonempty > 1 && J >= 2 * nonempty && nu_tot <= 6u * (uint32_t)J) {
+        uint32_t wc[kClasses];
+        int nwc[kClasses], used = 0;
+        const float per_weight = (float)J * __builtin_amdgcn_rcpf((float)wtot);
 #pragma unroll
-    for (int c = 0; c < kClasses; ++c) {
-        const int klo = min(lo_w <= wbase ? 0 : ceil_div_pos(lo_w - wbase, (uint32_t)wgt[c]), nu[c]);
-        const int khi = min(hi_w <= wbase ? 0 : ceil_div_pos(hi_w - wbase, (uint32_t)wgt[c]), nu[c]);
-        first[c] = strided ? klo + ((wave + NW - (dealt % NW)) % NW) : klo;
-        last[c] = khi;
-        dealt += khi - klo;
-        wbase += (uint32_t)nu[c] * (uint32_t)wgt[c];
+        for (int c = 0; c < kClasses; ++c) {
+            wc[c] = (uint32_t)nu[c] * (uint32_t)wgt[c];
+            nwc[c] = wc[c] ? max(1, (int)((float)wc[c] * per_weight)) : 0;
+            used += nwc[c];
+        }
+        for (int it = 0; it < 2 * kClasses && used != J; ++it) {
+            const bool more = used < J;
+            int pick = -1;
+            uint32_t pw = 0, pn = 1;                                // the picked class's weight and wave count (less one when taking away)
+#pragma unroll
+            for (int c = 0; c < kClasses; ++c) {
+                const uint32_t n = (uint32_t)(more ? nwc[c] : nwc[c] - 1);
+                // more: the class with the largest load per wave gets one more; else: the class whose load per wave
+                // rises least (smallest weight per remaining wave) gives one back
+                const bool ok = more ? nwc[c] > 0 : nwc[c] > 1;
+                const bool better = pick < 0 || (more ? wc[c] * pn > pw * n : wc[c] * pn < pw * n);
+                if (ok && better) { pick = c; pw = wc[c]; pn = n; }
+            }
+            if (pick < 0) break;
+            const int d = more ? 1 : -1;
+#pragma unroll
+            for (int c = 0; c < kClasses; ++c)
+                if (c == pick) nwc[c] += d;
+            used += d;
+        }
+        if (used == J) {
+            int jc = j;
+#pragma unroll
+            for (int c = 0; c < kClasses; ++c) {
+                if (jc >= 0 && jc < nwc[c]) {
+                    const float per_wave = (float)nu[c] * __builtin_amdgcn_rcpf((float)nwc[c]);
+                    first[c] = min((int)((float)jc * per_wave), nu[c]);
+                    last[c] = jc + 1 == nwc[c] ? nu[c] : min((int)((float)(jc + 1) * per_wave), nu[c]);
+                }
+                jc -= nwc[c];
+            }
+            ranged = true;
+        }
+    }
+    if (!ranged) {
+        // 64-bit division is a long emulated routine, and this runs before a wave's first load: 32 bits whenever
+        // wtot * J fits (it does unless a context has millions of tokens)
+        uint32_t lo_w, hi_w;
+        if (((unsigned long long)wtot * (uint32_t)J) >> 32 == 0) {
+            lo_w = wtot * (uint32_t)j / (uint32_t)J;
+            hi_w = wtot * (uint32_t)(j + 1) / (uint32_t)J;
+        } else {
+            lo_w = (uint32_t)((unsigned long long)wtot * (uint32_t)j / (uint32_t)J);
+            hi_w = (uint32_t)((unsigned long long)wtot * (uint32_t)(j + 1) / (uint32_t)J);
+        }
+        uint32_t wbase = 0;
+        int dealt = 0;
+#pragma unroll
+        for (int c = 0; c < kClasses; ++c) {
+            const int klo = min(lo_w <= wbase ? 0 : ceil_div_pos(lo_w - wbase, (uint32_t)wgt[c]), nu[c]);
+            const int khi = min(hi_w <= wbase ? 0 : ceil_div_pos(hi_w - wbase, (uint32_t)wgt[c]), nu[c]);
+            first[c] = strided ? klo + ((wave + NW - (dealt % NW)) % NW) : klo;
+            last[c] = khi;
+            dealt += khi - klo;
+            wbase += (uint32_t)nu[c] * (uint32_t)wgt[c];
+        }
     }
     ClassWalk w;
     w.Hkv = cv.Hkv; w.kvh = kvh; w.bpp = cv.blocks_per_page; w.bpp_log2 = 31 - __builtin_clz(cv.blocks_per_page);
@@ -848,16 +921,35 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
 #undef KVQ_WALK
 
     // ---- sum the 64 lanes: a transposing butterfly leaves channel c's total in lane c ----------------
+    // Level `half` pairs lane l with lane l ^ half: the lanes with that bit clear end up with the sum of acc[i], the
+    // others with the sum of acc[i + half].  The two widest levels are the half- and row-swap instructions of this
+    // chip (v_permlane32_swap exchanges lanes 32..63 of one register with lanes 0..31 of another, v_permlane16_swap the
+    // odd 16-lane rows of one with the even rows of the other): one swap and one add per pair.  The narrow levels are
+    // data-parallel-primitive moves inside a row of 16 lanes.  No LDS traffic at all.
 #pragma unroll
-    for (int half = 32; half >= 1; half >>= 1) {
-        const bool upper = (lane & half) != 0;
-#pragma unroll
-        for (int i = 0; i < half; ++i) {
-            const float keep = upper ? st.acc[i + half] : st.acc[i];
-            const float send = upper ? st.acc[i] : st.acc[i + half];
-            st.acc[i] = keep + __shfl_xor(send, half, 64);
-        }
+    for (int i = 0; i < 32; ++i) {
+        const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(st.acc[i]), __float_as_uint(st.acc[i + 32]), false, false);
+        st.acc[i] = __uint_as_float(r.x) + __uint_as_float(r.y);
     }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(st.acc[i]), __float_as_uint(st.acc[i + 16]), false, false);
+        st.acc[i] = __uint_as_float(r.x) + __uint_as_float(r.y);
+    }
+#define KVQ_LEVEL(HALF, RECV)                                                  \
+    {                                                                          \
+        const bool upper = (lane & (HALF)) != 0;                               \
+        _Pragma("unroll") for (int i = 0; i < (HALF); ++i) {                   \
+            const float keep = upper ? st.acc[i + (HALF)] : st.acc[i];         \
+            const float send = upper ? st.acc[i] : st.acc[i + (HALF)];         \
+            st.acc[i] = keep + (RECV);                                         \
+        }                                                                      \
+    }
+    KVQ_LEVEL(8, dpp_mov<0x128>(send))                     // row_ror:8 = lane ^ 8 inside a row
+    KVQ_LEVEL(4, dpp_mov<0x141>(dpp_mov<0x1B>(send)))      // quad_perm [3,2,1,0] (lane ^ 3), then row_half_mirror (lane ^ 7)
+    KVQ_LEVEL(2, dpp_mov<0x4E>(send))                      // quad_perm [2,3,0,1]
+    KVQ_LEVEL(1, dpp_mov<0xB1>(send))                      // quad_perm [1,0,3,2]
+#undef KVQ_LEVEL
     const float l = wave_sum(st.l), l2 = wave_sum(st.l2), z = wave_sum(st.z);
     const float ps0 = wave_sum(st.ps[0]), ps1 = wave_sum(st.ps[1]), ps2 = wave_sum(st.ps[2]);
     // channel `lane`: its pair index inside a word decides which target multiplier it was scaled with
@@ -897,7 +989,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
             if (P.p2) P.p2[oi] = L2 * inv * inv;
         }
     } else {
-        float *wsu = P.ws + (size_t)unit * kPartialFloats;
+        float *wsu = P.ws + (size_t)unit * kPartialFloats;           // a second kernel merges the S partial results
         wsu[lane] = o;
         if (lane == 0) { wsu[64] = M; wsu[65] = L; wsu[66] = L2; }
     }
@@ -1017,6 +1109,7 @@ static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t lay
     P.n_seq = n_seq;
     P.S = (int)S;
     P.strided = env_int("KVQ_STRIDED", 0);
+    P.by_class = env_int("KVQ_ATTN_BY_CLASS", 1);
     // Relative cost of one unit of each class (2 bit: 128 tokens, 5 KiB; 4 bit: 64 tokens, 4.5 KiB; 8 bit: 8.5 KiB;
     // FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost VALU time for unpacking,
     // and the ratios below are the ones that equalise the finishing times of a workgroup's waves (measured).
@@ -1027,6 +1120,7 @@ static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t lay
     hipStream_t st = (hipStream_t)stream;
     P.longest_first = env_int("KVQ_ATTN_LONGEST_FIRST", (n_seq <= 64 && n_seq % 8 == 0 && heads * S * nw > 2048) ? 1 : 0);
     if (n_seq > 64 || n_seq % 8 != 0) P.longest_first = 0;
+    if (S > 1) P.longest_first = 0;                               // the merging kernel looks partial results up by output row
     if (!cache->view.k_channel) {
         if (nw == 1) hipLaunchKernelGGL((k_decode_split<1, false>), dim3(grid), dim3(64), 0, st, P);
         else if (nw == 2) hipLaunchKernelGGL((k_decode_split<2, false>), dim3(grid), dim3(128), 0, st, P);
