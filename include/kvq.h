@@ -60,7 +60,7 @@ typedef struct {
     int32_t n_kv_heads;      /* Hkv; query head h reads kv-head h / (Hq/Hkv) */
     int32_t head_dim;        /* must be 64 */
     int32_t page_tokens;     /* tokens per page, a power of two >= 256; 0 selects 256 */
-    int64_t max_context;     /* largest number of tokens one sequence may hold */
+    int64_t max_context;     /* largest number of tokens one sequence may hold, 1 .. 2^26 */
     int64_t pool_pages[4];   /* pages available to the 2/4/8/16-bit classes; 0 = enough for every
                                 sequence to put max_context tokens into that class */
     void *arena;             /* device memory for the whole cache, 256-byte aligned, or NULL to let

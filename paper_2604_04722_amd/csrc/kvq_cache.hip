@@ -96,7 +96,8 @@ static bool valid_desc(const kvq_cache_desc *d)
     }
     const int P = d->page_tokens ? d->page_tokens : 256;
     if (P < 256 || (P & (P - 1)) != 0 || P > (1 << 20)) { set_error("page_tokens must be a power of two, at least 256"); return false; }
-    if (d->max_context < 1 || d->max_context > (int64_t)0x7fff0000) { set_error("max_context out of range"); return false; }
+    // the upper limit keeps a sequence's units x class weight inside 32 bits in the attention kernel
+    if (d->max_context < 1 || d->max_context > ((int64_t)1 << 26)) { set_error("max_context out of range (1 .. 2^26)"); return false; }
     const int64_t mpps = (d->max_context + P - 1) / P;
     for (int c = 0; c < kClasses; ++c) {
         if (d->pool_pages[c] < 0 || d->pool_pages[c] > 0x7ffffff0) { set_error("pool_pages[%d] out of range", c); return false; }

@@ -75,7 +75,7 @@ def test_default_pools_cover_the_worst_case(lib):
 
 
 @pytest.mark.parametrize("kw", [dict(head_dim=128), dict(n_q_heads=30), dict(page_tokens=100), dict(max_context=0),
-                                dict(n_layers=0), dict(pool_pages=(-1, 0, 0, 0))])
+                                dict(n_layers=0), dict(pool_pages=(-1, 0, 0, 0)), dict(max_context=(1 << 26) + 1)])
 def test_invalid_descriptors_are_rejected_on_the_host(lib, kw):
     d = make_desc(**kw)
     assert lib.kvq_cache_arena_bytes(ctypes.byref(d)) == 0
