@@ -128,7 +128,7 @@ struct QConst {
 struct AttnParams {
     CacheView cv;
     int32_t wgt[4];
-    int32_t by_class;        // short ranges: whole waves per class (0 switches it off)
+    int32_t by_class;        // whole waves per class when a wave has at most this many units on average (0: never)
     int32_t strided;
     const uint32_t *q;          // [n_seq][Hq][32] fp16 pairs
     const __half *k_new, *v_new; // fused append: the new token's K/V [n_seq][Hkv][64], or nullptr
@@ -822,16 +822,17 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     const int J = strided ? S : S * NW, j = strided ? s : s * NW + wave;
     int first[kClasses] = {0, 0, 0, 0}, last[kClasses] = {0, 0, 0, 0};
     const int step = strided ? NW : 1;
-    // Short ranges (a few units per wave: small batches, short contexts): a wave that crosses from one class into the
-    // next pays that class's pipeline start, a full memory latency, a second time, and its workgroup waits for it.
-    // There the classes get whole waves instead, in proportion to their weight (at least one for a class that has
-    // units; what rounding leaves over goes where the load per wave is largest), and a wave's range lies inside
-    // its class.  Every wave of the (sequence, head) computes the same allocation from the same numbers, so the
-    // quotients may be reciprocal approximations: the ranges tile a class whatever their exact cut points are.
+    // Short ranges (one workgroup per head and up to a dozen units per wave: small batches, short contexts): a wave
+    // that crosses from one class into the next pays that class's pipeline start, a full memory latency, a second
+    // time, and its workgroup waits for it.  There the classes get whole waves instead, in proportion to their weight
+    // (at least one for a class that has units; what rounding leaves over goes where the load per wave is largest),
+    // and a wave's range lies inside its class.  Every wave of the (sequence, head) computes the same allocation from
+    // the same numbers, so the quotients may be reciprocal approximations: the ranges tile a class whatever their
+    // exact cut points are.
     const uint32_t nu_tot = (uint32_t)(nu[0] + nu[1] + nu[2] + nu[3]);
     const int nonempty = (nu[0] > 0) + (nu[1] > 0) + (nu[2] > 0) + (nu[3] > 0);
     bool ranged = false;
-    if (!strided && P.by_class && nonempty > 1 && J >= 2 * nonempty && nu_tot <= 6u * (uint32_t)J) {
+    if (!strided && S == 1 && nonempty > 1 && J >= 2 * nonempty && nu_tot <= (uint32_t)P.by_class * (uint32_t)J) {
         uint32_t wc[kClasses];
         int nwc[kClasses], used = 0;
         const float per_weight = (float)J * __builtin_amdgcn_rcpf((float)wtot);
@@ -1109,7 +1110,7 @@ static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t lay
     P.n_seq = n_seq;
     P.S = (int)S;
     P.strided = env_int("KVQ_STRIDED", 0);
-    P.by_class = env_int("KVQ_ATTN_BY_CLASS", 1);
+    P.by_class = env_int("KVQ_ATTN_BY_CLASS", 12);
     // Relative cost of one unit of each class (2 bit: 128 tokens, 5 KiB; 4 bit: 64 tokens, 4.5 KiB; 8 bit: 8.5 KiB;
     // FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost VALU time for unpacking,
     // and the ratios below are the ones that equalise the finishing times of a workgroup's waves (measured).
