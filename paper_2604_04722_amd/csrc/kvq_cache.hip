@@ -367,7 +367,10 @@ __device__ __forceinline__ uint32_t quantize_lane(uint32_t (&p)[32], float level
 }
 
 // packs the lane's 32 pair registers into the words of class C and stores them as 16-byte chunks
-template <int C> __device__ __forceinline__ void pack_store(const uint32_t (&p)[32], uint8_t *codes, int tok)
+// `streaming`: the wavefront holds a long run of this class, its piece of each chunk row is mostly whole cache
+// lines, and the stores go past the cache (non-temporal); short pieces are stored normally so that the lines they
+// share with the neighbouring tiles' pieces are put together in the cache before they reach memory.
+template <int C> __device__ __forceinline__ void pack_store(const uint32_t (&p)[32], uint8_t *codes, int tok, bool streaming)
 {
     constexpr int b = class_bits(C);
     constexpr int PW = 16 / b;                                      // pair registers per 32-bit word
@@ -382,7 +385,11 @@ template <int C> __device__ __forceinline__ void pack_store(const uint32_t (&p)[
             for (int j = 0; j < PW; ++j) word |= p[(4 * c + k) * PW + j] << (b * j);
             o[k] = word;
         }
-        *(u32x4 *)(codes + (size_t)c * (kBlockTokens * 16) + tok * 16) = o;
+        u32x4 *dst = (u32x4 *)(codes + (size_t)c * (kBlockTokens * 16) + tok * 16);
+        // the streaming form is spelled out: two stores that differ only in the non-temporal hint are merged into
+        // one plain store by the optimizer
+        if (streaming) asm volatile("global_store_dwordx4 %0, %1, off nt" : : "v"(dst), "v"(o) : "memory");
+        else *dst = o;
     }
 }
 
@@ -418,20 +425,20 @@ __device__ __forceinline__ void tile_transpose(const u32x4 (&x)[8], uint32_t (&p
     __builtin_amdgcn_wave_barrier();
 }
 
-__device__ __forceinline__ void quantize_pack_store(uint32_t (&p)[32], int cls, uint8_t *codes, uint32_t *meta, int tok)
+__device__ __forceinline__ void quantize_pack_store(uint32_t (&p)[32], int cls, uint8_t *codes, uint32_t *meta, int tok, uint32_t streaming)
 {
     if (cls != 3) *meta = quantize_lane(p, (float)((1 << (2 << cls)) - 1));
     switch (cls) {
-    case 0: pack_store<0>(p, codes, tok); break;
-    case 1: pack_store<1>(p, codes, tok); break;
-    case 2: pack_store<2>(p, codes, tok); break;
-    default: pack_store<3>(p, codes, tok); break;
+    case 0: pack_store<0>(p, codes, tok, (streaming & 1u) != 0); break;
+    case 1: pack_store<1>(p, codes, tok, (streaming & 2u) != 0); break;
+    case 2: pack_store<2>(p, codes, tok, (streaming & 4u) != 0); break;
+    default: pack_store<3>(p, codes, tok, (streaming & 8u) != 0); break;
     }
 }
 
 // One wavefront per (layer, sequence, tile of 64 input tokens, kv-head); k and v must be 16-byte aligned.
 __global__ __launch_bounds__(256) void k_append_bulk(CacheView cv, int layer, const __half *k, const __half *v,
-                                                     const int32_t *seq_ids, int n_seq, int T, int tiles, long long total_waves)
+                                                     const int32_t *seq_ids, int n_seq, int T, int tiles, long long total_waves, int P_stream_min)
 {
     __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][kBlockTokens * kStageRow];
     const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
@@ -476,9 +483,15 @@ __global__ __launch_bounds__(256) void k_append_bulk(CacheView cv, int layer, co
 
     tile_transpose(x, p, stage, lane);
     tile_load(x, v + src, row_halves, nrow, lane);                 // V is in flight while K is quantized
-    if (valid) quantize_pack_store(p, cls, base + meta_bytes, meta, tok);
+    // which classes have a long run in this tile (bit c: at least P_stream_min of the 64 tokens, i.e. pieces of 256 bytes
+    // and more per chunk row with the default of 16)
+    uint32_t streaming = 0;
+#pragma unroll
+    for (int c = 0; c < kClasses; ++c)
+        if (__popcll(__ballot(valid && cls == c)) >= P_stream_min) streaming |= 1u << c;
+    if (valid) quantize_pack_store(p, cls, base + meta_bytes, meta, tok, streaming);
     tile_transpose(x, p, stage, lane);
-    if (valid) quantize_pack_store(p, cls, base + meta_bytes + region, meta + 1, tok);
+    if (valid) quantize_pack_store(p, cls, base + meta_bytes + region, meta + 1, tok, streaming);
 }
 
 // Canonical dump of one (layer, sequence): one wavefront per (token, kv-head), lane = element.
@@ -805,7 +818,8 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
         const int tiles = (T + kBlockTokens - 1) / kBlockTokens;
         const long long waves = nl * n_seq * (long long)tiles * d.n_kv_heads;
         hipLaunchKernelGGL(k_append_bulk, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer,
-                           (const __half *)k, (const __half *)v, seq_ids, n_seq, T, tiles, waves);
+                           (const __half *)k, (const __half *)v, seq_ids, n_seq, T, tiles, waves,
+                           getenv("KVQ_APPEND_STREAM_MIN") ? atoi(getenv("KVQ_APPEND_STREAM_MIN")) : 16);
     } else {
         hipLaunchKernelGGL(k_append_write, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, st, cache->view, layer,
                            (const __half *)k, (const __half *)v, seq_ids, n_seq, T, total);
