@@ -14,6 +14,7 @@ constexpr int kFeatThreads = 256;
 constexpr int kMaxSlices = 64;
 
 struct Lse3 { float m, s, t; };
+typedef uint32_t u32x4_nt __attribute__((ext_vector_type(4)));
 
 // e^d for d <= 0 through the hardware 2^x: relative error below 2e-6 over the range that still contributes to a
 // sum (d > -20), which is a tenth of the tolerance of the features; the library routine costs ten times the issue
@@ -96,7 +97,8 @@ template <> __device__ __forceinline__ void lse3_add_vec<Bf16>(Lse3 &a, const ui
 }
 
 // (m, S, T) of the part of one slice of a logits row that thread `lt` of kFeatThreads takes
-template <typename T>
+// Stream: the rows are read once and are too many to stay in any cache (a bulk call), so the loads go past the caches.
+template <typename T, bool Stream = false>
 __device__ __forceinline__ Lse3 thread_partial(const T *logits, long long vocab, int slices, long long row, int slice, int lt)
 {
     constexpr int kPer = 16 / (int)sizeof(T);             // logits per 16-byte load
@@ -122,7 +124,12 @@ __device__ __forceinline__ Lse3 thread_partial(const T *logits, long long vocab,
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const long long k = i + u * kFeatThreads;
-                v[u] = p4[k < n4 ? k : i];
+                if constexpr (Stream) {
+                    const u32x4_nt t = __builtin_nontemporal_load((const u32x4_nt *)(p4 + (k < n4 ? k : i)));
+                    v[u] = make_uint4(t[0], t[1], t[2], t[3]);
+                } else {
+                    v[u] = p4[k < n4 ? k : i];
+                }
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
@@ -159,13 +166,13 @@ __device__ __forceinline__ void group_merge(Lse3 *sm, int lt)
     __syncthreads();
 }
 
-template <typename T>
+template <typename T, bool Stream>
 __global__ __launch_bounds__(kFeatThreads) void k_lse_partial(const T *logits, long long vocab, int slices, float *ws)
 {
     __shared__ Lse3 sm[kFeatThreads];
     const long long row = blockIdx.y;
     const int slice = blockIdx.x;
-    sm[threadIdx.x] = thread_partial(logits, vocab, slices, row, slice, threadIdx.x);
+    sm[threadIdx.x] = thread_partial<T, Stream>(logits, vocab, slices, row, slice, threadIdx.x);
     group_merge(sm, threadIdx.x);
     if (threadIdx.x == 0) {
         float *w = ws + (row * slices + slice) * 4;
@@ -396,7 +403,11 @@ extern "C" size_t kvq_features_workspace(int64_t n, int64_t vocab)
 template <typename T>
 static int launch_lse_partial(const void *logits, int64_t n, int64_t vocab, int slices, float *ws, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_lse_partial<T>, dim3(slices, (unsigned)n), dim3(kFeatThreads), 0, st, (const T *)logits, (long long)vocab, slices, ws);
+    // beyond what the L2 caches hold together, the logits are streamed
+    if ((long long)n * vocab * (long long)sizeof(T) >= (32LL << 20))
+        hipLaunchKernelGGL((k_lse_partial<T, true>), dim3(slices, (unsigned)n), dim3(kFeatThreads), 0, st, (const T *)logits, (long long)vocab, slices, ws);
+    else
+        hipLaunchKernelGGL((k_lse_partial<T, false>), dim3(slices, (unsigned)n), dim3(kFeatThreads), 0, st, (const T *)logits, (long long)vocab, slices, ws);
     KVQ_HIP(hipGetLastError());
     return KVQ_OK;
 }
