@@ -258,6 +258,9 @@ __global__ __launch_bounds__(256) void k_append_write(CacheView cv, int layer, c
     const int L = layer < 0 ? li : layer;
     const int seq = seq_ids ? seq_ids[si] : si;
     if (seq < 0 || seq >= cv.max_seqs) return;
+    // the vectors themselves do not depend on where they go: asked for first, they travel with the slot lookup
+    const size_t src = ((((size_t)li * n_seq + si) * T + t) * cv.Hkv + h) * kD + lane;
+    const __half kx = k[src], vx = v[src];
     int b, slot, page;
     if (T == 1) {
         // the decode step: everything about the new token in one 16-byte read
@@ -277,7 +280,6 @@ __global__ __launch_bounds__(256) void k_append_write(CacheView cv, int layer, c
     const int blk = (slot % cv.page_tokens) / kBlockTokens;
     const int tok = slot % kBlockTokens;
     uint8_t *base = cv.pool[cls] + block_offset(cv, cls, L, page, h, blk);
-    const size_t src = ((((size_t)li * n_seq + si) * T + t) * cv.Hkv + h) * kD + lane;
     const int meta_bytes = class_meta_bytes(cls);
     const size_t region = (size_t)class_chunks(cls) * kBlockTokens * 16;
     __half *meta = (__half *)(base + tok * 8);
@@ -285,11 +287,11 @@ __global__ __launch_bounds__(256) void k_append_write(CacheView cv, int layer, c
         const size_t ti = ((size_t)L * cv.Hkv + h) * kD + lane;
         const float mn = __half2float(cv.kch_min[ti]);
         const float st = __half2float(cv.kch_step[(size_t)cls * cv.n_layers * cv.Hkv * kD + ti]);
-        quantize_store_kch(k[src], b, mn, st, lane, tok, base + meta_bytes, meta);
+        quantize_store_kch(kx, b, mn, st, lane, tok, base + meta_bytes, meta);
     } else {
-        quantize_store(k[src], b, lane, tok, base + meta_bytes, meta);
+        quantize_store(kx, b, lane, tok, base + meta_bytes, meta);
     }
-    quantize_store(v[src], b, lane, tok, base + meta_bytes + region, meta + 2);
+    quantize_store(vx, b, lane, tok, base + meta_bytes + region, meta + 2);
 }
 
 // per-class steps of the static per-channel key quantizer: step = fp16(range / levels), IEEE binary32 division
