@@ -19,13 +19,15 @@ namespace kvq {
 
 constexpr int kBulkThreads = 64;     // vector-ALU bulk shape: rows per workgroup
 
-__global__ __launch_bounds__(kRowThreads) void k_mlp_row(MlpArgs A, int staged)
+// Launched with kRowThreads threads, or with 1024 for a handful of rows: the forward pass needs one thread per output
+// unit, but the weights reach LDS in one batch of loads when a thousand threads fetch them.
+__global__ __launch_bounds__(1024) void k_mlp_row(MlpArgs A, int staged)
 {
     extern __shared__ float stage[];               // all weights, when they fit
     __shared__ float act[2][kMaxWidth];
     const long long row = blockIdx.x;
     const int tid = threadIdx.x;
-    if (staged) mlp_stage_weights(A, stage, tid, kRowThreads);
+    if (staged) mlp_stage_weights(A, stage, tid, (int)blockDim.x);
     if (tid < A.dims[0]) act[0][tid] = A.feats[row * A.dims[0] + tid];
     __syncthreads();
     const int cur = staged ? mlp_row_forward<true>(A, act, tid, stage) : mlp_row_forward<false>(A, act, tid, nullptr);
@@ -366,7 +368,7 @@ extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp,
         const int rc_lds = ensure_dynamic_lds((const void *)k_mlp_row, lds, &granted);
         if (rc_lds != KVQ_OK) return rc_lds;
     }
-        hipLaunchKernelGGL(k_mlp_row, dim3((unsigned)n), dim3(kRowThreads), lds, st, A, staged);
+        hipLaunchKernelGGL(k_mlp_row, dim3((unsigned)n), dim3(staged && n <= 256 ? 1024 : kRowThreads), lds, st, A, staged);
     } else if (mfma_width(A.dims[1]) && (A.n_linear == 2 || mfma_width(A.dims[2])) && ((uintptr_t)feats & 15) == 0 &&
                !getenv("KVQ_CONTROLLER_NO_MFMA")) {
         const int t1 = A.dims[1] / 32, t2 = A.n_linear == 3 ? A.dims[2] / 32 : 0;
