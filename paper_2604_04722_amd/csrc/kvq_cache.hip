@@ -339,7 +339,7 @@ __device__ __forceinline__ uint32_t quantize_lane(uint32_t (&p)[32], float level
     const float s = __half2float(sh);
     const float inv = s != 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f;  // s == 0: every quotient reads 0, every code is 0
     // four elements at a time: one near-tie test (and one rarely taken branch) per group keeps the common path a
-    // straight run of independent chains.  d >= 0 always (mn is the minimum), so only the upper clamp is needed.
+    // straight run of independent chains.  d >= 0 always (mn is the minimum), so no code is negative.
     constexpr float kNearTie = 0.5f - 0x1p-12f;
     const uint32_t ilevels = (uint32_t)levels;
 #pragma unroll
@@ -358,35 +358,29 @@ __device__ __forceinline__ uint32_t quantize_lane(uint32_t (&p)[32], float level
 #pragma unroll
             for (int e = 0; e < 4; ++e) r[e] = rintf(d[e] / s);
         }
-        // r is a non-negative whole number (or an overflow that the conversion saturates): clamp as an integer
-        uint32_t c[4];
+        p[m] = (uint32_t)r[0] | ((uint32_t)r[1] << 16);
+        p[m + 1] = (uint32_t)r[2] | ((uint32_t)r[3] << 16);
+    }
+    // The clamp to `levels`: with a normal fp16 scale the largest quotient is at most levels / (1 - 2^-11), which
+    // rounds to levels, so no code exceeds it.  Only a subnormal scale (a vector whose range is below levels * 2^-14)
+    // can undershoot the exact quotient far enough; those rare lanes clamp their codes afterwards.
+    if (s < 0x1p-14f) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) c[e] = min((uint32_t)r[e], ilevels);
-        p[m] = c[0] | (c[1] << 16);
-        p[m + 1] = c[2] | (c[3] << 16);
+        for (int m = 0; m < 32; ++m) p[m] = min(p[m] & 0xffffu, ilevels) | (min(p[m] >> 16, ilevels) << 16);
     }
     return (uint32_t)__half_as_ushort(sh) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
 }
 
-// packs the lane's 32 pair registers into the words of class C and stores them as 16-byte chunks
+// Stores n16 16-byte chunks of the lane's registers p[0 .. 4 n16), chunk c at row c of the token's column.
 // `streaming`: the wavefront holds a long run of this class, its piece of each chunk row is mostly whole cache
 // lines, and the stores go past the cache (non-temporal); short pieces are stored normally so that the lines they
 // share with the neighbouring tiles' pieces are put together in the cache before they reach memory.
-template <int C> __device__ __forceinline__ void pack_store(const uint32_t (&p)[32], uint8_t *codes, int tok, bool streaming)
+template <int N16> __device__ __forceinline__ void store_chunks(const uint32_t (&p)[32], uint8_t *codes, int tok, bool streaming)
 {
-    constexpr int b = class_bits(C);
-    constexpr int PW = 16 / b;                                      // pair registers per 32-bit word
-    constexpr int NWORDS = 32 / PW;
 #pragma unroll
-    for (int c = 0; c < NWORDS / 4; ++c) {
+    for (int c = 0; c < N16; ++c) {
         u32x4 o;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            uint32_t word = 0;
-#pragma unroll
-            for (int j = 0; j < PW; ++j) word |= p[(4 * c + k) * PW + j] << (b * j);
-            o[k] = word;
-        }
+        o[0] = p[4 * c]; o[1] = p[4 * c + 1]; o[2] = p[4 * c + 2]; o[3] = p[4 * c + 3];
         u32x4 *dst = (u32x4 *)(codes + (size_t)c * (kBlockTokens * 16) + tok * 16);
         // the streaming form is spelled out: two stores that differ only in the non-temporal hint are merged into
         // one plain store by the optimizer
@@ -427,15 +421,27 @@ __device__ __forceinline__ void tile_transpose(const u32x4 (&x)[8], uint32_t (&p
     __builtin_amdgcn_wave_barrier();
 }
 
+// Quantizes (classes 0..2) and stores the lane's vector.  The packing is one tree for all widths: a word of class b
+// holds 16 / b pair registers, pair j at bit b * j, so joining neighbours with shifts b, 2b and 4b (per lane) turns
+// the 32 pair registers into the 16 words of the 8-bit class after the first level, the 8 words of the 4-bit class
+// after the second and the 4 words of the 2-bit class after the third -- 28 shift-or operations for whatever mix of
+// classes the wavefront holds, where a packing routine per class would run one after the other.  The FP16 lanes
+// store their registers as they are, before the tree overwrites them.
 __device__ __forceinline__ void quantize_pack_store(uint32_t (&p)[32], int cls, uint8_t *codes, uint32_t *meta, int tok, uint32_t streaming)
 {
-    if (cls != 3) *meta = quantize_lane(p, (float)((1 << (2 << cls)) - 1));
-    switch (cls) {
-    case 0: pack_store<0>(p, codes, tok, (streaming & 1u) != 0); break;
-    case 1: pack_store<1>(p, codes, tok, (streaming & 2u) != 0); break;
-    case 2: pack_store<2>(p, codes, tok, (streaming & 4u) != 0); break;
-    default: pack_store<3>(p, codes, tok, (streaming & 8u) != 0); break;
-    }
+    const int b = 2 << cls;
+    if (cls == 3) store_chunks<8>(p, codes, tok, (streaming & 8u) != 0);
+    else *meta = quantize_lane(p, (float)((1 << b) - 1));
+    const uint32_t s1 = (uint32_t)b & 31u, s2 = (uint32_t)(2 * b) & 31u, s3 = (uint32_t)(4 * b) & 31u;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) p[i] = p[2 * i] | (p[2 * i + 1] << s1);
+    if (cls == 2) store_chunks<4>(p, codes, tok, (streaming & 4u) != 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) p[i] = p[2 * i] | (p[2 * i + 1] << s2);
+    if (cls == 1) store_chunks<2>(p, codes, tok, (streaming & 2u) != 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p[i] = p[2 * i] | (p[2 * i + 1] << s3);
+    if (cls == 0) store_chunks<1>(p, codes, tok, (streaming & 1u) != 0);
 }
 
 // One wavefront per (layer, sequence, tile of 64 input tokens, kv-head); k and v must be 16-byte aligned.
