@@ -345,33 +345,37 @@ def main():
             pb = bb.view(B, ctx)
         Tc = min(2048, ctx)
         nch = ctx // Tc
-        pc = kvq.Cache(2, B, Hq, Hkv, Tc * nch)
+        # a prompt chunk goes through every layer back to back, each layer with K/V of its own: PL layers here, layer 0
+        # with the bookkeeping, the others timed as "what every further layer costs" (in steady state a call also
+        # carries the write-back of what the call before it left in the caches)
+        PL = 5
+        pc = kvq.Cache(PL, B, Hq, Hkv, Tc * nch)
         evs = []
         for c in range(nch):
-            K, V = wl.kv_chunk_fast(cfg, 0, 9000 + c, B, Tc, dev)
+            kv_l = [wl.kv_chunk_fast(cfg, l_ % L, 9000 + c, B, Tc, dev) for l_ in range(PL)]
             bt = pb[:, c * Tc:(c + 1) * Tc].contiguous()
-            a0, a1, a2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-            a0.record()
-            kvq.kvq_append(pc, 0, K, V, bt, None, B, Tc)          # bookkeeping + write
-            a1.record()
-            kvq.kvq_append(pc, 1, K, V, None, None, B, Tc)        # write only: what every further layer costs
-            a2.record()
-            evs.append((a0, a1, a2))
-            del K, V
+            marks = [torch.cuda.Event(enable_timing=True) for _ in range(PL + 1)]
+            marks[0].record()
+            for l_ in range(PL):
+                kvq.kvq_append(pc, l_, kv_l[l_][0], kv_l[l_][1], bt if l_ == 0 else None, None, B, Tc)
+                marks[l_ + 1].record()
+            evs.append(marks)
+            del kv_l
         torch.cuda.synchronize()
         pflags, _ = pc.status()
         if pflags:
             raise RuntimeError("prefill append raised device flags %d" % pflags)
         cnt = pc.counts()[:B, :4].to(torch.float64).sum(dim=0).tolist()
         app_bytes = sum(n * Hkv * (256 + wl.BYTES_PER_TOKEN_HEAD[w]) for n, w in zip(cnt, (2, 4, 8, 16))) / nch
-        us0 = float(np.median([a.elapsed_time(b_) * 1e3 for a, b_, _ in evs]))
-        us1 = float(np.median([b_.elapsed_time(c_) * 1e3 for _, b_, c_ in evs]))
+        us0 = float(np.median([m[0].elapsed_time(m[1]) * 1e3 for m in evs]))
+        us1 = float(np.median([m[i].elapsed_time(m[i + 1]) * 1e3 for m in evs for i in range(1, PL)]))
         prefill = {
             "controller": {"rows": n_rows, "us": ctrl_us, "rows_per_s": n_rows / (ctrl_us * 1e-6),
                            "TFLOPs": 2 * macs * n_rows / (ctrl_us * 1e-6) / 1e12, "frac_of_fp32_mfma_peak": 2 * macs * n_rows / (ctrl_us * 1e-6) / 1e12 / 157.3},
             "append": {"tokens_per_seq_per_call": Tc, "bytes_per_call": app_bytes, "us_layer0_with_bookkeeping": us0, "us_other_layers": us1,
                        "GBps_other_layers": app_bytes / (us1 * 1e-6) / 1e9, "frac_of_hbm_peak": app_bytes / (us1 * 1e-6) / 1e9 / HBM_PEAK_GBPS},
-            "note": "bulk controller (fp32 MFMA) on batch x context rows in one call; bulk append of one layer in 2048-token chunks, "
+            "note": "bulk controller (fp32 MFMA) on batch x context rows in one call; bulk append in 2048-token chunks, five layers "
+                    "back to back per chunk with K/V of their own (median over the layers after the first); "
                     "algorithmic bytes = 256 B read + the class's bytes written per (token, kv-head)"}
         # the controller's training step (Sec. 3.8, Algorithm 1) on mini-batches of labelled feature rows
         tr = {}
