@@ -129,7 +129,6 @@ struct AttnParams {
     CacheView cv;
     int32_t wgt[4];
     int32_t by_class;        // whole waves per class when a wave has at most this many units on average (0: never)
-    int32_t strided;
     const uint32_t *q;          // [n_seq][Hq][32] fp16 pairs
     const __half *k_new, *v_new; // fused append: the new token's K/V [n_seq][Hkv][64], or nullptr
     const int32_t *seq_ids;
@@ -688,7 +687,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     // one batch behind a single wait.
 #define KVQ_FETCH_NOW(x) asm volatile("" : : "s"(x))
     KVQ_FETCH_NOW(P.S); KVQ_FETCH_NOW(P.n_seq); KVQ_FETCH_NOW(P.longest_first); KVQ_FETCH_NOW(P.seq_ids); KVQ_FETCH_NOW(P.q);
-    KVQ_FETCH_NOW(P.k_new); KVQ_FETCH_NOW(P.layer); KVQ_FETCH_NOW(P.strided); KVQ_FETCH_NOW(P.by_class);
+    KVQ_FETCH_NOW(P.k_new); KVQ_FETCH_NOW(P.layer); KVQ_FETCH_NOW(P.by_class);
     KVQ_FETCH_NOW(P.wgt[0]); KVQ_FETCH_NOW(P.wgt[1]); KVQ_FETCH_NOW(P.wgt[2]); KVQ_FETCH_NOW(P.wgt[3]);
     KVQ_FETCH_NOW(cv.Hq); KVQ_FETCH_NOW(cv.Hkv); KVQ_FETCH_NOW(cv.max_seqs); KVQ_FETCH_NOW(cv.counts); KVQ_FETCH_NOW(cv.last_rec);
     KVQ_FETCH_NOW(cv.page_table); KVQ_FETCH_NOW(cv.max_pages_per_seq); KVQ_FETCH_NOW(cv.blocks_per_page);
@@ -818,10 +817,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         nu[c] = (cnt[c] + class_unit_blocks(c) * kBlockTokens - 1) / (class_unit_blocks(c) * kBlockTokens);
         wtot += (uint32_t)nu[c] * (uint32_t)wgt[c];
     }
-    const bool strided = P.strided != 0;
-    const int J = strided ? S : S * NW, j = strided ? s : s * NW + wave;
+    const int J = S * NW, j = s * NW + wave;
     int first[kClasses] = {0, 0, 0, 0}, last[kClasses] = {0, 0, 0, 0};
-    const int step = strided ? NW : 1;
+    constexpr int step = 1;                                  // a wave's units are consecutive
     // Short ranges (one workgroup per head and up to a dozen units per wave: small batches, short contexts): a wave
     // that crosses from one class into the next pays that class's pipeline start, a full memory latency, a second
     // time, and its workgroup waits for it.  There the classes get whole waves instead, in proportion to their weight
@@ -832,7 +830,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     const uint32_t nu_tot = (uint32_t)(nu[0] + nu[1] + nu[2] + nu[3]);
     const int nonempty = (nu[0] > 0) + (nu[1] > 0) + (nu[2] > 0) + (nu[3] > 0);
     bool ranged = false;
-    if (!strided && S == 1 && nonempty > 1 && J >= 2 * nonempty && nu_tot <= (uint32_t)P.by_class * (uint32_t)J) {
+    if (S == 1 && nonempty > 1 && J >= 2 * nonempty && nu_tot <= (uint32_t)P.by_class * (uint32_t)J) {
         uint32_t wc[kClasses];
         int nwc[kClasses], used = 0;
         const float per_weight = (float)J * __builtin_amdgcn_rcpf((float)wtot);
@@ -888,14 +886,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
             hi_w = (uint32_t)((unsigned long long)wtot * (uint32_t)(j + 1) / (uint32_t)J);
         }
         uint32_t wbase = 0;
-        int dealt = 0;
 #pragma unroll
         for (int c = 0; c < kClasses; ++c) {
             const int klo = min(lo_w <= wbase ? 0 : ceil_div_pos(lo_w - wbase, (uint32_t)wgt[c]), nu[c]);
             const int khi = min(hi_w <= wbase ? 0 : ceil_div_pos(hi_w - wbase, (uint32_t)wgt[c]), nu[c]);
-            first[c] = strided ? klo + ((wave + NW - (dealt % NW)) % NW) : klo;
+            first[c] = klo;
             last[c] = khi;
-            dealt += khi - klo;
             wbase += (uint32_t)nu[c] * (uint32_t)wgt[c];
         }
     }
@@ -1109,7 +1105,6 @@ static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t lay
     P.layer = layer;
     P.n_seq = n_seq;
     P.S = (int)S;
-    P.strided = env_int("KVQ_STRIDED", 0);
     P.by_class = env_int("KVQ_ATTN_BY_CLASS", 12);
     // Relative cost of one unit of each class (2 bit: 128 tokens, 5 KiB; 4 bit: 64 tokens, 4.5 KiB; 8 bit: 8.5 KiB;
     // FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost VALU time for unpacking,
