@@ -299,6 +299,29 @@ def test_bulk_append_degenerate_vectors_and_all_layers_in_one_call():
     assert cache.status()[0] == 0
 
 
+@pytest.mark.parametrize("stream_min", [1, 16, 65])
+@pytest.mark.parametrize("pattern", ["iid", "runs", "one_class"])
+def test_bulk_append_streaming_and_cached_stores_write_the_same_bytes(stream_min, pattern):
+    say("bulk append, store kind by run length: stream_min=%d pattern=%s" % (stream_min, pattern))
+    B, T, Hq, Hkv = 2, 333, 4, 4
+    rng = np.random.default_rng(800 + stream_min)
+    if pattern == "iid":
+        bits = rng.choice([2, 4, 8, 16], (B, T), p=[0.5, 0.25, 0.15, 0.1]).astype(np.uint8)
+    elif pattern == "runs":
+        bits = np.repeat(rng.choice([2, 4, 8, 16], (B, T // 20 + 1)), 20, axis=1)[:, :T].astype(np.uint8)
+    else:
+        bits = np.full((B, T), 8, np.uint8)
+    K, V = make_kv((B, T, Hkv, 64), 801), make_kv((B, T, Hkv, 64), 802, outlier=False)
+    cache = kvq.Cache(1, B, Hq, Hkv, T)
+    oc = OracleCache(B, Hkv)
+    with env(KVQ_APPEND_STREAM_MIN=stream_min):
+        kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+    for s in range(B):
+        oc.append(s, K[s], V[s], bits[s])
+        assert_export_equals(cache, 0, s, oc)
+    assert cache.status()[0] == 0
+
+
 def test_student_t_heavy_tailed_channels_and_long_mixed_context():
     say("heavy-tailed channels, ctx 3000, mix 40/30/20/10, 15q/5kv")
     B, T, Hq, Hkv = 2, 3000, 15, 5
