@@ -25,7 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-EVENT_EVERY = 5        # timed steps between two steps whose launches are bracketed by events
+EVENT_EVERY = 10       # timed steps between two steps whose launches are bracketed by events (fewer for short runs)
 
 
 def parse():
@@ -249,8 +249,9 @@ def main():
                 replay()
             else:
                 # event brackets on every EVENT_EVERY-th timed step only: an event record costs ~3 us of device time, and
-                # bracketing every launch of every step would inflate the step by 5 %
-                step(s, events and (s - warm_steps) % EVENT_EVERY == EVENT_EVERY // 2)
+                # bracketing every launch of every step would inflate the step by 5 %, every fifth by 1 %
+                every = max(1, min(EVENT_EVERY, timed_steps // 2))
+                step(s, events and (s - warm_steps) % every == every // 2)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         gc.enable()
