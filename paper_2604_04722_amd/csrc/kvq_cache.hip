@@ -421,16 +421,52 @@ __device__ __forceinline__ void tile_transpose(const u32x4 (&x)[8], uint32_t (&p
     __builtin_amdgcn_wave_barrier();
 }
 
+// The static per-channel variant of quantize_lane for a key vector: tab[c] = {step, 1 / step, minimum, -} of channel c
+// for the lane's class (LDS; a lane read of a register would not do here: this runs under divergent control flow, and
+// the lanes it would read from need not hold the value).  code = clamp(rint((x - min_c) / step_c), 0, levels) with the
+// IEEE quotient deciding near a tie, code 0 where the step is 0.  Same arithmetic as quantize_store_kch.  p[m] becomes
+// code(2m) | code(2m+1) << 16.
+__device__ __forceinline__ void quantize_lane_kch(uint32_t (&p)[32], float levels, const float4 *tab)
+{
+    constexpr float kNearTie = 0.5f - 0x1p-12f;
+#pragma unroll
+    for (int m = 0; m < 32; ++m) {
+        const f16x2 x = __builtin_bit_cast(f16x2, p[m]);
+        float r[2];
+        bool near = false;
+        float d[2], st[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const float4 t = tab[2 * m + e];
+            d[e] = (float)x[e] - t.z;
+            st[e] = t.x;
+            const float q = d[e] * t.y;
+            r[e] = rintf(q);
+            near |= fabsf(q - r[e]) > kNearTie;
+        }
+        if (near) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) r[e] = st[e] != 0.0f ? rintf(d[e] / st[e]) : 0.0f;
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) r[e] = __builtin_amdgcn_fmed3f(r[e], 0.0f, levels);
+        p[m] = (uint32_t)r[0] | ((uint32_t)r[1] << 16);
+    }
+}
+
 // Quantizes (classes 0..2) and stores the lane's vector.  The packing is one tree for all widths: a word of class b
 // holds 16 / b pair registers, pair j at bit b * j, so joining neighbours with shifts b, 2b and 4b (per lane) turns
 // the 32 pair registers into the 16 words of the 8-bit class after the first level, the 8 words of the 4-bit class
 // after the second and the 4 words of the 2-bit class after the third -- 28 shift-or operations for whatever mix of
 // classes the wavefront holds, where a packing routine per class would run one after the other.  The FP16 lanes
 // store their registers as they are, before the tree overwrites them.
-__device__ __forceinline__ void quantize_pack_store(uint32_t (&p)[32], int cls, uint8_t *codes, uint32_t *meta, int tok, uint32_t streaming)
+// kch_tab != nullptr: a key vector under the static per-channel variant (the token's own metadata entry is zero).
+__device__ __forceinline__ void quantize_pack_store(uint32_t (&p)[32], int cls, uint8_t *codes, uint32_t *meta, int tok, uint32_t streaming,
+                                                    const float4 *kch_tab = nullptr)
 {
     const int b = 2 << cls;
     if (cls == 3) store_chunks<8>(p, codes, tok, (streaming & 8u) != 0);
+    else if (kch_tab) { quantize_lane_kch(p, (float)((1 << b) - 1), kch_tab + cls * kD); *meta = 0u; }
     else *meta = quantize_lane(p, (float)((1 << b) - 1));
     const uint32_t s1 = (uint32_t)b & 31u, s2 = (uint32_t)(2 * b) & 31u, s3 = (uint32_t)(4 * b) & 31u;
 #pragma unroll
@@ -445,10 +481,14 @@ __device__ __forceinline__ void quantize_pack_store(uint32_t (&p)[32], int cls, 
 }
 
 // One wavefront per (layer, sequence, tile of 64 input tokens, kv-head); k and v must be 16-byte aligned.
+// KCH: the keys use the static per-channel variant; the wavefront then keeps its head's {step, 1 / step, minimum} per
+// channel and quantized class in LDS.
+template <bool KCH>
 __global__ __launch_bounds__(256) void k_append_bulk(CacheView cv, int layer, const __half *k, const __half *v,
                                                      const int32_t *seq_ids, int n_seq, int T, int tiles, long long total_waves, int P_stream_min)
 {
     __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][kBlockTokens * kStageRow];
+    __shared__ float4 kch_all[KCH ? 4 : 1][KCH ? 3 * kD : 1];
     const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
     uint8_t *stage = stage_all[threadIdx.x >> 6];
@@ -497,7 +537,21 @@ __global__ __launch_bounds__(256) void k_append_bulk(CacheView cv, int layer, co
 #pragma unroll
     for (int c = 0; c < kClasses; ++c)
         if (__popcll(__ballot(valid && cls == c)) >= P_stream_min) streaming |= 1u << c;
-    if (valid) quantize_pack_store(p, cls, base + meta_bytes, meta, tok, streaming);
+    if constexpr (KCH) {
+        float4 *tab = kch_all[threadIdx.x >> 6];
+        const size_t ti = ((size_t)L * cv.Hkv + h) * kD + lane;
+        const float minv = __half2float(cv.kch_min[ti]);
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const float st = __half2float(cv.kch_step[(size_t)c * cv.n_layers * cv.Hkv * kD + ti]);
+            tab[c * kD + lane] = make_float4(st, st != 0.0f ? __builtin_amdgcn_rcpf(st) : 0.0f, minv, 0.0f);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (valid) quantize_pack_store(p, cls, base + meta_bytes, meta, tok, streaming, tab);
+    } else {
+        if (valid) quantize_pack_store(p, cls, base + meta_bytes, meta, tok, streaming);
+    }
     tile_transpose(x, p, stage, lane);
     if (valid) quantize_pack_store(p, cls, base + meta_bytes + region, meta + 1, tok, streaming);
 }
@@ -819,15 +873,18 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
         const int rc = kvq_append_bookkeeping(cache, bits, seq_ids, n_seq, T, stream);
         if (rc != KVQ_OK) return rc;
     }
-    // many tokens per sequence: the lane-per-token kernel (needs 16-byte aligned vectors; per-token quantizer only);
-    // else a wave per vector
+    // many tokens per sequence: the lane-per-token kernel (needs 16-byte aligned vectors); else a wave per vector
     static const int bulk_min_T = getenv("KVQ_APPEND_BULK_MIN_T") ? atoi(getenv("KVQ_APPEND_BULK_MIN_T")) : 32;
-    if (T >= bulk_min_T && (((uintptr_t)k | (uintptr_t)v) & 15) == 0 && !cache->view.k_channel) {
+    if (T >= bulk_min_T && (((uintptr_t)k | (uintptr_t)v) & 15) == 0) {
         const int tiles = (T + kBlockTokens - 1) / kBlockTokens;
         const long long waves = nl * n_seq * (long long)tiles * d.n_kv_heads;
-        hipLaunchKernelGGL(k_append_bulk, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer,
-                           (const __half *)k, (const __half *)v, seq_ids, n_seq, T, tiles, waves,
-                           getenv("KVQ_APPEND_STREAM_MIN") ? atoi(getenv("KVQ_APPEND_STREAM_MIN")) : 16);
+        const int stream_min = getenv("KVQ_APPEND_STREAM_MIN") ? atoi(getenv("KVQ_APPEND_STREAM_MIN")) : 16;
+        if (cache->view.k_channel)
+            hipLaunchKernelGGL(k_append_bulk<true>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer,
+                               (const __half *)k, (const __half *)v, seq_ids, n_seq, T, tiles, waves, stream_min);
+        else
+            hipLaunchKernelGGL(k_append_bulk<false>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer,
+                               (const __half *)k, (const __half *)v, seq_ids, n_seq, T, tiles, waves, stream_min);
     } else {
         hipLaunchKernelGGL(k_append_write, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, st, cache->view, layer,
                            (const __half *)k, (const __half *)v, seq_ids, n_seq, T, total);

@@ -145,3 +145,37 @@ def test_switching_the_key_quantizer_needs_an_empty_cache_and_can_be_undone():
     codes, meta = oracle.append(K[0].view(np.uint16), V[0].view(np.uint16), bits[0])
     b, c, m = cache.export(0, 0, 5)
     assert np.array_equal(c.cpu().numpy(), codes) and np.array_equal(m.cpu().numpy().view(np.uint16), meta)
+
+
+@pytest.mark.parametrize("T", [8, 100, 333])      # the wave-per-vector kernel, then the lane-per-token bulk kernel (ragged tail)
+def test_per_channel_quotients_on_ties_out_of_range_values_and_all_layers_at_once(T):
+    print("per-channel keys: ties, saturation, layer = -1, T=%d" % T, flush=True)
+    B, L, Hq, Hkv = 2, 3, 4, 4
+    rng = np.random.default_rng(900 + T)
+    # ranges whose steps are exact in fp16 for every width: range = 255 * 15 * 2^-e  (divisible by 3, 15 and 255)
+    e = rng.integers(4, 9, (L, Hkv, 64))
+    rg = (3825.0 * 2.0 ** (-e.astype(np.float64))).astype(np.float16)
+    rg[..., 11] = 0.0
+    mn = (-rg.astype(np.float64) / 2).astype(np.float16)
+    bits = rng.choice([2, 4, 8, 16], (B, T)).astype(np.uint8)
+    K = np.zeros((L, B, T, Hkv, 64), np.float16)
+    for l in range(L):
+        for b in range(B):
+            for t in range(T):
+                w = int(bits[b, t])
+                levels = (1 << w) - 1 if w < 16 else 255
+                step = rg[l].astype(np.float64) / levels
+                j = rng.integers(-2, levels + 3, (Hkv, 64))                       # some codes fall outside 0..levels
+                frac = rng.choice([0.0, 0.5, 0.5 - 2.0 ** -9, 0.5 + 2.0 ** -9, 0.25], (Hkv, 64))
+                K[l, b, t] = (mn[l].astype(np.float64) + step * (j + frac)).astype(np.float16)
+    V = np.stack([make_kv((B, T, Hkv, 64), 910 + l, outlier=False) for l in range(L)])
+    cache = kvq.Cache(L, B, Hq, Hkv, T)
+    cache.set_k_channel_quant(torch.from_numpy(mn.view(np.int16)).view(torch.float16).to(dev()),
+                              torch.from_numpy(rg.view(np.int16)).view(torch.float16).to(dev()))
+    kvq.kvq_append(cache, -1, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+    for l in range(L):
+        oc = OracleKch(B, Hkv, mn[l], rg[l])
+        for b in range(B):
+            oc.append(b, K[l, b], V[l, b], bits[b])
+            check_export(cache, l, b, oc)
+    assert cache.status()[0] == 0
