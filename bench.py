@@ -270,6 +270,11 @@ def main():
             if args.trace_steps:
                 per = np.array(attn_us).reshape(-1, L).mean(axis=1)
                 log("[bench] attn us/layer by step: " + " ".join("%.0f" % x for x in per))
+            if not fused and L > 1:
+                # what lies between the end of one layer's attention and the start of the next one's: that layer's append
+                # (layers >= 1: no bookkeeping), plus one event record (~3 us)
+                gaps = [ev_pairs[i][1].elapsed_time(ev_pairs[i + 1][0]) * 1e3 for i in range(len(ev_pairs) - 1) if i % L != L - 1]
+                res["append_us_per_layer"] = float(np.median(gaps))
             res["attn_us_per_layer"] = float(np.mean(attn_us))
             res["attn_us_min"] = float(np.min(attn_us))
             res["attn_us_median"] = float(np.median(attn_us))
@@ -505,6 +510,7 @@ def main():
                    "mix_2_4_8_16": [round(x / tot, 4) for x in tok],
                    "expected_bits": round(sum(x * w for x, w in zip(tok, (2, 4, 8, 16))) / tot, 3)},
         "stages_us": {"features": mixed.get("features_us"), "controller": mixed.get("controller_us"),
+                      "append_per_layer": mixed.get("append_us_per_layer"),
                       "attn_per_layer": mixed.get("attn_us_per_layer"), "attn_per_layer_median": mixed.get("attn_us_median"),
                       "attn_per_layer_min": mixed.get("attn_us_min")},
         "stream_read_GBps": stream_gbps,
