@@ -8,23 +8,46 @@
 
 namespace kvq {
 
+// Cross-lane steps as data-parallel-primitive moves (no LDS permutes, which cost a round trip each): quad_perm
+// [1,0,3,2] and [2,3,0,1] pair a lane with lane ^ 1 and lane ^ 2; once the quads are uniform, row_half_mirror brings in
+// the other quad of an 8-lane group and row_mirror the other half of a 16-lane row.  All lanes must be active.
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row_of(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
 __device__ __forceinline__ float wave_min_all(float x)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fminf(x, __shfl_xor(x, o, 64));
-    return x;
+    x = fminf(x, dpp_f32<0xB1>(x));
+    x = fminf(x, dpp_f32<0x4E>(x));
+    x = fminf(x, dpp_f32<0x141>(x));
+    x = fminf(x, dpp_f32<0x140>(x));            // every lane of a row holds the row's minimum
+    return fminf(fminf(row_of(x, 0), row_of(x, 16)), fminf(row_of(x, 32), row_of(x, 48)));
 }
 __device__ __forceinline__ float wave_max_all(float x)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
-    return x;
+    x = fmaxf(x, dpp_f32<0xB1>(x));
+    x = fmaxf(x, dpp_f32<0x4E>(x));
+    x = fmaxf(x, dpp_f32<0x141>(x));
+    x = fmaxf(x, dpp_f32<0x140>(x));
+    return fmaxf(fmaxf(row_of(x, 0), row_of(x, 16)), fmaxf(row_of(x, 32), row_of(x, 48)));
 }
 
-// OR of `word` over the aligned group of `per` lanes (per = 2, 4, 8 or 16)
+// OR of `word` over the aligned group of `per` lanes (per = 2, 4, 8 or 16; wave-uniform)
 __device__ __forceinline__ uint32_t group_or(uint32_t word, int per)
 {
-    for (int o = 1; o < per; o <<= 1) word |= (uint32_t)__shfl_xor((int)word, o, 64);
+    word |= dpp_u32<0xB1>(word);
+    if (per >= 4) word |= dpp_u32<0x4E>(word);
+    if (per >= 8) word |= dpp_u32<0x141>(word);
+    if (per >= 16) word |= dpp_u32<0x140>(word);
     return word;
 }
 
