@@ -789,27 +789,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
             has_new = true;
         }
     }
-    float new_score = -INFINITY, new_v = 0.f;
-    if (has_new && s == 0 && wave == 0) {
+    // The wave that will quantize the new token asks for its K, V and query element now and uses them after its walk:
+    // their latency then costs that wave nothing.
+    const bool does_new = has_new && s == 0 && wave == 0;
+    __half new_kx = __ushort_as_half((unsigned short)0), new_vx = new_kx, new_qx = new_kx;
+    if (does_new) {
         const size_t src = ((size_t)si * cv.Hkv + kvh) * kD + lane;
-        const int page = new_page;
-        const int blk = (new_slot % cv.page_tokens) / kBlockTokens, tok = new_slot % kBlockTokens;
-        uint8_t *base = cv.pool[new_cls] + block_offset(cv, new_cls, P.layer, page, kvh, blk);
-        const size_t region = (size_t)class_chunks(new_cls) * kBlockTokens * 16;
-        const int mb = class_meta_bytes(new_cls);
-        __half *meta = (__half *)(base + tok * 8);
-        const bool writer = g == 0;
-        float khat;
-        if (KCH && new_bits != 16) {
-            const size_t ti = ((size_t)P.layer * cv.Hkv + kvh) * kD + lane;
-            khat = quantize_store_kch(P.k_new[src], new_bits, __half2float(cv.kch_min[ti]),
-                                      __half2float(cv.kch_step[(size_t)new_cls * cv.n_layers * cv.Hkv * kD + ti]), lane, tok, base + mb, meta, writer);
-        } else {
-            khat = quantize_store(P.k_new[src], new_bits, lane, tok, base + mb, meta, writer);
-        }
-        new_v = quantize_store(P.v_new[src], new_bits, lane, tok, base + mb + region, meta + 2, writer);
-        const float qf = __half2float(((const __half *)P.q)[((size_t)si * cv.Hq + qh) * kD + lane]);
-        new_score = wave_sum(qf * khat) * kScoreScale;
+        new_kx = P.k_new[src];
+        new_vx = P.v_new[src];
+        new_qx = ((const __half *)P.q)[((size_t)si * cv.Hq + qh) * kD + lane];
     }
 #pragma unroll
     for (int c = 0; c < kClasses; ++c) {
@@ -916,6 +904,28 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         if (first[2] < last[2]) { kch_prepare<2>(P, si, qh, kvh, lane, q2, q2l, qc); KVQ_WALK(2) run_8bit<true>(w, first[2], last[2], step, lane, q2, q2l, qc, st); }
     }
 #undef KVQ_WALK
+
+    // ---- the fused new token: quantized in registers, stored for later steps, one more partial result -----------
+    float new_score = -INFINITY, new_v = 0.f;
+    if (does_new) {
+        const int page = new_page;
+        const int blk = (new_slot % cv.page_tokens) / kBlockTokens, tok = new_slot % kBlockTokens;
+        uint8_t *base = cv.pool[new_cls] + block_offset(cv, new_cls, P.layer, page, kvh, blk);
+        const size_t region = (size_t)class_chunks(new_cls) * kBlockTokens * 16;
+        const int mb = class_meta_bytes(new_cls);
+        __half *meta = (__half *)(base + tok * 8);
+        const bool writer = g == 0;
+        float khat;
+        if (KCH && new_bits != 16) {
+            const size_t ti = ((size_t)P.layer * cv.Hkv + kvh) * kD + lane;
+            khat = quantize_store_kch(new_kx, new_bits, __half2float(cv.kch_min[ti]),
+                                      __half2float(cv.kch_step[(size_t)new_cls * cv.n_layers * cv.Hkv * kD + ti]), lane, tok, base + mb, meta, writer);
+        } else {
+            khat = quantize_store(new_kx, new_bits, lane, tok, base + mb, meta, writer);
+        }
+        new_v = quantize_store(new_vx, new_bits, lane, tok, base + mb + region, meta + 2, writer);
+        new_score = wave_sum(__half2float(new_qx) * khat) * kScoreScale;
+    }
 
     // ---- sum the 64 lanes: a transposing butterfly leaves channel c's total in lane c ----------------
     // Level `half` pairs lane l with lane l ^ half: the lanes with that bit clear end up with the sum of acc[i], the
