@@ -1002,7 +1002,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     }
 }
 
-// Merge the S partial results of each (sequence, query head): one wavefront each, lane = channel.
+// Merge the S partial results of each (sequence, query head): one wavefront each.  First lane s < S fetches the
+// (maximum, sum, sum of squares) triple of split s, so that the S triples travel together instead of one after the
+// other; then lane = channel, four splits' vectors in flight at a time.
 __global__ __launch_bounds__(256) void k_decode_combine(const float *ws, int n_seq, int Hq, int Hkv, int S,
                                                         float *out, float *lse, float *p2)
 {
@@ -1013,16 +1015,24 @@ __global__ __launch_bounds__(256) void k_decode_combine(const float *ws, int n_s
     const int si = oi / Hq, qh = oi % Hq;
     const int kvh = qh / G, g = qh % G;
     const size_t u0 = ((size_t)(si * Hkv + kvh) * S) * G + g;
-    float M = -INFINITY;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, ws[(u0 + (size_t)s * G) * kPartialFloats + 64]);
-    float o = 0.f, L = 0.f, L2 = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const float *w = ws + (u0 + (size_t)s * G) * kPartialFloats;
-        const float mw = w[64];
-        const float f = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-        o = fmaf(f, w[lane], o);
-        L = fmaf(f, w[65], L);
-        L2 = fmaf(f * f, w[66], L2);
+    const float *w0 = ws + u0 * kPartialFloats;
+    const size_t stride = (size_t)G * kPartialFloats;
+    float mw = -INFINITY, lw = 0.f, l2w = 0.f;                   // S <= kMaxSplits = 64: one lane per split
+    if (lane < S) {
+        const float *w = w0 + lane * stride;
+        mw = w[64]; lw = w[65]; l2w = w[66];
+    }
+    const float M = wave_max(mw);
+    const float f = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+    const float L = wave_sum(f * lw), L2 = wave_sum(f * f * l2w);
+    float o = 0.f;
+    for (int s0 = 0; s0 < S; s0 += 4) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = w0[(size_t)min(s0 + u, S - 1) * stride + lane];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (s0 + u < S) o = fmaf(lane_bcast(f, s0 + u), v[u], o);
     }
     const float inv = L > 0.f ? 1.0f / L : 0.f;
     out[(size_t)oi * kD + lane] = o * inv;
