@@ -68,6 +68,10 @@ static size_t plan_arena(const kvq_cache_desc &d, CacheView *v, uint8_t *base)
     off = align256(off + (size_t)d.max_seqs * d.max_context);
     cv.slot_log = (int32_t *)(base + off);
     off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs * d.max_context);
+    cv.pos_log = (int32_t *)(base + off);
+    off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs * 2 * d.max_context);
+    cv.last_start = (int32_t *)(base + off);
+    off = align256(off + sizeof(int32_t) * (size_t)d.max_seqs * 4);
     for (int c = 0; c < kClasses; ++c) {
         cv.free_stack[c] = (int32_t *)(base + off);
         off = align256(off + sizeof(int32_t) * (size_t)cv.n_pages[c]);
@@ -178,6 +182,7 @@ __global__ __launch_bounds__(64 * kAdvanceMaxWaves) void k_advance(CacheView cv,
         return;
     }
     int cc[kClasses] = {cnt[0], cnt[1], cnt[2], cnt[3]};
+    if (tid < kClasses) cv.last_start[(size_t)seq * 4 + tid] = cnt[tid];
     bool bad = false;
     int newest_b = 0, newest_cls = 0, newest_slot = -1;            // set by the thread that handles the call's last token
     for (int t0 = 0; t0 < T; t0 += 64 * n_waves) {
@@ -220,6 +225,7 @@ __global__ __launch_bounds__(64 * kAdvanceMaxWaves) void k_advance(CacheView cv,
             const size_t pos = (size_t)seq * cv.max_context + len + t;
             cv.bits_log[pos] = (uint8_t)b;
             cv.slot_log[pos] = slot;
+            cv.pos_log[pos_log_index(cv, seq, cls, slot)] = len + t;
             if (t == T - 1) { newest_b = b; newest_cls = cls; newest_slot = slot; }
         }
 #pragma unroll
@@ -460,13 +466,14 @@ __device__ __forceinline__ void quantize_lane_kch(uint32_t (&p)[32], float level
 // after the second and the 4 words of the 2-bit class after the third -- 28 shift-or operations for whatever mix of
 // classes the wavefront holds, where a packing routine per class would run one after the other.  The FP16 lanes
 // store their registers as they are, before the tree overwrites them.
-// kch_tab != nullptr: a key vector under the static per-channel variant (the token's own metadata entry is zero).
+// kch_tab != nullptr: a key vector under the static per-channel variant (the token's own metadata entry is zero);
+// the table is the one of this lane's class.
 __device__ __forceinline__ void quantize_pack_store(uint32_t (&p)[32], int cls, uint8_t *codes, uint32_t *meta, int tok, uint32_t streaming,
                                                     const float4 *kch_tab = nullptr)
 {
     const int b = 2 << cls;
     if (cls == 3) store_chunks<8>(p, codes, tok, (streaming & 8u) != 0);
-    else if (kch_tab) { quantize_lane_kch(p, (float)((1 << b) - 1), kch_tab + cls * kD); *meta = 0u; }
+    else if (kch_tab) { quantize_lane_kch(p, (float)((1 << b) - 1), kch_tab); *meta = 0u; }
     else *meta = quantize_lane(p, (float)((1 << b) - 1));
     const uint32_t s1 = (uint32_t)b & 31u, s2 = (uint32_t)(2 * b) & 31u, s3 = (uint32_t)(4 * b) & 31u;
 #pragma unroll
@@ -548,12 +555,103 @@ __global__ __launch_bounds__(256) void k_append_bulk(CacheView cv, int layer, co
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        if (valid) quantize_pack_store(p, cls, base + meta_bytes, meta, tok, streaming, tab);
+        if (valid) quantize_pack_store(p, cls, base + meta_bytes, meta, tok, streaming, tab + (cls < 3 ? cls : 0) * kD);
     } else {
         if (valid) quantize_pack_store(p, cls, base + meta_bytes, meta, tok, streaming);
     }
     tile_transpose(x, p, stage, lane);
     if (valid) quantize_pack_store(p, cls, base + meta_bytes + region, meta + 1, tok, streaming);
+}
+
+// The prefill writer proper: one wavefront per (layer, sequence, block of 64 slots of one class, kv-head), lane =
+// slot.  Working from the output side means that a wavefront writes one whole block of the cache (every chunk row a
+// contiguous kilobyte) and meets a single class, whatever the order of widths in the prompt; the token that sits in a
+// slot comes from the slot -> position log, and its two 128-byte input rows are whole cache lines wherever it lies.
+// Only the first and the last block of a class in a call are pieces.  A sequence's work items are the blocks its call
+// touches, widest class first; `items` (at most tiles + 7) bounds their number and the surplus wavefronts leave at once.
+constexpr int kGridY = 32768;
+template <bool KCH>
+__global__ __launch_bounds__(256, KCH ? 3 : 4) void k_append_blocks(CacheView cv, int layer, const __half *k, const __half *v,
+                                                       const int32_t *seq_ids, int n_seq, int n_pairs, int T, int items, int P_stream_min)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][kBlockTokens * kStageRow];
+    __shared__ float4 kch_all[KCH ? 4 : 1][KCH ? kD : 1];
+    // the wavefront's number inside the workgroup as a scalar: everything derived from it (work item, class, block
+    // address) then lives in scalar registers and the class branches are uniform
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int iw = blockIdx.x * 4 + wv;                            // grid: x = (work item, kv-head), y and z = (layer, sequence)
+    const int pair = blockIdx.z * kGridY + blockIdx.y;
+    if (iw >= items * cv.Hkv || pair >= n_pairs) return;
+    const int lane = threadIdx.x & 63;
+    uint8_t *stage = stage_all[wv];
+    const int h = iw % cv.Hkv, item = iw / cv.Hkv;
+    const int si = pair % n_seq, li = pair / n_seq;
+    const int L = layer < 0 ? li : layer;
+    const int seq = seq_ids ? seq_ids[si] : si;
+    if (seq < 0 || seq >= cv.max_seqs) return;
+    if (cv.last_T[seq] != T) return;                                // the bookkeeping call skipped this sequence
+    const int32_t *cnt = cv.counts + (size_t)seq * 5, *start = cv.last_start + (size_t)seq * 4;
+    const int len0 = cnt[4] - T;
+    // which block of which class this work item is
+    int cls = -1, s0 = 0, lo = 0, hi = 0, left = item;
+#pragma unroll
+    for (int c = kClasses - 1; c >= 0; --c) {
+        const int s = start[c], e = cnt[c];
+        const int nb = e > s ? ((e - 1) >> 6) - (s >> 6) + 1 : 0;
+        if (cls < 0 && left < nb) {
+            cls = c;
+            s0 = ((s >> 6) + left) << 6;
+            lo = s > s0 ? s - s0 : 0;
+            hi = e - s0 < kBlockTokens ? e - s0 : kBlockTokens;
+        }
+        left -= nb;
+    }
+    if (cls < 0) return;
+    const bool valid = lane >= lo && lane < hi;
+    int t = 0;
+    if (valid) t = cv.pos_log[pos_log_index(cv, seq, cls, s0 + lane)] - len0;
+    t = t < 0 ? 0 : t > T - 1 ? T - 1 : t;                          // in bounds whatever the log holds
+    const int t_first = __shfl(t, lo);
+    if (!valid) t = t_first;                                        // rows outside the piece repeat its first token
+    const size_t row_halves = (size_t)cv.Hkv * kD;
+    const size_t src = (((size_t)li * n_seq + si) * T * cv.Hkv + h) * kD;
+    int row_t[8];                                                   // load i takes rows 8 i .. 8 i + 7, eight lanes per row
+#pragma unroll
+    for (int i = 0; i < 8; ++i) row_t[i] = __shfl(t, i * 8 + (lane >> 3));
+    u32x4 x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = __builtin_nontemporal_load((const u32x4 *)(k + src + (size_t)row_t[i] * row_halves) + (lane & 7));
+
+    const int page = cv.page_table[((size_t)seq * kClasses + cls) * cv.max_pages_per_seq + s0 / cv.page_tokens];
+    uint8_t *base = cv.pool[cls] + block_offset(cv, cls, L, page, h, (s0 % cv.page_tokens) / kBlockTokens);
+    const bool streaming = hi - lo >= P_stream_min;
+    const __half *vsrc = v + src + (lane & 7) * 8;
+    float4 *tab = nullptr;
+    if constexpr (KCH) {
+        tab = kch_all[wv];
+        if (cls < 3) {
+            const size_t ti = ((size_t)L * cv.Hkv + h) * kD + lane;
+            const float minv = __half2float(cv.kch_min[ti]);
+            const float st = __half2float(cv.kch_step[(size_t)cls * cv.n_layers * cv.Hkv * kD + ti]);
+            tab[lane] = make_float4(st, st != 0.0f ? __builtin_amdgcn_rcpf(st) : 0.0f, minv, 0.0f);
+        }
+    }
+    // The class as the quantizer sees it sits in a vector register: the addresses above are scalar, but branches the
+    // compiler knows to be uniform make it schedule the four widths' code so that the V rows in flight no longer fit
+    // in four wavefronts' worth of registers.
+    int cls_v = cls;
+    asm volatile("" : "+v"(cls_v));
+    const int meta_bytes = cls == 3 ? 0 : kBlockTokens * 8;
+    const size_t region = (size_t)(1 << cls) * kBlockTokens * 16;
+    uint32_t *meta = (uint32_t *)(base + lane * 8);
+    const uint32_t stm = streaming ? 15u : 0u;
+    uint32_t p[32];
+    tile_transpose(x, p, stage, lane);                             // its barrier also publishes tab
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = __builtin_nontemporal_load((const u32x4 *)(vsrc + (size_t)row_t[i] * row_halves));
+    if (valid) quantize_pack_store(p, cls_v, base + meta_bytes, meta, lane, stm, tab);
+    tile_transpose(x, p, stage, lane);
+    if (valid) quantize_pack_store(p, cls_v, base + meta_bytes + region, meta + 1, lane, stm);
 }
 
 // Canonical dump of one (layer, sequence): one wavefront per (token, kv-head), lane = element.
@@ -879,7 +977,21 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
         const int tiles = (T + kBlockTokens - 1) / kBlockTokens;
         const long long waves = nl * n_seq * (long long)tiles * d.n_kv_heads;
         const int stream_min = getenv("KVQ_APPEND_STREAM_MIN") ? atoi(getenv("KVQ_APPEND_STREAM_MIN")) : 16;
-        if (cache->view.k_channel)
+        // long prompts go block by block of the cache; below about 512 tokens per sequence the tile kernel's shorter
+        // chain of dependent reads wins (measured at 32 sequences: 256 tokens 31 against 37 us, 512 tokens 53 against 48)
+        const int block_min_T = getenv("KVQ_APPEND_BLOCK_MIN_T") ? atoi(getenv("KVQ_APPEND_BLOCK_MIN_T")) : 512;
+        if (T >= block_min_T) {
+            const int items = tiles + 7;
+            const long long pairs = nl * n_seq, gx = ((long long)items * d.n_kv_heads + 3) / 4;
+            if (gx * pairs > (1LL << 24)) { set_error("append too large for one launch"); return KVQ_ERR_CAPACITY; }
+            const dim3 grid((unsigned)gx, (unsigned)(pairs < kGridY ? pairs : kGridY), (unsigned)((pairs + kGridY - 1) / kGridY));
+            if (cache->view.k_channel)
+                hipLaunchKernelGGL(k_append_blocks<true>, grid, dim3(256), 0, st, cache->view, layer,
+                                   (const __half *)k, (const __half *)v, seq_ids, n_seq, (int)pairs, T, items, stream_min);
+            else
+                hipLaunchKernelGGL(k_append_blocks<false>, grid, dim3(256), 0, st, cache->view, layer,
+                                   (const __half *)k, (const __half *)v, seq_ids, n_seq, (int)pairs, T, items, stream_min);
+        } else if (cache->view.k_channel)
             hipLaunchKernelGGL(k_append_bulk<true>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer,
                                (const __half *)k, (const __half *)v, seq_ids, n_seq, T, tiles, waves, stream_min);
         else

@@ -54,6 +54,11 @@ struct CacheView {
                                        // for the single-token writers instead of four dependent ones
     uint8_t *bits_log;                 // [max_seqs][max_context]
     int32_t *slot_log;                 // [max_seqs][max_context]
+    // slot -> position, written by the multi-token bookkeeping kernel (the prefill writer works a block of slots at a
+    // time and asks which token sits in each).  Two classes share an array of max_context entries: one fills it from
+    // the front, the other from the back; their counts never add up to more than the length.  See pos_log_index.
+    int32_t *pos_log;                  // [max_seqs][2][max_context]
+    int32_t *last_start;               // [max_seqs][4]: the class counts before the latest multi-token bookkeeping append
     // static per-channel key quantizer (a variant Q_b, off unless k_channel != 0): per (layer, kv-head, channel) the
     // minimum, and per quantized class the step fp16(range / levels)
     __half *kch_min;                   // [n_layers][Hkv][64]
@@ -113,6 +118,11 @@ __device__ __forceinline__ size_t block_offset(const CacheView &cv, int cls, int
 {
     return (size_t)layer * cv.layer_stride[cls] +
            (((size_t)page * cv.Hkv + kvh) * cv.blocks_per_page + blk_in_page) * (size_t)class_block_bytes(cls);
+}
+
+__device__ __forceinline__ size_t pos_log_index(const CacheView &cv, int seq, int cls, int slot)
+{
+    return ((size_t)seq * 2 + (cls >> 1)) * (size_t)cv.max_context + (size_t)((cls & 1) ? cv.max_context - 1 - slot : slot);
 }
 
 // Bucket bookkeeping of ONE new token of `seq` by a single thread: the same state changes as the bookkeeping

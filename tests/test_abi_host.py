@@ -62,7 +62,8 @@ def test_arena_size_follows_the_documented_block_sizes(lib):
     d = make_desc(pool_pages=pages)
     total = lib.kvq_cache_arena_bytes(ctypes.byref(d))
     pools = sum(24 * (p + 1) * 32 * 4 * bb for p, bb in zip(pages, (2560, 4608, 8704, 16384)))
-    assert pools <= total <= pools + 32 * 8192 * 5 + (1 << 20)
+    # bookkeeping per (sequence, position): the width (1 byte), its slot (4) and the slot -> position log (2 x 4)
+    assert pools <= total <= pools + 32 * 8192 * 13 + (1 << 20)
     # per-token cost of a full block matches the algorithmic bytes per (token, kv-head): 40 / 72 / 136 / 256
     assert [bb // 64 for bb in (2560, 4608, 8704, 16384)] == [40, 72, 136, 256]
 

@@ -147,9 +147,10 @@ def test_switching_the_key_quantizer_needs_an_empty_cache_and_can_be_undone():
     assert np.array_equal(c.cpu().numpy(), codes) and np.array_equal(m.cpu().numpy().view(np.uint16), meta)
 
 
-@pytest.mark.parametrize("T", [8, 100, 333])      # the wave-per-vector kernel, then the lane-per-token bulk kernel (ragged tail)
-def test_per_channel_quotients_on_ties_out_of_range_values_and_all_layers_at_once(T):
-    print("per-channel keys: ties, saturation, layer = -1, T=%d" % T, flush=True)
+# the wave-per-vector kernel (T = 8), then both prefill writers (64 input tokens, or 64 slots of a class, per wavefront)
+@pytest.mark.parametrize("T,block_min_T", [(8, 512), (100, 1 << 30), (333, 1 << 30), (100, 32), (333, 32)])
+def test_per_channel_quotients_on_ties_out_of_range_values_and_all_layers_at_once(T, block_min_T):
+    print("per-channel keys: ties, saturation, layer = -1, T=%d, block writer from T=%d" % (T, block_min_T), flush=True)
     B, L, Hq, Hkv = 2, 3, 4, 4
     rng = np.random.default_rng(900 + T)
     # ranges whose steps are exact in fp16 for every width: range = 255 * 15 * 2^-e  (divisible by 3, 15 and 255)
@@ -172,7 +173,8 @@ def test_per_channel_quotients_on_ties_out_of_range_values_and_all_layers_at_onc
     cache = kvq.Cache(L, B, Hq, Hkv, T)
     cache.set_k_channel_quant(torch.from_numpy(mn.view(np.int16)).view(torch.float16).to(dev()),
                               torch.from_numpy(rg.view(np.int16)).view(torch.float16).to(dev()))
-    kvq.kvq_append(cache, -1, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+    with env(KVQ_APPEND_BLOCK_MIN_T=block_min_T):
+        kvq.kvq_append(cache, -1, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
     for l in range(L):
         oc = OracleKch(B, Hkv, mn[l], rg[l])
         for b in range(B):
