@@ -326,15 +326,40 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 // Same arithmetic as quantize_store.  The quotient (x - min) / s is first formed with a reciprocal (error below
 // 7e-5 for quotients up to 1.5 * 255); it decides the rounding unless it lies within 2^-12 of a tie, where the
 // IEEE division is evaluated, so every code equals rint of the correctly rounded quotient.
+// Packed fp16 min / max as the instructions themselves: the generic builtins first canonicalize every operand (a
+// v_pk_max_f16 x, x each), which for a running minimum and maximum over 32 registers is as many instructions again.
+__device__ __forceinline__ uint32_t pk_min_f16(uint32_t a, uint32_t b)
+{
+    uint32_t r;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b)
+{
+    uint32_t r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// 1.0f that the optimizer cannot see through: fmaf((float)h, one, -m) is h - m rounded once, the same value as the
+// binary32 subtraction of the converted half, but it is a single v_fma_mix_f32 that takes the half where it sits
+// (either half of the pair register) instead of a conversion and a subtraction.
+__device__ __forceinline__ float opaque_one()
+{
+    float one = 1.0f;
+    asm volatile("" : "+s"(one));
+    return one;
+}
+
 __device__ __forceinline__ uint32_t quantize_lane(uint32_t (&p)[32], float levels)
 {
-    f16x2 mn2 = __builtin_bit_cast(f16x2, p[0]), mx2 = mn2;
+    uint32_t mnp = p[0], mxp = p[0];
 #pragma unroll
     for (int m = 1; m < 32; ++m) {
-        const f16x2 x = __builtin_bit_cast(f16x2, p[m]);
-        mn2 = __builtin_elementwise_min(mn2, x);
-        mx2 = __builtin_elementwise_max(mx2, x);
+        mnp = pk_min_f16(mnp, p[m]);
+        mxp = pk_max_f16(mxp, p[m]);
     }
+    const f16x2 mn2 = __builtin_bit_cast(f16x2, mnp), mx2 = __builtin_bit_cast(f16x2, mxp);
     float mn = fminf((float)mn2[0], (float)mn2[1]);
     float mx = fmaxf((float)mx2[0], (float)mx2[1]);
     if (mn == 0.0f) mn = 0.0f;
@@ -348,24 +373,28 @@ __device__ __forceinline__ uint32_t quantize_lane(uint32_t (&p)[32], float level
     // straight run of independent chains.  d >= 0 always (mn is the minimum), so no code is negative.
     constexpr float kNearTie = 0.5f - 0x1p-12f;
     const uint32_t ilevels = (uint32_t)levels;
+    const float one = opaque_one(), nmn = -mn;
 #pragma unroll
     for (int m = 0; m < 32; m += 2) {
         const f16x2 x0 = __builtin_bit_cast(f16x2, p[m]), x1 = __builtin_bit_cast(f16x2, p[m + 1]);
-        const float d[4] = {(float)x0[0] - mn, (float)x0[1] - mn, (float)x1[0] - mn, (float)x1[1] - mn};
-        float r[4];
+        const float d[4] = {fmaf((float)x0[0], one, nmn), fmaf((float)x0[1], one, nmn), fmaf((float)x1[0], one, nmn), fmaf((float)x1[1], one, nmn)};
+        // rounding and conversion in one addition: q + 1.5 * 2^23 has an ulp of 1, so the sum is rint(q) (ties to even,
+        // as v_rndne) and its low mantissa bits are the code itself (0 <= q < 2^16 here)
+        constexpr float kMagic = 12582912.0f;
+        float t[4];
         bool near = false;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float q = d[e] * inv;
-            r[e] = rintf(q);
-            near |= fabsf(q - r[e]) > kNearTie;
+            t[e] = fmaf(d[e], inv, kMagic);
+            near |= fabsf(fmaf(d[e], inv, kMagic - t[e])) > kNearTie;
         }
         if (near) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) r[e] = rintf(d[e] / s);
+            for (int e = 0; e < 4; ++e) t[e] = rintf(d[e] / s) + kMagic;
         }
-        p[m] = (uint32_t)r[0] | ((uint32_t)r[1] << 16);
-        p[m + 1] = (uint32_t)r[2] | ((uint32_t)r[3] << 16);
+        // (low half of t[1]) << 16 | low half of t[0]
+        p[m] = __builtin_amdgcn_perm(__float_as_uint(t[1]), __float_as_uint(t[0]), 0x05040100u);
+        p[m + 1] = __builtin_amdgcn_perm(__float_as_uint(t[3]), __float_as_uint(t[2]), 0x05040100u);
     }
     // The clamp to `levels`: with a normal fp16 scale the largest quotient is at most levels / (1 - 2^-11), which
     // rounds to levels, so no code exceeds it.  Only a subnormal scale (a vector whose range is below levels * 2^-14)
@@ -980,10 +1009,9 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
         // long prompts go block by block of the cache; below about 512 tokens per sequence the tile kernel's shorter
         // chain of dependent reads wins (measured at 32 sequences: 256 tokens 31 against 37 us, 512 tokens 53 against 48)
         const int block_min_T = getenv("KVQ_APPEND_BLOCK_MIN_T") ? atoi(getenv("KVQ_APPEND_BLOCK_MIN_T")) : 512;
-        if (T >= block_min_T) {
-            const int items = tiles + 7;
-            const long long pairs = nl * n_seq, gx = ((long long)items * d.n_kv_heads + 3) / 4;
-            if (gx * pairs > (1LL << 24)) { set_error("append too large for one launch"); return KVQ_ERR_CAPACITY; }
+        const int items = tiles + 7;                               // upper bound of the blocks one sequence's call touches
+        const long long pairs = nl * n_seq, gx = ((long long)items * d.n_kv_heads + 3) / 4;
+        if (T >= block_min_T && gx * pairs <= (1LL << 24)) {       // (a launch beyond that size goes tile by tile)
             const dim3 grid((unsigned)gx, (unsigned)(pairs < kGridY ? pairs : kGridY), (unsigned)((pairs + kGridY - 1) / kGridY));
             if (cache->view.k_channel)
                 hipLaunchKernelGGL(k_append_blocks<true>, grid, dim3(256), 0, st, cache->view, layer,
