@@ -313,11 +313,12 @@ __global__ void k_set_kch(CacheView cv, const __half *kmin, const __half *krange
 
 // ---- bulk (prefill) append: lane = token ------------------------------------------------------------------
 //
-// With many tokens per sequence in one call, a wavefront takes 64 consecutive input tokens of one (layer, sequence,
-// kv-head); each lane holds its token's whole 64-element vector in 32 registers (element pair (2m, 2m+1) per
-// register, exactly the pairing of the cache's words), finds min and max without any cross-lane traffic, quantizes
-// in place and writes its 16-byte chunks.  Lanes of one class hold consecutive slots, so their chunk stores are
-// contiguous.
+// With many tokens per sequence in one call a lane takes a whole token: it holds the token's 64-element vector in 32
+// registers (element pair (2m, 2m+1) per register, exactly the pairing of the cache's words), finds min and max
+// without any cross-lane traffic, quantizes in place and writes its 16-byte chunks.  Two kernels share these pieces:
+// k_append_bulk gives a wavefront 64 consecutive input tokens (lanes of one class hold consecutive slots, so their
+// chunk stores are contiguous pieces of that class's block), k_append_blocks gives it 64 consecutive slots of one
+// class (a whole block of the cache) and has it fetch the tokens that sit there.
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));

@@ -39,20 +39,22 @@ def test_random_case(case):
     splits = int(rng.choice([0, 0, 1, 2, 5]))
     lf = int(rng.integers(0, 2))
     fused = bool(rng.integers(0, 2))
-    print("case %d: B=%d Hq=%d Hkv=%d lens=%s waves=%d splits=%d longest_first=%d fused=%s" %
-          (case, B, Hq, Hkv, lens.tolist(), waves, splits, lf, fused), flush=True)
+    block_min_T = (32, 512, 1 << 30)[case % 3]                 # which prefill writer takes the chunks of 32 tokens and more
+    print("case %d: B=%d Hq=%d Hkv=%d lens=%s waves=%d splits=%d longest_first=%d fused=%s block writer from T=%d" %
+          (case, B, Hq, Hkv, lens.tolist(), waves, splits, lf, fused, block_min_T), flush=True)
     max_ctx = 8192 if long_ctx else 1024
     cache = kvq.Cache(1, B, Hq, Hkv, max_ctx)
     oc = OracleCache(B, Hkv)
     for s in range(B):
         n, t0 = int(lens[s]), 0
         bits = random_bits(rng, n)
-        while t0 < n:                                          # appended in random chunks: both append kernels take part
+        while t0 < n:                                          # appended in random chunks: all three append kernels take part
             tc = int(min(n - t0, rng.choice([1, 7, 31, 32, 64, 100, 300] + ([1500, 2500] if long_ctx else []))))
             K = make_kv((1, tc, Hkv, 64), 10000 * case + 100 * s + t0, outlier=bool(rng.integers(0, 2)))
             V = make_kv((1, tc, Hkv, 64), 10000 * case + 100 * s + t0 + 50, outlier=False)
             ids = torch.tensor([s], dtype=torch.int32, device=dev())
-            kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits[None, t0:t0 + tc].copy()).to(dev()), ids, 1, tc)
+            with env(KVQ_APPEND_BLOCK_MIN_T=block_min_T):
+                kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits[None, t0:t0 + tc].copy()).to(dev()), ids, 1, tc)
             oc.append(s, K[0], V[0], bits[t0:t0 + tc])
             t0 += tc
     torch.cuda.synchronize()
