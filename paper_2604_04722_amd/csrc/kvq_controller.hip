@@ -101,8 +101,8 @@ __host__ __device__ constexpr size_t mfma_lds_floats(int T1, int T2)
     return (size_t)T1 * 128 + T1 * 32 + (size_t)T2 * T1 * 1024 + T2 * 32 + TL * 128 + 4;
 }
 
-template <int T1, int T2>       // hidden widths 32*T1 and 32*T2; T2 == 0: one hidden layer
-__global__ __launch_bounds__(256, 2) void k_mlp_mfma(MlpArgs A, long long ntiles)
+template <int T1, int T2, int NW>   // hidden widths 32*T1 and 32*T2 (T2 == 0: one hidden layer); NW wavefronts per workgroup
+__global__ __launch_bounds__(64 * NW) void k_mlp_mfma(MlpArgs A, long long ntiles)
 {
     extern __shared__ float lds[];
     constexpr int TL = T2 ? T2 : T1;
@@ -112,33 +112,38 @@ __global__ __launch_bounds__(256, 2) void k_mlp_mfma(MlpArgs A, long long ntiles
     float *b2p = w2p + (size_t)T2 * T1 * 1024;      // [T2][16][2]
     float *wfp = b2p + T2 * 32;                     // [TL][16][2][4 outputs]
     float *bfp = wfp + TL * 128;                    // [4]
+    constexpr int NT = 64 * NW;
     const int tid = threadIdx.x;
     const float *W1 = A.W[0], *Wf = A.W[T2 ? 2 : 1];
-    for (int idx = tid; idx < T1 * 128; idx += 256) {
+    for (int idx = tid; idx < T1 * 128; idx += NT) {
         const int l = idx & 63, s = (idx >> 6) & 1, ot = idx >> 7;
         w1p[idx] = W1[(32 * ot + (l & 31)) * 4 + 2 * s + (l >> 5)];
     }
-    for (int idx = tid; idx < T1 * 32; idx += 256) {
+    for (int idx = tid; idx < T1 * 32; idx += NT) {
         const int hh = idx & 1, r = (idx >> 1) & 15, it = idx >> 5;
         b1p[idx] = A.b[0][32 * it + (r >> 2) * 8 + hh * 4 + (r & 3)];
     }
     if constexpr (T2 > 0) {
-        // W2 is read in memory order, four consecutive inputs per load and eight loads in flight per thread; each
-        // element then goes to the (tile, k-step, lane) slot that the MFMA loop reads it from
+        // W2: four consecutive inputs per load, eight loads in flight per thread, and consecutive threads take
+        // consecutive output units.  Each element goes to the (tile, k-step, lane) slot that the MFMA loop reads it
+        // from, and in that layout the lane is the output unit: with the units across the threads a wavefront's
+        // writes spread over all LDS banks (in memory order, where 32 consecutive threads share a unit, they all fall
+        // into one bank and the staging alone took a seventh of the kernel's time).
         const float *W2 = A.W[1];
-        constexpr int K = 32 * T1, N4 = T2 * 32 * K / 4;
-        for (int e0 = tid; e0 < N4; e0 += 8 * 256) {
+        constexpr int K = 32 * T1, NJ = 32 * T2, N4 = NJ * K / 4;
+        for (int e0 = tid; e0 < N4; e0 += 8 * NT) {
             f32x4 v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int e4 = e0 + u * 256;
-                v[u] = ((const f32x4 *)W2)[e4 < N4 ? e4 : e0];
+                const int e4 = e0 + u * NT;
+                const int ec = e4 < N4 ? e4 : e0;
+                v[u] = *(const f32x4 *)(W2 + (size_t)(ec % NJ) * K + (ec / NJ) * 4);
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int e4 = e0 + u * 256;
+                const int e4 = e0 + u * NT;
                 if (e4 < N4) {
-                    const int j = (e4 * 4) / K, i = (e4 * 4) % K;          // output unit, first of four inputs
+                    const int j = e4 % NJ, i = (e4 / NJ) * 4;               // output unit, first of four inputs
                     const int ot = j >> 5, it = i >> 5, rem = i & 31;
                     const int r0 = (rem >> 3) * 4, l = ((rem >> 2) & 1) * 32 + (j & 31);
                     float *d = w2p + ((ot * T1 + it) * 16 + r0) * 64 + l;
@@ -146,12 +151,12 @@ __global__ __launch_bounds__(256, 2) void k_mlp_mfma(MlpArgs A, long long ntiles
                 }
             }
         }
-        for (int idx = tid; idx < T2 * 32; idx += 256) {
+        for (int idx = tid; idx < T2 * 32; idx += NT) {
             const int hh = idx & 1, r = (idx >> 1) & 15, it = idx >> 5;
             b2p[idx] = A.b[1][32 * it + (r >> 2) * 8 + hh * 4 + (r & 3)];
         }
     }
-    for (int idx = tid; idx < TL * 128; idx += 256) {
+    for (int idx = tid; idx < TL * 128; idx += NT) {
         const int o = idx & 3, hh = (idx >> 2) & 1, r = (idx >> 3) & 15, it = idx >> 7;
         wfp[idx] = Wf[o * (32 * TL) + 32 * it + (r >> 2) * 8 + hh * 4 + (r & 3)];
     }
@@ -159,11 +164,23 @@ __global__ __launch_bounds__(256, 2) void k_mlp_mfma(MlpArgs A, long long ntiles
     __syncthreads();
 
     const int lane = tid & 63, hh = lane >> 5, j = lane & 31;
-    const long long stride = (long long)gridDim.x * 4;
-    for (long long tile = (long long)blockIdx.x * 4 + (tid >> 6); tile < ntiles; tile += stride) {
+    const long long stride = (long long)gridDim.x * NW;
+    // a tile's feature rows are asked for one tile ahead: the load's latency would otherwise stand at the head of every
+    // tile, in front of the first matrix instruction that needs it
+    const long long tile0 = (long long)blockIdx.x * NW + (tid >> 6);
+    f32x4 x_next = {0.f, 0.f, 0.f, 0.f};
+    if (tile0 < ntiles) {
+        const long long row0 = tile0 * 32 + j;
+        x_next = *(const f32x4 *)(A.feats + (row0 < A.n ? row0 : A.n - 1) * 4);
+    }
+    for (long long tile = tile0; tile < ntiles; tile += stride) {
         const long long row = tile * 32 + j;
         const bool live = row < A.n;
-        const f32x4 x = *(const f32x4 *)(A.feats + (live ? row : A.n - 1) * 4);
+        const f32x4 x = x_next;
+        if (tile + stride < ntiles) {
+            const long long rown = (tile + stride) * 32 + j;
+            x_next = *(const f32x4 *)(A.feats + (rown < A.n ? rown : A.n - 1) * 4);
+        }
         const float xb[2] = {hh ? x[1] : x[0], hh ? x[3] : x[2]};
         f32x16 h1[T1];
 #pragma unroll
@@ -177,13 +194,21 @@ __global__ __launch_bounds__(256, 2) void k_mlp_mfma(MlpArgs A, long long ntiles
             for (int r = 0; r < 16; ++r) h1[it][r] = fmaxf(h1[it][r], 0.f);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // Second hidden layer two output tiles at a time, each pair folded into the 4-output layer as soon as it is
-        // complete: 32 accumulator registers live instead of 16 * T2, which leaves room for two waves per SIMD (one
-        // wave's MFMAs cover the other's LDS reads and vector work).  The 4-output layer is a short vector dot product:
-        // each lane sums over the units it holds, the two halves of a token are added at the end.
+        // Second hidden layer two output tiles at a time: 32 accumulator registers live instead of 16 * T2, which leaves
+        // room for two waves per SIMD.  The 4-output layer is a short vector dot product (each lane sums over the units it
+        // holds, the two halves of a token are added at the end), and a finished pair is folded into it while the next
+        // pair's matrix instructions run: one slice of the fold per chunk of k-steps, in the order r = 0..15 of the
+        // pair's first tile, then of its second.  Only the last pair's fold stands alone.
         float o[4] = {0.f, 0.f, 0.f, 0.f};
         if constexpr (T2 > 0) {
             constexpr int GO = T2 >= 2 ? 2 : 1;
+            constexpr int NCH = T1 * 4;                         // chunks of four k-steps
+            constexpr int RPC = GO * 16 / NCH;                  // registers of the previous pair folded per chunk
+            f32x16 hp[GO];                                      // the pair before this one, waiting to be folded
+#pragma unroll
+            for (int g = 0; g < GO; ++g)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) hp[g][r] = 0.f;
 #pragma unroll
             for (int o0 = 0; o0 < T2; o0 += GO) {
                 f32x16 h2[GO];
@@ -191,9 +216,8 @@ __global__ __launch_bounds__(256, 2) void k_mlp_mfma(MlpArgs A, long long ntiles
                 for (int g = 0; g < GO; ++g)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) h2[g][r] = b2p[((o0 + g) * 16 + r) * 2 + hh];
-                // k-steps in chunks of four; the next chunk's A operands are read from LDS while this chunk's MFMAs run, and
-                // a scheduling fence per chunk keeps the compiler from hoisting every LDS read of the layer to the top
-                constexpr int NCH = T1 * 4;
+                // the next chunk's A operands are read from LDS while this chunk's MFMAs run, and a scheduling fence per
+                // chunk keeps the compiler from hoisting every LDS read of the layer to the top
                 float a_cur[4][GO], a_nxt[4][GO];
 #pragma unroll
                 for (int s_ = 0; s_ < 4; ++s_)
@@ -214,21 +238,36 @@ __global__ __launch_bounds__(256, 2) void k_mlp_mfma(MlpArgs A, long long ntiles
                         for (int g = 0; g < GO; ++g)
                             h2[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[s_][g], h1[st_ / 16][st_ % 16], h2[g], 0, 0, 0);
                     }
+                    if (o0 > 0) {
+#pragma unroll
+                        for (int q = c * RPC; q < (c + 1) * RPC; ++q) {
+                            const int g = q / 16, r = q % 16;
+                            const float h = fmaxf(hp[g][r], 0.f);
+                            const f32x4 w = *(const f32x4 *)(wfp + (((o0 - GO + g) * 16 + r) * 2 + hh) * 4);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) o[k] = fmaf(h, w[k], o[k]);
+                        }
+                    }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int s_ = 0; s_ < 4; ++s_)
 #pragma unroll
                         for (int g = 0; g < GO; ++g) a_cur[s_][g] = a_nxt[s_][g];
                 }
+                if (o0 + GO < T2) {
 #pragma unroll
-                for (int g = 0; g < GO; ++g)
+                    for (int g = 0; g < GO; ++g) hp[g] = h2[g];
+                } else {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float h = fmaxf(h2[g][r], 0.f);
-                        const f32x4 w = *(const f32x4 *)(wfp + (((o0 + g) * 16 + r) * 2 + hh) * 4);
+                    for (int g = 0; g < GO; ++g)
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) o[k] = fmaf(h, w[k], o[k]);
-                    }
+                        for (int r = 0; r < 16; ++r) {
+                            const float h = fmaxf(h2[g][r], 0.f);
+                            const f32x4 w = *(const f32x4 *)(wfp + (((o0 + g) * 16 + r) * 2 + hh) * 4);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) o[k] = fmaf(h, w[k], o[k]);
+                        }
+                }
             }
         } else {
 #pragma unroll
@@ -247,23 +286,15 @@ __global__ __launch_bounds__(256, 2) void k_mlp_mfma(MlpArgs A, long long ntiles
     }
 }
 
-static int env_per_cu()
+static int env_int_or(const char *name, int dflt, int lo, int hi)
 {
-    const char *e = getenv("KVQ_CONTROLLER_WG_PER_CU");
-    const int v = e ? atoi(e) : 2;
-    return v >= 1 && v <= 4 ? v : 2;
+    const char *e = getenv(name);
+    const int v = e ? atoi(e) : dflt;
+    return v >= lo && v <= hi ? v : dflt;
 }
 
-template <int T1, int T2> static int launch_mfma(const MlpArgs &A, hipStream_t st)
+static int device_cu_count(int *out)
 {
-    const size_t lds = mfma_lds_floats(T1, T2) * sizeof(float);
-    {
-        static size_t granted = 0;                 // one per instantiation
-        const int rc_lds = ensure_dynamic_lds((const void *)k_mlp_mfma<T1, T2>, lds, &granted);
-        if (rc_lds != KVQ_OK) return rc_lds;
-    }
-    const long long ntiles = (A.n + 31) / 32;
-    // persistent: one workgroup per compute unit stages the weights once and walks over the row tiles
     static int n_cu = 0;
     if (n_cu == 0) {
         int dev = 0;
@@ -271,12 +302,39 @@ template <int T1, int T2> static int launch_mfma(const MlpArgs &A, hipStream_t s
         KVQ_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (n_cu < 1) n_cu = 1;
     }
-    // two workgroups per compute unit (two waves per SIMD: one wave's MFMAs cover the other's LDS reads and vector work)
-    const int per_cu = env_per_cu();
-    long long blocks = (ntiles + 3) / 4;
-    if (blocks > (long long)per_cu * n_cu) blocks = (long long)per_cu * n_cu;
-    hipLaunchKernelGGL((k_mlp_mfma<T1, T2>), dim3((unsigned)blocks), dim3(256), lds, st, A, ntiles);
+    *out = n_cu;
     return KVQ_OK;
+}
+
+template <int T1, int T2, int NW> static int launch_mfma_nw(const MlpArgs &A, hipStream_t st, long long max_blocks)
+{
+    const size_t lds = mfma_lds_floats(T1, T2) * sizeof(float);
+    {
+        static size_t granted = 0;                 // one per instantiation
+        const int rc_lds = ensure_dynamic_lds((const void *)k_mlp_mfma<T1, T2, NW>, lds, &granted);
+        if (rc_lds != KVQ_OK) return rc_lds;
+    }
+    const long long ntiles = (A.n + 31) / 32;
+    long long blocks = (ntiles + NW - 1) / NW;
+    if (blocks > max_blocks) blocks = max_blocks;
+    hipLaunchKernelGGL((k_mlp_mfma<T1, T2, NW>), dim3((unsigned)blocks), dim3(64 * NW), lds, st, A, ntiles);
+    return KVQ_OK;
+}
+
+// Persistent launch: every workgroup stages the weights once and walks over the row tiles.  Two waves per SIMD either
+// way (one wave's matrix instructions cover the other's LDS reads and vector work): as one workgroup of eight waves
+// per compute unit when there are enough tiles to give every compute unit one (the weights are then staged once per
+// compute unit: 82.5 against 84.5 us for 262 144 rows of the 4-128-128-4 network), else as two of four.
+template <int T1, int T2> static int launch_mfma(const MlpArgs &A, hipStream_t st)
+{
+    int n_cu = 1;
+    const int rc = device_cu_count(&n_cu);
+    if (rc != KVQ_OK) return rc;
+    const long long ntiles = (A.n + 31) / 32;
+    const int nw = env_int_or("KVQ_CONTROLLER_WAVES", ntiles >= 8LL * n_cu ? 8 : 4, 4, 8);
+    const int per_cu = env_int_or("KVQ_CONTROLLER_WG_PER_CU", nw == 8 ? 1 : 2, 1, 4);
+    if (nw == 8) return launch_mfma_nw<T1, T2, 8>(A, st, (long long)per_cu * n_cu);
+    return launch_mfma_nw<T1, T2, 4>(A, st, (long long)per_cu * n_cu);
 }
 
 template <int T1> static int launch_mfma_t2(int t2, const MlpArgs &A, hipStream_t st)
