@@ -13,16 +13,34 @@ __device__ __forceinline__ uint4 ld_stream(const uint4 *p)
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+// Both kernels give every workgroup one contiguous region of the buffer and walk it eight 4-KiB rows at a time.  On
+// this part that is the faster order: with the usual grid-stride loop (all workgroups inside one moving window) the
+// same loads reach 6.0-6.4 TB/s on a 2 GiB read, with a region per workgroup 7.1-7.2 TB/s.
+constexpr int kProbeUnroll = 8;
+
+__device__ __forceinline__ void probe_region(size_t n16, size_t *begin, size_t *end)
+{
+    size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    per = (per + 255) & ~(size_t)255;                              // whole rows of 256 x 16 bytes
+    const size_t b = per * blockIdx.x;
+    *begin = b < n16 ? b : n16;
+    *end = b + per < n16 ? b + per : n16;
+}
+
 __global__ __launch_bounds__(256) void k_probe_read(const uint4 *src, size_t n16, uint32_t *sink)
 {
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i, end;
+    probe_region(n16, &i, &end);
+    i += threadIdx.x;
     uint32_t acc = 0;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = ld_stream(src + i), b = ld_stream(src + i + stride), c = ld_stream(src + i + 2 * stride), d = ld_stream(src + i + 3 * stride);
-        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    for (; i + (kProbeUnroll - 1) * 256 < end; i += kProbeUnroll * 256) {
+        uint4 v[kProbeUnroll];
+#pragma unroll
+        for (int u = 0; u < kProbeUnroll; ++u) v[u] = ld_stream(src + i + u * 256);
+#pragma unroll
+        for (int u = 0; u < kProbeUnroll; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
-    for (; i < n16; i += stride) {
+    for (; i < end; i += 256) {
         const uint4 a = ld_stream(src + i);
         acc ^= a.x ^ a.y ^ a.z ^ a.w;
     }
@@ -31,9 +49,17 @@ __global__ __launch_bounds__(256) void k_probe_read(const uint4 *src, size_t n16
 
 __global__ __launch_bounds__(256) void k_probe_copy(uint4 *dst, const uint4 *src, size_t n16)
 {
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (; i < n16; i += stride) dst[i] = ld_stream(src + i);
+    size_t i, end;
+    probe_region(n16, &i, &end);
+    i += threadIdx.x;
+    for (; i + (kProbeUnroll - 1) * 256 < end; i += kProbeUnroll * 256) {
+        u32x4 v[kProbeUnroll];
+#pragma unroll
+        for (int u = 0; u < kProbeUnroll; ++u) v[u] = __builtin_nontemporal_load((const u32x4 *)(src + i + u * 256));
+#pragma unroll
+        for (int u = 0; u < kProbeUnroll; ++u) __builtin_nontemporal_store(v[u], (u32x4 *)(dst + i + u * 256));
+    }
+    for (; i < end; i += 256) __builtin_nontemporal_store(__builtin_nontemporal_load((const u32x4 *)(src + i)), (u32x4 *)(dst + i));
 }
 
 }  // namespace kvq
@@ -46,7 +72,7 @@ extern "C" int kvq_probe_read(const void *src, size_t bytes, uint32_t *sink, voi
     if (bytes == 0) return KVQ_OK;
     const size_t n16 = bytes / 16;
     size_t blocks = (n16 + 256 * 8 - 1) / (256 * 8);
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(k_probe_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src, n16, sink);
     KVQ_HIP(hipGetLastError());
     return KVQ_OK;
@@ -60,8 +86,8 @@ extern "C" int kvq_probe_copy(void *dst, const void *src, size_t bytes, void *st
     }
     if (bytes == 0) return KVQ_OK;
     const size_t n16 = bytes / 16;
-    size_t blocks = (n16 + 256 * 4 - 1) / (256 * 4);
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    size_t blocks = (n16 + 256 * 8 - 1) / (256 * 8);
+    if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (uint4 *)dst, (const uint4 *)src, n16);
     KVQ_HIP(hipGetLastError());
     return KVQ_OK;

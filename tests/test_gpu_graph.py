@@ -83,3 +83,19 @@ def test_graph_replay_of_a_decode_step_equals_the_eager_step():
             for x, y in zip(eager["cache"].export(l, s, T0 + 6), graphed["cache"].export(l, s, T0 + 6)):
                 assert torch.equal(x, y)
     assert eager["cache"].counts()[:, 4].tolist() == [T0 + 6] * B
+
+
+@pytest.mark.parametrize("n16", [1, 255, 256, 257, 2048 * 8 + 3, 1000003])
+def test_measurement_probes_copy_every_byte_and_read_in_bounds(n16):
+    """The bandwidth probes behind bench.py's stream ceilings: the copy must reproduce its source at any size (whole
+    and ragged regions per workgroup), and neither kernel may touch anything past the end (guard words stay intact)."""
+    print("probe kernels, %d 16-byte words" % n16, flush=True)
+    g = torch.Generator(device="cpu").manual_seed(n16)
+    src = torch.randint(0, 2 ** 31 - 1, (n16 * 4 + 8,), dtype=torch.int32, generator=g).to(dev())
+    dst = torch.full((n16 * 4 + 8,), -7, dtype=torch.int32, device=dev())
+    kvq.kvq_probe_copy(dst[:n16 * 4], src[:n16 * 4])
+    sink = torch.zeros(1, dtype=torch.int32, device=dev())
+    kvq.kvq_probe_read(src[:n16 * 4], sink)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n16 * 4], src[:n16 * 4])
+    assert bool((dst[n16 * 4:] == -7).all())
