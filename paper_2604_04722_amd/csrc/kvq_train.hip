@@ -8,8 +8,9 @@
 // with thread = gradient element; deltas are propagated in place of the activations they belong to.  Each
 // (persistent) workgroup accumulates its rows' gradient into its own slice of the workspace, so no atomics are needed
 // and the result does not depend on scheduling.  k_train_adam: thread = parameter; sums the slices in order and
-// applies Adam.  The network is small (17 540 parameters for 4-128-128-4): at mini-batch sizes the step is bound by
-// launch and memory latency, not by arithmetic.
+// applies Adam.  The network is small (17 540 parameters for 4-128-128-4) and a mini-batch is a handful of tiles: the
+// step takes as long as one workgroup needs for one tile, which is set by its LDS reads (both operands of every FMA),
+// not by arithmetic.
 #include "kvq_internal.h"
 #include "kvq_mlp.h"
 
