@@ -9,8 +9,9 @@
 // (persistent) workgroup accumulates its rows' gradient into its own slice of the workspace, so no atomics are needed
 // and the result does not depend on scheduling.  k_train_adam: thread = parameter; sums the slices in order and
 // applies Adam.  The network is small (17 540 parameters for 4-128-128-4) and a mini-batch is a handful of tiles: the
-// step takes as long as one workgroup needs for one tile, which is set by its LDS reads (both operands of every FMA),
-// not by arithmetic.
+// step takes as long as one workgroup needs for one tile.  On the vector ALU that is set by LDS reads (both operands
+// of every FMA); with hidden widths of 32, 64 or 128 the middle layer's three products run on the matrix cores instead
+// (see k_train_grad).
 #include "kvq_internal.h"
 #include "kvq_mlp.h"
 
@@ -70,8 +71,30 @@ __device__ __forceinline__ TrainLds train_lds_layout(const TrainArgs &A)
     return L;
 }
 
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// unit of a 32 x 32 MFMA result that register r holds in the lanes of half hh (the row is lane % 32)
+__device__ __forceinline__ int mfma_unit(int r, int hh) { return 8 * (r >> 2) + 4 * hh + (r & 3); }
+
+// T1, T2 > 0: three linear layers with hidden widths 32 T1 and 32 T2; the middle layer (all but a few percent of the
+// arithmetic) then runs on the matrix cores.  A tile's 32 rows are the N of v_mfma_f32_32x32x2_f32, the activations
+// [unit][row] in LDS are its B operands as they lie, and the three products are
+//   forward   h2[j][row]  = b2[j] + sum_i W2[j][i] h1[i][row]       A = W2 rows,        K = 32 T1 units
+//   weights   dW2[j][i]  += sum_row D2[j][row] h1[i][row]           A = D2, B = h1,     K = 32 rows
+//   deltas    D1[i][row]  = sum_j W2[j][i] D2[j][row]  (h1 > 0)     A = W2 columns,     K = 32 T2 units
+// Each wavefront owns ceil(T1 T2 / 4) tiles of dW2 and keeps them in registers over all of the workgroup's row tiles.
+// T1 == 0: every layer on the vector ALU (any widths).
+template <int T1, int T2>
 __global__ __launch_bounds__(kTrainThreads) void k_train_grad(TrainArgs A)
 {
+    constexpr bool MM = T1 > 0;
+    constexpr int kGradTiles = MM ? (T1 * T2 + 3) / 4 : 1;
+    f32x16 gacc[kGradTiles];
+#pragma unroll
+    for (int q = 0; q < kGradTiles; ++q)
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr) gacc[q][rr] = 0.f;
+    const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63, hh = lane >> 5, jl = lane & 31;
     extern __shared__ float lds[];
     const TrainLds L = train_lds_layout(A);
     const int tid = threadIdx.x, r = tid & (kTrainRows - 1), ug = tid / kTrainRows;
@@ -107,6 +130,22 @@ __global__ __launch_bounds__(kTrainThreads) void k_train_grad(TrainArgs A)
             const int in = A.dims[l], outw = A.dims[l + 1];
             const bool hidden = l + 1 < A.n_linear;
             const int in_off = L.act[l] + r, out_off = (hidden ? L.act[l < 2 ? l + 1 : 2] : L.dO) + r;
+            if (MM && l == 1) {
+                for (int ot = wv; ot < T2; ot += 4) {
+                    f32x16 acc;
+#pragma unroll
+                    for (int rr = 0; rr < 16; ++rr) acc[rr] = lds[L.b[1] + 32 * ot + mfma_unit(rr, hh)];
+                    const int a_off = L.W[1] + (32 * ot + jl) * (in + 1) + hh, b_off = L.act[1] + hh * kTrainRS + jl;
+#pragma unroll 8
+                    for (int s2 = 0; s2 < 32 * T1; s2 += 2)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(lds[a_off + s2], lds[b_off + s2 * kTrainRS], acc, 0, 0, 0);
+#pragma unroll
+                    for (int rr = 0; rr < 16; ++rr)
+                        lds[L.act[2] + (32 * ot + mfma_unit(rr, hh)) * kTrainRS + jl] = fmaxf(acc[rr], 0.f);
+                }
+                __syncthreads();
+                continue;
+            }
             for (int j = ug; j < outw; j += kGroups) {
                 float a = lds[L.b[l] + j];
                 const int w_off = L.W[l] + j * (in + 1);
@@ -163,6 +202,43 @@ __global__ __launch_bounds__(kTrainThreads) void k_train_grad(TrainArgs A)
             const int in = A.dims[l], outw = A.dims[l + 1];
             const int d_off = l + 1 < A.n_linear ? L.act[l < 2 ? l + 1 : 2] : L.dO;      // delta of this layer's output
             const int in_off = L.act[l];
+            if (MM && l == 1) {
+#pragma unroll
+                for (int q = 0; q < kGradTiles; ++q) {
+                    const int idx = wv + 4 * q;
+                    if (idx < T1 * T2) {
+                        const int jt = idx / T1, it = idx % T1;
+                        const int a_off = d_off + (32 * jt + jl) * kTrainRS + hh, b_off = in_off + (32 * it + jl) * kTrainRS + hh;
+#pragma unroll 8
+                        for (int s2 = 0; s2 < kTrainRows; s2 += 2)
+                            gacc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(lds[a_off + s2], lds[b_off + s2], gacc[q], 0, 0, 0);
+                    }
+                }
+                for (int j = tid; j < outw; j += kTrainThreads) {
+                    float g = 0.f;
+#pragma unroll
+                    for (int rr = 0; rr < kTrainRows; ++rr) g += lds[d_off + j * kTrainRS + rr];
+                    float *dst = slice + A.offb[l] + j;
+                    *dst = first ? g : *dst + g;
+                }
+                __syncthreads();                               // every gradient of this layer has read act[l]
+                for (int it = wv; it < T1; it += 4) {
+                    f32x16 acc;
+#pragma unroll
+                    for (int rr = 0; rr < 16; ++rr) acc[rr] = 0.f;
+                    const int a_off = L.W[1] + hh * (in + 1) + 32 * it + jl, b_off = d_off + hh * kTrainRS + jl;
+#pragma unroll 8
+                    for (int s2 = 0; s2 < 32 * T2; s2 += 2)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(lds[a_off + s2 * (in + 1)], lds[b_off + s2 * kTrainRS], acc, 0, 0, 0);
+#pragma unroll
+                    for (int rr = 0; rr < 16; ++rr) {
+                        const int at = in_off + (32 * it + mfma_unit(rr, hh)) * kTrainRS + jl;
+                        lds[at] = lds[at] > 0.f ? acc[rr] : 0.f;
+                    }
+                }
+                __syncthreads();
+                continue;
+            }
             for (int e = tid; e < in * outw; e += kTrainThreads) {
                 const int j = e / in, i = e - j * in;
                 float g = 0.f;
@@ -208,6 +284,21 @@ __global__ __launch_bounds__(kTrainThreads) void k_train_grad(TrainArgs A)
     // a workgroup that had no tile still owns a slice: clear it
     if (first) {
         for (int e = tid; e < A.P; e += kTrainThreads) slice[e] = 0.f;
+    }
+    if constexpr (MM) {
+        // the middle layer's weight gradient, summed in registers over the workgroup's tiles
+        if (!first) {
+#pragma unroll
+            for (int q = 0; q < kGradTiles; ++q) {
+                const int idx = wv + 4 * q;
+                if (idx < T1 * T2) {
+                    const int jt = idx / T1, it = idx % T1;
+#pragma unroll
+                    for (int rr = 0; rr < 16; ++rr)
+                        slice[A.offW[1] + (32 * jt + mfma_unit(rr, hh)) * (32 * T1) + 32 * it + jl] = gacc[q][rr];
+                }
+            }
+        }
     }
     if (tid < kTrainRows) {
 #pragma unroll
@@ -298,6 +389,16 @@ static int fill_train_args(const kvq_mlp *mlp, const kvq_mlp *am, const kvq_mlp 
     return KVQ_OK;
 }
 
+template <int T1, int T2> static int launch_train_grad(const TrainArgs &A, size_t lds, hipStream_t st)
+{
+    static size_t granted = 0;                     // one per instantiation
+    const int rc_lds = ensure_dynamic_lds((const void *)k_train_grad<T1, T2>, lds, &granted);
+    if (rc_lds != KVQ_OK) return rc_lds;
+    hipLaunchKernelGGL((k_train_grad<T1, T2>), dim3((unsigned)A.groups), dim3(kTrainThreads), lds, st, A);
+    KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+}
+
 static int train_groups(int64_t n)
 {
     const int64_t tiles = (n + kTrainRows - 1) / kTrainRows;
@@ -358,14 +459,24 @@ extern "C" int kvq_controller_train_step(const float *feats, const uint8_t *labe
     A.inv_n = (float)(1.0 / (double)n);
     size_t lds = (size_t)(8 + A.dims[1] + (A.n_linear == 3 ? A.dims[2] : 0)) * kTrainRS * sizeof(float);
     for (int l = 0; l < A.n_linear; ++l) lds += (size_t)A.dims[l + 1] * (A.dims[l] + 2) * sizeof(float);    // weights (padded rows) + bias
-    {
-        static size_t granted = 0;
-        const int rc_lds = ensure_dynamic_lds((const void *)k_train_grad, lds, &granted);
-        if (rc_lds != KVQ_OK) return rc_lds;
-    }
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(k_train_grad, dim3((unsigned)A.groups), dim3(kTrainThreads), lds, st, A);
-    KVQ_HIP(hipGetLastError());
+    const auto mm_width = [](int w) { return w == 32 || w == 64 || w == 128; };
+    const bool mm = A.n_linear == 3 && mm_width(A.dims[1]) && mm_width(A.dims[2]) && !getenv("KVQ_TRAIN_NO_MFMA");
+    const int t1 = mm ? A.dims[1] / 32 : 0, t2 = mm ? A.dims[2] / 32 : 0;
+    int rc_launch = KVQ_OK;
+    switch (t1 * 8 + t2) {
+    case 1 * 8 + 1: rc_launch = launch_train_grad<1, 1>(A, lds, st); break;
+    case 1 * 8 + 2: rc_launch = launch_train_grad<1, 2>(A, lds, st); break;
+    case 1 * 8 + 4: rc_launch = launch_train_grad<1, 4>(A, lds, st); break;
+    case 2 * 8 + 1: rc_launch = launch_train_grad<2, 1>(A, lds, st); break;
+    case 2 * 8 + 2: rc_launch = launch_train_grad<2, 2>(A, lds, st); break;
+    case 2 * 8 + 4: rc_launch = launch_train_grad<2, 4>(A, lds, st); break;
+    case 4 * 8 + 1: rc_launch = launch_train_grad<4, 1>(A, lds, st); break;
+    case 4 * 8 + 2: rc_launch = launch_train_grad<4, 2>(A, lds, st); break;
+    case 4 * 8 + 4: rc_launch = launch_train_grad<4, 4>(A, lds, st); break;
+    default: rc_launch = launch_train_grad<0, 0>(A, lds, st); break;
+    }
+    if (rc_launch != KVQ_OK) return rc_launch;
     hipLaunchKernelGGL(k_train_adam, dim3((unsigned)((A.P + 255) / 256)), dim3(256), 0, st, A);
     KVQ_HIP(hipGetLastError());
     return KVQ_OK;

@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import dev
+from helpers import env, dev
 from oracle import train as T
 from paper_2604_04722_amd import binding as kvq
 
@@ -93,11 +93,20 @@ def check_step(dims, n, seed):
     assert off == g.P
 
 
+# hidden widths of 32, 64 or 128 on both sides put the middle layer on the matrix cores (every tile mapping: equal and
+# unequal widths, fewer tiles than wavefronts and more); other widths and two-layer networks stay on the vector ALU
 @pytest.mark.parametrize("dims,n", [((4, 32, 32, 4), 64), ((4, 128, 128, 4), 1000), ((4, 64, 4), 333), ((4, 128, 128, 4), 1),
-                                    ((4, 40, 24, 4), 4096), ((4, 128, 128, 4), 10000)])
+                                    ((4, 40, 24, 4), 4096), ((4, 128, 128, 4), 10000), ((4, 64, 128, 4), 777),
+                                    ((4, 128, 32, 4), 2050), ((4, 32, 64, 4), 31), ((4, 128, 64, 4), 9000)])
 def test_train_step_matches_the_oracle(dims, n):
     print("train step dims %s n=%d" % (dims, n), flush=True)
     check_step(dims, n, seed=sum(dims) + n)
+
+
+def test_train_step_on_the_vector_alu_when_the_matrix_core_path_is_switched_off():
+    print("train step 4-128-128-4, n=500, KVQ_TRAIN_NO_MFMA=1", flush=True)
+    with env(KVQ_TRAIN_NO_MFMA=1):
+        check_step((4, 128, 128, 4), 500, seed=99)
 
 
 def test_training_run_follows_the_oracle_and_learns():
