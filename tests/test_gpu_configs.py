@@ -140,6 +140,27 @@ def test_config4_full_shape_one_layer_sampled_sequences():
         c2.destroy()
 
 
+def test_config4_prefill_in_the_2048_token_calls_the_benchmark_times():
+    cfg = wl.CONFIGS[4]
+    say("config 4 prefill leg: B=%d, calls of 2048 tokens per sequence (the block-at-a-time writer at its benchmark shape)" % cfg.batch)
+    B, T, CH = cfg.batch, cfg.context, 2048
+    lens = np.full(B, T, np.int64)
+    bits = np.stack([controller_bits_both(cfg, wl.bulk_features(cfg, T, chunk=100 + s)) for s in range(B)])
+    pools = [int(sum(-(-int((bits[s] == w).sum()) // 256) + 1 for s in range(B))) for w in (2, 4, 8, 16)]
+    cache = kvq.Cache(1, B, cfg.n_q_heads, cfg.n_kv_heads, T, pool_pages=pools)
+    prefill(cfg, cache, 1, bits, lens, chunk=CH)
+    assert cache.status()[0] == 0
+    seqs = [7, 30]
+    codes, meta = oracle_cache_for(cfg, 0, seqs, bits, lens, chunk=CH)
+    q = wl.queries(cfg, 0, 0, B, dev())
+    check_sampled(cfg, cache, 0, seqs, bits, lens, codes, meta, q)
+    # every sequence, cheaply: class counts and the free pages they imply
+    counts = cache.counts().cpu().numpy() if hasattr(cache.counts(), "cpu") else np.asarray(cache.counts())
+    for s in range(B):
+        assert [int(x) for x in counts[s, :4]] == [int((bits[s] == w).sum()) for w in (2, 4, 8, 16)]
+    cache.destroy()
+
+
 def test_config5_ragged_long_context_run_clustered_widths_one_layer():
     cfg = wl.CONFIGS[5]
     B = 16                                                   # a quarter of the batch keeps the test at ~1 GB
