@@ -155,6 +155,15 @@ def test_controller_assignments_match_the_oracle(cfg_index, n):
         assert np.max(np.abs(mix - np.array(cfg.mix))) < 0.03       # the calibrated mix holds on a fresh draw
 
 
+def test_controller_bulk_call_at_the_benchmark_size():
+    say("controller cfg 4, 262 144 rows (batch x context: the prefill call that bench.py times)")
+    cfg = wl.CONFIGS[4]
+    Ws, bs = wl.calibrated_mlp(cfg)
+    got, want = check_controller(wl.bulk_features(cfg, cfg.batch * cfg.context, chunk=7), Ws, bs)
+    mix = np.array([(want == w).mean() for w in (2, 4, 8, 16)])
+    assert np.max(np.abs(mix - np.array(cfg.mix))) < 0.03
+
+
 def test_controller_ties_zero_weights_and_two_layer_network():
     say("controller ties / hand-built weights")
     feats = np.random.default_rng(4).standard_normal((10, 4)).astype(np.float32)
