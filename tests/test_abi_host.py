@@ -128,3 +128,12 @@ def test_product_package_never_imports_the_oracle():
         if f.endswith((".c", ".h")) or f == "__init__.py":
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2604_04722_amd" not in text and "libkvq.so" not in text, f
+
+
+def test_bench_refuses_more_than_one_gpu_before_touching_a_device():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
+    assert r.stdout.strip() == ""                       # no JSON line for a run that did not happen
