@@ -490,6 +490,39 @@ __device__ __forceinline__ void quantize_lane_kch(uint32_t (&p)[32], float level
     }
 }
 
+// The per-channel key quantizer applied to rows as they were loaded (eight lanes per 128-byte row, so a lane holds the
+// same eight channels 8 (lane % 8) .. + 7 of eight different rows): the lane needs the tables of its eight channels
+// only, in registers, and the LDS transposition then moves 16-bit codes instead of fp16 values.  Same arithmetic as
+// quantize_lane_kch; st / inv / mn: step, 1 / step (0 for a zero step) and minimum of the lane's channels.
+__device__ __forceinline__ uint32_t quantize_pair_kch(uint32_t word, float levels, float st0, float st1, float inv0, float inv1, float mn0, float mn1)
+{
+    constexpr float kNearTie = 0.5f - 0x1p-12f;
+    const f16x2 hv = __builtin_bit_cast(f16x2, word);
+    const float d0 = (float)hv[0] - mn0, d1 = (float)hv[1] - mn1;
+    const float q0 = d0 * inv0, q1 = d1 * inv1;
+    float r0 = rintf(q0), r1 = rintf(q1);
+    if (fabsf(q0 - r0) > kNearTie || fabsf(q1 - r1) > kNearTie) {
+        r0 = st0 != 0.0f ? rintf(d0 / st0) : 0.0f;
+        r1 = st1 != 0.0f ? rintf(d1 / st1) : 0.0f;
+    }
+    r0 = __builtin_amdgcn_fmed3f(r0, 0.0f, levels);
+    r1 = __builtin_amdgcn_fmed3f(r1, 0.0f, levels);
+    return (uint32_t)r0 | ((uint32_t)r1 << 16);
+}
+
+__device__ __forceinline__ void quantize_rows_kch(u32x4 (&x)[8], float levels, const float (&st)[8], const float (&inv)[8], const float (&mn)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        u32x4 v = x[i];
+        v.x = quantize_pair_kch(v.x, levels, st[0], st[1], inv[0], inv[1], mn[0], mn[1]);
+        v.y = quantize_pair_kch(v.y, levels, st[2], st[3], inv[2], inv[3], mn[2], mn[3]);
+        v.z = quantize_pair_kch(v.z, levels, st[4], st[5], inv[4], inv[5], mn[4], mn[5]);
+        v.w = quantize_pair_kch(v.w, levels, st[6], st[7], inv[6], inv[7], mn[6], mn[7]);
+        x[i] = v;
+    }
+}
+
 // Quantizes (classes 0..2) and stores the lane's vector.  The packing is one tree for all widths: a word of class b
 // holds 16 / b pair registers, pair j at bit b * j, so joining neighbours with shifts b, 2b and 4b (per lane) turns
 // the 32 pair registers into the 16 words of the 8-bit class after the first level, the 8 words of the 4-bit class
@@ -498,11 +531,14 @@ __device__ __forceinline__ void quantize_lane_kch(uint32_t (&p)[32], float level
 // store their registers as they are, before the tree overwrites them.
 // kch_tab != nullptr: a key vector under the static per-channel variant (the token's own metadata entry is zero);
 // the table is the one of this lane's class.
+// quantized == true: p already holds the codes (a key vector of the per-channel variant quantized row-wise before the
+// transposition); only the zero metadata entry, the packing and the stores are left.
 __device__ __forceinline__ void quantize_pack_store(uint32_t (&p)[32], int cls, uint8_t *codes, uint32_t *meta, int tok, uint32_t streaming,
-                                                    const float4 *kch_tab = nullptr)
+                                                    const float4 *kch_tab = nullptr, bool quantized = false)
 {
     const int b = 2 << cls;
     if (cls == 3) store_chunks<8>(p, codes, tok, (streaming & 8u) != 0);
+    else if (quantized) *meta = 0u;
     else if (kch_tab) { quantize_lane_kch(p, (float)((1 << b) - 1), kch_tab); *meta = 0u; }
     else *meta = quantize_lane(p, (float)((1 << b) - 1));
     const uint32_t s1 = (uint32_t)b & 31u, s2 = (uint32_t)(2 * b) & 31u, s3 = (uint32_t)(4 * b) & 31u;
@@ -605,7 +641,6 @@ __global__ __launch_bounds__(256, KCH ? 3 : 4) void k_append_blocks(CacheView cv
                                                        const int32_t *seq_ids, int n_seq, int n_pairs, int T, int items, int P_stream_min)
 {
     __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][kBlockTokens * kStageRow];
-    __shared__ float4 kch_all[KCH ? 4 : 1][KCH ? kD : 1];
     // the wavefront's number inside the workgroup as a scalar: everything derived from it (work item, class, block
     // address) then lives in scalar registers and the class branches are uniform
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -656,14 +691,25 @@ __global__ __launch_bounds__(256, KCH ? 3 : 4) void k_append_blocks(CacheView cv
     uint8_t *base = cv.pool[cls] + block_offset(cv, cls, L, page, h, (s0 % cv.page_tokens) / kBlockTokens);
     const bool streaming = hi - lo >= P_stream_min;
     const __half *vsrc = v + src + (lane & 7) * 8;
-    float4 *tab = nullptr;
+    // per-channel keys: the lane's eight channels' tables (the class is the wave's), asked for while the rows travel
+    float kst[8], kinv[8], kmn[8];
+    const bool kch_rows = KCH && cls < 3;
     if constexpr (KCH) {
-        tab = kch_all[wv];
         if (cls < 3) {
-            const size_t ti = ((size_t)L * cv.Hkv + h) * kD + lane;
-            const float minv = __half2float(cv.kch_min[ti]);
-            const float st = __half2float(cv.kch_step[(size_t)cls * cv.n_layers * cv.Hkv * kD + ti]);
-            tab[lane] = make_float4(st, st != 0.0f ? __builtin_amdgcn_rcpf(st) : 0.0f, minv, 0.0f);
+            const size_t ti = ((size_t)L * cv.Hkv + h) * kD + (lane & 7) * 8;
+            const u32x4 mn4 = *(const u32x4 *)(cv.kch_min + ti);
+            const u32x4 st4 = *(const u32x4 *)(cv.kch_step + (size_t)cls * cv.n_layers * cv.Hkv * kD + ti);
+            const uint32_t mw[4] = {mn4.x, mn4.y, mn4.z, mn4.w}, sw[4] = {st4.x, st4.y, st4.z, st4.w};
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd) {
+                const f16x2 a = __builtin_bit_cast(f16x2, mw[wd]), b2 = __builtin_bit_cast(f16x2, sw[wd]);
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    kmn[2 * wd + e] = (float)a[e];
+                    kst[2 * wd + e] = (float)b2[e];
+                    kinv[2 * wd + e] = kst[2 * wd + e] != 0.0f ? __builtin_amdgcn_rcpf(kst[2 * wd + e]) : 0.0f;
+                }
+            }
         }
     }
     // The class as the quantizer sees it sits in a vector register: the addresses above are scalar, but branches the
@@ -676,10 +722,13 @@ __global__ __launch_bounds__(256, KCH ? 3 : 4) void k_append_blocks(CacheView cv
     uint32_t *meta = (uint32_t *)(base + lane * 8);
     const uint32_t stm = streaming ? 15u : 0u;
     uint32_t p[32];
-    tile_transpose(x, p, stage, lane);                             // its barrier also publishes tab
+    if constexpr (KCH) {
+        if (kch_rows) quantize_rows_kch(x, (float)((1 << (2 << cls)) - 1), kst, kinv, kmn);
+    }
+    tile_transpose(x, p, stage, lane);
 #pragma unroll
     for (int i = 0; i < 8; ++i) x[i] = __builtin_nontemporal_load((const u32x4 *)(vsrc + (size_t)row_t[i] * row_halves));
-    if (valid) quantize_pack_store(p, cls_v, base + meta_bytes, meta, lane, stm, tab);
+    if (valid) quantize_pack_store(p, cls_v, base + meta_bytes, meta, lane, stm, nullptr, kch_rows);
     tile_transpose(x, p, stage, lane);
     if (valid) quantize_pack_store(p, cls_v, base + meta_bytes + region, meta + 1, lane, stm);
 }
