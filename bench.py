@@ -62,7 +62,8 @@ def main():
     import torch
 
     from paper_2604_04722_amd import binding as kvq
-    from paper_2604_04722_amd import workloads as wl
+    import benchprobe
+    import workloads as wl
 
     kvq.load_library()                      # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
@@ -313,17 +314,17 @@ def main():
     probe.zero_()
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
     for _ in range(2):
-        kvq.kvq_probe_read(probe, sink)
+        benchprobe.read(probe, sink)
     p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     p0.record()
     for _ in range(5):
-        kvq.kvq_probe_read(probe, sink)
+        benchprobe.read(probe, sink)
     p1.record()
     torch.cuda.synchronize()
     stream_gbps = 5 * probe.numel() / (p0.elapsed_time(p1) * 1e-3) / 1e9
     # one plain copy of known size (1 GiB read + 1 GiB written): the reference reading for the hardware byte counters
     half = probe.numel() // 2
-    kvq.kvq_probe_copy(probe[half:], probe[:half])
+    benchprobe.copy(probe[half:], probe[:half])
     torch.cuda.synchronize()
     del probe
 

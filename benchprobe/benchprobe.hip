@@ -1,8 +1,11 @@
-// Measurement helpers: a streaming read-reduce and a plain copy, used to find the HBM rate a trivial
-// kernel attains on the same device and to calibrate hardware byte counters against a known size.
-#include "kvq_internal.h"
+// Measurement helpers of the benchmark (a library of its own, libbenchprobe.so; no part of the method and not linked
+// into libkvq.so): a streaming read-reduce and a plain copy, used to find the HBM rate a trivial kernel attains on the
+// same device and to calibrate hardware byte counters against a transfer of known size.
+#include "benchprobe.h"
 
-namespace kvq {
+#include <hip/hip_runtime.h>
+
+namespace benchprobe {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -62,33 +65,28 @@ __global__ __launch_bounds__(256) void k_probe_copy(uint4 *dst, const uint4 *src
     for (; i < end; i += 256) __builtin_nontemporal_store(__builtin_nontemporal_load((const u32x4 *)(src + i)), (u32x4 *)(dst + i));
 }
 
-}  // namespace kvq
+}  // namespace benchprobe
 
-using namespace kvq;
+using namespace benchprobe;
 
-extern "C" int kvq_probe_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
+extern "C" int benchprobe_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
 {
-    if (!src || !sink || (bytes & 15) || ((uintptr_t)src & 15)) { set_error("bad probe arguments"); return KVQ_ERR_INVALID_ARG; }
-    if (bytes == 0) return KVQ_OK;
+    if (!src || !sink || (bytes & 15) || ((uintptr_t)src & 15)) return 1;
+    if (bytes == 0) return 0;
     const size_t n16 = bytes / 16;
     size_t blocks = (n16 + 256 * 8 - 1) / (256 * 8);
     if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(k_probe_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src, n16, sink);
-    KVQ_HIP(hipGetLastError());
-    return KVQ_OK;
+    return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
-extern "C" int kvq_probe_copy(void *dst, const void *src, size_t bytes, void *stream)
+extern "C" int benchprobe_copy(void *dst, const void *src, size_t bytes, void *stream)
 {
-    if (!src || !dst || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) {
-        set_error("bad probe arguments");
-        return KVQ_ERR_INVALID_ARG;
-    }
-    if (bytes == 0) return KVQ_OK;
+    if (!src || !dst || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return 1;
+    if (bytes == 0) return 0;
     const size_t n16 = bytes / 16;
     size_t blocks = (n16 + 256 * 8 - 1) / (256 * 8);
     if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (uint4 *)dst, (const uint4 *)src, n16);
-    KVQ_HIP(hipGetLastError());
-    return KVQ_OK;
+    return hipGetLastError() == hipSuccess ? 0 : 2;
 }

@@ -346,13 +346,19 @@ int kvq_controller_train_step(const float *feats, const uint8_t *label_bits, int
                               size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Measurement helpers (not part of the method): a streaming read-reduce and a plain copy of `bytes`
- * bytes (a multiple of 16), used to measure the attainable HBM rate next to the kernels above and to
- * calibrate hardware byte counters against a transfer of known size.
- *   src, dst  device, 16-byte aligned;  sink device uint32[1]
+ * Launch-shape overrides for tests and tuning runs (never needed in normal use; no part of the method).
+ * The library keeps one process-wide table of small integers; the hot-path calls read that table and
+ * never the environment.  The table starts from its defaults, overridden by the KVQ_* environment
+ * variables as they stand when it is first needed; kvq_tuning_set changes an entry afterwards.
+ *   name   host string: attn_splits (0 = automatic, 1..64), attn_waves (0, 1, 2, 3, 4, 8),
+ *          attn_longest_first (-1 = automatic, 0, 1), attn_by_class, append_bulk_min_T,
+ *          append_stream_min, append_block_min_T, controller_no_mfma, controller_waves,
+ *          controller_wg_per_cu, train_no_mfma
+ * KVQ_ERR_INVALID_ARG for an unknown name or a value outside the entry's range (nothing changes).
+ * Not synchronised with calls running on other threads.
  * ------------------------------------------------------------------------------------------- */
-int kvq_probe_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
-int kvq_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+int kvq_tuning_set(const char *name, int32_t value);
+int kvq_tuning_get(const char *name, int32_t *value);
 
 #ifdef __cplusplus
 }

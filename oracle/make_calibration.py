@@ -1,4 +1,4 @@
-"""Writes paper_2604_04722_amd/controller_calibration.json: the output-layer bias that makes the seeded Xavier
+"""Writes workloads/controller_calibration.json: the output-layer bias that makes the seeded Xavier
 controller of each config reproduce that config's precision mix on the seeded bulk feature draw.
 
 Also writes, per config, the thresholds of the stand-in rule-based policy that give the same mix.
@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 
 import oracle                                          # noqa: E402
-from paper_2604_04722_amd import workloads as wl       # noqa: E402
+import workloads as wl       # noqa: E402
 
 N_SAMPLE = 200_000
 

@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export", "kvq_cache_import", "kvq_cache_set_k_channel_quant",
     "kvq_features_workspace", "kvq_features", "kvq_features_typed", "kvq_controller", "kvq_features_controller", "kvq_features_controller_typed", "kvq_rule_policy", "kvq_controller_param_count", "kvq_controller_train_workspace",
     "kvq_controller_train_step", "kvq_append", "kvq_decode_attn_workspace",
-    "kvq_decode_attn", "kvq_append_decode_attn", "kvq_probe_read", "kvq_probe_copy",
+    "kvq_decode_attn", "kvq_append_decode_attn", "kvq_tuning_set", "kvq_tuning_get",
 )
 
 
@@ -114,8 +114,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_decode_attn_workspace.argtypes = [vp, i32]
     lib.kvq_decode_attn.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.kvq_append_decode_attn.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
-    lib.kvq_probe_read.argtypes = [vp, sz, vp, vp]
-    lib.kvq_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.kvq_tuning_set.argtypes = [ctypes.c_char_p, i32]
+    lib.kvq_tuning_get.argtypes = [ctypes.c_char_p, ctypes.POINTER(i32)]
     _lib = lib
     return lib
 
@@ -422,9 +422,28 @@ def kvq_append_decode_attn(cache: Cache, layer: int, k: torch.Tensor, v: torch.T
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
 
 
-def kvq_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
-    _check(load_library().kvq_probe_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream(stream)))
+def kvq_tuning_set(name: str, value: int) -> None:
+    _check(load_library().kvq_tuning_set(name.encode(), int(value)))
 
 
-def kvq_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
-    _check(load_library().kvq_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), _stream(stream)))
+def kvq_tuning_get(name: str) -> int:
+    v = ctypes.c_int32(0)
+    _check(load_library().kvq_tuning_get(name.encode(), ctypes.byref(v)))
+    return int(v.value)
+
+
+class tuning:
+    """Context manager: set entries of the library's launch-shape table, restore them on exit (tests and sweeps)."""
+
+    def __init__(self, **kw):
+        self.kw = kw
+
+    def __enter__(self):
+        self.old = {k: kvq_tuning_get(k) for k in self.kw}
+        for k, v in self.kw.items():
+            kvq_tuning_set(k, v)
+        return self
+
+    def __exit__(self, *a):
+        for k, v in self.old.items():
+            kvq_tuning_set(k, v)

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libkvq.so")
-SOURCES = ["kvq_cache.hip", "kvq_attn.hip", "kvq_features.hip", "kvq_controller.hip", "kvq_train.hip", "kvq_probe.hip"]
+SOURCES = ["kvq_cache.hip", "kvq_attn.hip", "kvq_features.hip", "kvq_controller.hip", "kvq_train.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1042,13 +1042,6 @@ __global__ __launch_bounds__(256) void k_decode_combine(const float *ws, int n_s
     }
 }
 
-static int env_int(const char *name, int dflt)
-{
-    const char *e = getenv(name);
-    if (!e || !*e) return dflt;
-    return atoi(e);
-}
-
 }  // namespace kvq
 
 using namespace kvq;
@@ -1087,8 +1080,8 @@ static int plan_attn(const kvq_cache *cache, int32_t n_seq, int extra_tokens, co
     const int nw_auto = wph >= 8 ? 8 : wph >= 4 ? 4 : wph >= 3 ? 3 : 2;
     long long S = wph >= 16 ? wph / 8 : 1;
     if (S > kMaxSplits) S = kMaxSplits;
-    const int forced = env_int("KVQ_ATTN_SPLITS", 0);
-    if (forced >= 1 && forced <= kMaxSplits) S = forced;
+    const Tuning &tn = tuning();
+    if (tn.attn_splits >= 1 && tn.attn_splits <= kMaxSplits) S = tn.attn_splits;
     if (heads * S > 0x3fffffffLL) { set_error("too many work items"); return KVQ_ERR_CAPACITY; }
     if (S > 1) {
         const size_t need = (size_t)heads * S * kPartialFloats * sizeof(float);
@@ -1097,7 +1090,7 @@ static int plan_attn(const kvq_cache *cache, int32_t n_seq, int extra_tokens, co
             return KVQ_ERR_INVALID_ARG;
         }
     }
-    int nw = env_int("KVQ_ATTN_WAVES", 0);                      // 1, 2, 3, 4 or 8; anything else: the rule above
+    int nw = tn.attn_waves;                                     // 1, 2, 3, 4 or 8; anything else: the rule above
     if (nw != 1 && nw != 2 && nw != 3 && nw != 4 && nw != 8) nw = nw_auto;
     plan->S = S;
     plan->nw = nw;
@@ -1125,16 +1118,16 @@ static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t lay
     P.layer = layer;
     P.n_seq = n_seq;
     P.S = (int)S;
-    P.by_class = env_int("KVQ_ATTN_BY_CLASS", 12);
+    const Tuning &tn = tuning();
+    P.by_class = tn.attn_by_class;
     // Relative cost of one unit of each class (2 bit: 128 tokens, 5 KiB; 4 bit: 64 tokens, 4.5 KiB; 8 bit: 8.5 KiB;
     // FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost VALU time for unpacking,
     // and the ratios below are the ones that equalise the finishing times of a workgroup's waves (measured).
-    P.wgt[0] = env_int("KVQ_W0", 14); P.wgt[1] = env_int("KVQ_W1", 11); P.wgt[2] = env_int("KVQ_W2", 17); P.wgt[3] = env_int("KVQ_W3", 32);
-    for (int c = 0; c < 4; ++c) P.wgt[c] = P.wgt[c] < 1 ? 1 : P.wgt[c] > 255 ? 255 : P.wgt[c];
+    P.wgt[0] = 14; P.wgt[1] = 11; P.wgt[2] = 17; P.wgt[3] = 32;
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
-    P.longest_first = env_int("KVQ_ATTN_LONGEST_FIRST", (n_seq <= 64 && n_seq % 8 == 0 && heads * S * nw > 2048) ? 1 : 0);
+    P.longest_first = tn.attn_longest_first >= 0 ? tn.attn_longest_first : (n_seq <= 64 && n_seq % 8 == 0 && heads * S * nw > 2048) ? 1 : 0;
     if (n_seq > 64 || n_seq % 8 != 0) P.longest_first = 0;
     if (S > 1) P.longest_first = 0;                               // the merging kernel looks partial results up by output row
     if (!cache->view.k_channel) {

@@ -826,7 +826,68 @@ using namespace kvq;
 // C ABI
 // ---------------------------------------------------------------------------------------------
 
-extern "C" const char *kvq_version(void) { return "kvq 0.1 (gfx950)"; }
+namespace kvq {
+
+struct TuningKey { const char *name; const char *env; int Tuning::*field; int dflt, lo, hi; };
+
+static const TuningKey kTuningKeys[] = {
+    {"attn_splits", "KVQ_ATTN_SPLITS", &Tuning::attn_splits, 0, 0, 64},
+    {"attn_waves", "KVQ_ATTN_WAVES", &Tuning::attn_waves, 0, 0, 8},
+    {"attn_longest_first", "KVQ_ATTN_LONGEST_FIRST", &Tuning::attn_longest_first, -1, -1, 1},
+    {"attn_by_class", "KVQ_ATTN_BY_CLASS", &Tuning::attn_by_class, 12, 0, 1 << 20},
+    {"append_bulk_min_T", "KVQ_APPEND_BULK_MIN_T", &Tuning::append_bulk_min_T, 32, 1, 1 << 30},
+    {"append_stream_min", "KVQ_APPEND_STREAM_MIN", &Tuning::append_stream_min, 16, 0, 65},
+    {"append_block_min_T", "KVQ_APPEND_BLOCK_MIN_T", &Tuning::append_block_min_T, 512, 1, 1 << 30},
+    {"controller_no_mfma", "KVQ_CONTROLLER_NO_MFMA", &Tuning::controller_no_mfma, 0, 0, 1},
+    {"controller_waves", "KVQ_CONTROLLER_WAVES", &Tuning::controller_waves, 0, 0, 8},
+    {"controller_wg_per_cu", "KVQ_CONTROLLER_WG_PER_CU", &Tuning::controller_wg_per_cu, 0, 0, 4},
+    {"train_no_mfma", "KVQ_TRAIN_NO_MFMA", &Tuning::train_no_mfma, 0, 0, 1},
+};
+
+// The table's defaults, overridden by the KVQ_* environment variables as they stand when the table is first needed.
+Tuning &tuning()
+{
+    static Tuning t = [] {
+        Tuning v;
+        for (const TuningKey &k : kTuningKeys) {
+            int x = k.dflt;
+            const char *e = getenv(k.env);
+            if (e && *e) {
+                const int y = atoi(e);
+                if (y >= k.lo && y <= k.hi) x = y;
+            }
+            v.*(k.field) = x;
+        }
+        return v;
+    }();
+    return t;
+}
+
+}  // namespace kvq
+
+extern "C" int kvq_tuning_set(const char *name, int32_t value)
+{
+    if (!name) { set_error("name is NULL"); return KVQ_ERR_INVALID_ARG; }
+    for (const TuningKey &k : kTuningKeys)
+        if (strcmp(name, k.name) == 0) {
+            if (value < k.lo || value > k.hi) { set_error("%s = %d is outside %d .. %d", name, value, k.lo, k.hi); return KVQ_ERR_INVALID_ARG; }
+            tuning().*(k.field) = value;
+            return KVQ_OK;
+        }
+    set_error("unknown tuning entry '%s'", name);
+    return KVQ_ERR_INVALID_ARG;
+}
+
+extern "C" int kvq_tuning_get(const char *name, int32_t *value)
+{
+    if (!name || !value) { set_error("name or value is NULL"); return KVQ_ERR_INVALID_ARG; }
+    for (const TuningKey &k : kTuningKeys)
+        if (strcmp(name, k.name) == 0) { *value = tuning().*(k.field); return KVQ_OK; }
+    set_error("unknown tuning entry '%s'", name);
+    return KVQ_ERR_INVALID_ARG;
+}
+
+extern "C" const char *kvq_version(void) { return "kvq 0.2 (gfx950)"; }
 extern "C" const char *kvq_last_error(void) { return g_err; }
 
 extern "C" size_t kvq_cache_arena_bytes(const kvq_cache_desc *desc)
@@ -1051,14 +1112,14 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
         if (rc != KVQ_OK) return rc;
     }
     // many tokens per sequence: the lane-per-token kernel (needs 16-byte aligned vectors); else a wave per vector
-    static const int bulk_min_T = getenv("KVQ_APPEND_BULK_MIN_T") ? atoi(getenv("KVQ_APPEND_BULK_MIN_T")) : 32;
-    if (T >= bulk_min_T && (((uintptr_t)k | (uintptr_t)v) & 15) == 0) {
+    const Tuning &tn = tuning();
+    if (T >= tn.append_bulk_min_T && (((uintptr_t)k | (uintptr_t)v) & 15) == 0) {
         const int tiles = (T + kBlockTokens - 1) / kBlockTokens;
         const long long waves = nl * n_seq * (long long)tiles * d.n_kv_heads;
-        const int stream_min = getenv("KVQ_APPEND_STREAM_MIN") ? atoi(getenv("KVQ_APPEND_STREAM_MIN")) : 16;
+        const int stream_min = tn.append_stream_min;
         // long prompts go block by block of the cache; below about 512 tokens per sequence the tile kernel's shorter
         // chain of dependent reads wins (measured at 32 sequences: 256 tokens 31 against 37 us, 512 tokens 53 against 48)
-        const int block_min_T = getenv("KVQ_APPEND_BLOCK_MIN_T") ? atoi(getenv("KVQ_APPEND_BLOCK_MIN_T")) : 512;
+        const int block_min_T = tn.append_block_min_T;
         const int items = tiles + 7;                               // upper bound of the blocks one sequence's call touches
         const long long pairs = nl * n_seq, gx = ((long long)items * d.n_kv_heads + 3) / 4;
         if (T >= block_min_T && gx * pairs <= (1LL << 24)) {       // (a launch beyond that size goes tile by tile)

@@ -286,13 +286,6 @@ __global__ __launch_bounds__(64 * NW) void k_mlp_mfma(MlpArgs A, long long ntile
     }
 }
 
-static int env_int_or(const char *name, int dflt, int lo, int hi)
-{
-    const char *e = getenv(name);
-    const int v = e ? atoi(e) : dflt;
-    return v >= lo && v <= hi ? v : dflt;
-}
-
 static int device_cu_count(int *out)
 {
     static int n_cu = 0;
@@ -331,8 +324,9 @@ template <int T1, int T2> static int launch_mfma(const MlpArgs &A, hipStream_t s
     const int rc = device_cu_count(&n_cu);
     if (rc != KVQ_OK) return rc;
     const long long ntiles = (A.n + 31) / 32;
-    const int nw = env_int_or("KVQ_CONTROLLER_WAVES", ntiles >= 8LL * n_cu ? 8 : 4, 4, 8);
-    const int per_cu = env_int_or("KVQ_CONTROLLER_WG_PER_CU", nw == 8 ? 1 : 2, 1, 4);
+    const Tuning &tn = tuning();
+    const int nw = (tn.controller_waves == 4 || tn.controller_waves == 8) ? tn.controller_waves : ntiles >= 8LL * n_cu ? 8 : 4;
+    const int per_cu = tn.controller_wg_per_cu >= 1 ? tn.controller_wg_per_cu : nw == 8 ? 1 : 2;
     if (nw == 8) return launch_mfma_nw<T1, T2, 8>(A, st, (long long)per_cu * n_cu);
     return launch_mfma_nw<T1, T2, 4>(A, st, (long long)per_cu * n_cu);
 }
@@ -428,7 +422,7 @@ extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp,
     }
         hipLaunchKernelGGL(k_mlp_row, dim3((unsigned)n), dim3(staged && n <= 256 ? 1024 : kRowThreads), lds, st, A, staged);
     } else if (mfma_width(A.dims[1]) && (A.n_linear == 2 || mfma_width(A.dims[2])) && ((uintptr_t)feats & 15) == 0 &&
-               !getenv("KVQ_CONTROLLER_NO_MFMA")) {
+               !tuning().controller_no_mfma) {
         const int t1 = A.dims[1] / 32, t2 = A.n_linear == 3 ? A.dims[2] / 32 : 0;
         const int rc = t1 == 1 ? launch_mfma_t2<1>(t2, A, st) : t1 == 2 ? launch_mfma_t2<2>(t2, A, st) : launch_mfma_t2<4>(t2, A, st);
         if (rc != KVQ_OK) return rc;

@@ -7,6 +7,7 @@
 #include <stddef.h>
 
 #include "kvq.h"
+#include "kvq_tuning.h"
 
 namespace kvq {
 

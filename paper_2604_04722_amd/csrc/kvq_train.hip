@@ -461,7 +461,7 @@ extern "C" int kvq_controller_train_step(const float *feats, const uint8_t *labe
     for (int l = 0; l < A.n_linear; ++l) lds += (size_t)A.dims[l + 1] * (A.dims[l] + 2) * sizeof(float);    // weights (padded rows) + bias
     hipStream_t st = (hipStream_t)stream;
     const auto mm_width = [](int w) { return w == 32 || w == 64 || w == 128; };
-    const bool mm = A.n_linear == 3 && mm_width(A.dims[1]) && mm_width(A.dims[2]) && !getenv("KVQ_TRAIN_NO_MFMA");
+    const bool mm = A.n_linear == 3 && mm_width(A.dims[1]) && mm_width(A.dims[2]) && !tuning().train_no_mfma;
     const int t1 = mm ? A.dims[1] / 32 : 0, t2 = mm ? A.dims[2] / 32 : 0;
     int rc_launch = KVQ_OK;
     switch (t1 * 8 + t2) {

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import (OracleCache, assert_attn_close, assert_export_equals, dev, env, gpu_f16, make_kv, to_bits_u16)
+from helpers import (OracleCache, assert_attn_close, assert_export_equals, dev, tuning, gpu_f16, make_kv, to_bits_u16)
 from paper_2604_04722_amd import binding as kvq
 
 pytestmark = pytest.mark.gpu
@@ -60,14 +60,14 @@ def test_uniform_width_append_is_bit_exact(b, T):
 
 def test_config1_shape_mixed_append_bit_exact_and_attention_matches():
     say("config 1 shape: ctx 512, 9q/3kv, uniform random widths, one bulk append")
-    from paper_2604_04722_amd import workloads as wl
+    import workloads as wl
     cfg = wl.CONFIGS[1]
     bits = wl.uniform_bits(cfg, 1, cfg.context)
     cache, ocs = build_both(1, cfg.context, cfg.n_q_heads, cfg.n_kv_heads, bits, seed=11)
     assert_export_equals(cache, 0, 0, ocs[0])
     q = make_kv((1, cfg.n_q_heads, 64), 12, outlier=False)
     for splits in (0, 1, 3):
-        with env(KVQ_ATTN_SPLITS=splits):
+        with tuning(attn_splits=splits):
             out, lse, p2 = run_attn(cache, 0, q, 1, cfg.n_q_heads)
         want, want_lse, probs = ocs[0].attn(0, q[0], cfg.n_q_heads, want_probs=True)
         assert_attn_close(out[0], want, "splits=%d" % splits)
@@ -118,7 +118,7 @@ def test_attention_head_layouts_wave_counts_and_splits(Hq, Hkv, waves):
     cache, ocs = build_both(B, T, Hq, Hkv, bits, seed=41)
     q = make_kv((B, Hq, 64), 42, outlier=False)
     for splits in (1, 2, 5):
-        with env(KVQ_ATTN_SPLITS=splits, KVQ_ATTN_WAVES=waves):
+        with tuning(attn_splits=splits, attn_waves=waves):
             out, _, _ = run_attn(cache, 0, q, B, Hq, want_aux=False)
         for s in range(B):
             want, _, _ = ocs[0].attn(s, q[s], Hq)
@@ -186,7 +186,7 @@ def test_longest_first_launch_order_on_a_ragged_batch(B, fused):
     ws = torch.empty(kvq.kvq_decode_attn_workspace(cache, B), dtype=torch.uint8, device=dev())
     out = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=dev())
     lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
-    with env(KVQ_ATTN_LONGEST_FIRST=1):
+    with tuning(attn_longest_first=1):
         if fused:
             kn, vn = make_kv((B, 1, Hkv, 64), 901), make_kv((B, 1, Hkv, 64), 902)
             nb = rng.choice([2, 4, 8, 16], B).astype(np.uint8)
@@ -314,7 +314,7 @@ def test_bulk_append_streaming_and_cached_stores_write_the_same_bytes(stream_min
     K, V = make_kv((B, T, Hkv, 64), 801), make_kv((B, T, Hkv, 64), 802, outlier=False)
     cache = kvq.Cache(1, B, Hq, Hkv, T)
     oc = OracleCache(B, Hkv)
-    with env(KVQ_APPEND_STREAM_MIN=stream_min):
+    with tuning(append_stream_min=stream_min):
         kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
     for s in range(B):
         oc.append(s, K[s], V[s], bits[s])
@@ -424,10 +424,10 @@ def test_host_side_argument_checks_change_nothing():
     ws = torch.empty(16, dtype=torch.uint8, device=dev())
     with pytest.raises(kvq.KvqError):
         kvq.kvq_decode_attn(cache, 5, K, None, 2, out, ws)
-    with env(KVQ_ATTN_SPLITS=4):
+    with tuning(attn_splits=4):
         with pytest.raises(kvq.KvqError):
             kvq.kvq_decode_attn(cache, 0, K, None, 2, out, ws)    # workspace too small for 4 splits
-    with env(KVQ_ATTN_SPLITS=4):
+    with tuning(attn_splits=4):
         with pytest.raises(kvq.KvqError):                         # the fused call checks its workspace before it books the token
             kvq.kvq_append_decode_attn(cache, 0, K, K, bits.view(-1), K, None, 2, out, ws)
     assert int(cache.counts()[:, 4].sum()) == 0 and cache.status()[0] == 0
@@ -443,7 +443,7 @@ def test_running_twice_gives_bitwise_identical_attention():
     bits = np.random.default_rng(130).choice([2, 4, 8, 16], (B, T)).astype(np.uint8)
     cache, _ = build_both(B, T, Hq, Hkv, bits, seed=131)
     q = make_kv((B, Hq, 64), 132, outlier=False)
-    with env(KVQ_ATTN_SPLITS=3):
+    with tuning(attn_splits=3):
         a, _, _ = run_attn(cache, 0, q, B, Hq)
         b, _, _ = run_attn(cache, 0, q, B, Hq)
     assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
@@ -478,7 +478,7 @@ def test_fused_append_attention_equals_the_oracle_and_the_two_call_path(Hq, Hkv,
                 out = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=dev())
                 lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
                 p2 = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
-                with env(KVQ_ATTN_SPLITS=splits, KVQ_ATTN_WAVES=waves):
+                with tuning(attn_splits=splits, attn_waves=waves):
                     kvq.kvq_append_decode_attn(cache, l, gpu_f16(K), gpu_f16(V), bt if l == 0 else None, gpu_f16(q), None, B,
                                                out, ws, lse, p2)
                 for s in range(B):
@@ -486,7 +486,7 @@ def test_fused_append_attention_equals_the_oracle_and_the_two_call_path(Hq, Hkv,
                 if step % 23 == 0 or step == steps - 1:
                     out2 = torch.zeros_like(out)
                     kvq.kvq_append(ref, l, gpu_f16(K), gpu_f16(V), bt if l == 0 else None, None, B, 1)
-                    with env(KVQ_ATTN_SPLITS=splits, KVQ_ATTN_WAVES=waves):
+                    with tuning(attn_splits=splits, attn_waves=waves):
                         kvq.kvq_decode_attn(ref, l, gpu_f16(q), None, B, out2, ws)
                     torch.cuda.synchronize()
                     o, o2 = out.cpu().numpy(), out2.cpu().numpy()

@@ -14,7 +14,7 @@ import torch
 import oracle
 from helpers import ATOL, RTOL, assert_attn_close, dev, to_bits_u16
 from paper_2604_04722_amd import binding as kvq
-from paper_2604_04722_amd import workloads as wl
+import workloads as wl
 
 pytestmark = pytest.mark.gpu
 

@@ -8,7 +8,7 @@ import torch
 import oracle
 from helpers import dev
 from paper_2604_04722_amd import binding as kvq
-from paper_2604_04722_amd import workloads as wl
+import workloads as wl
 
 pytestmark = pytest.mark.gpu
 

@@ -7,7 +7,8 @@ import torch
 
 from helpers import dev
 from paper_2604_04722_amd import binding as kvq
-from paper_2604_04722_amd import workloads as wl
+import benchprobe
+import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
@@ -93,9 +94,9 @@ def test_measurement_probes_copy_every_byte_and_read_in_bounds(n16):
     g = torch.Generator(device="cpu").manual_seed(n16)
     src = torch.randint(0, 2 ** 31 - 1, (n16 * 4 + 8,), dtype=torch.int32, generator=g).to(dev())
     dst = torch.full((n16 * 4 + 8,), -7, dtype=torch.int32, device=dev())
-    kvq.kvq_probe_copy(dst[:n16 * 4], src[:n16 * 4])
+    benchprobe.copy(dst[:n16 * 4], src[:n16 * 4])
     sink = torch.zeros(1, dtype=torch.int32, device=dev())
-    kvq.kvq_probe_read(src[:n16 * 4], sink)
+    benchprobe.read(src[:n16 * 4], sink)
     torch.cuda.synchronize()
     assert torch.equal(dst[:n16 * 4], src[:n16 * 4])
     assert bool((dst[n16 * 4:] == -7).all())

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import oracle
-from helpers import assert_attn_close, dev, env, gpu_f16, make_kv
+from helpers import assert_attn_close, dev, tuning, gpu_f16, make_kv
 from paper_2604_04722_amd import binding as kvq
 
 pytestmark = pytest.mark.gpu
@@ -97,7 +97,7 @@ def test_per_channel_keys_prefill_then_decode_steps(Hq, Hkv, waves, splits):
             q = make_kv((B, Hq, 64), 9000 + 10 * step + l, outlier=False)
             out = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=dev())
             lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
-            with env(KVQ_ATTN_WAVES=waves, KVQ_ATTN_SPLITS=splits):
+            with tuning(attn_waves=waves, attn_splits=splits):
                 if fused:
                     kvq.kvq_append_decode_attn(cache, l, gpu_f16(K), gpu_f16(V), bt if l == 0 else None, gpu_f16(q), None, B, out, ws, lse)
                 else:
@@ -173,7 +173,7 @@ def test_per_channel_quotients_on_ties_out_of_range_values_and_all_layers_at_onc
     cache = kvq.Cache(L, B, Hq, Hkv, T)
     cache.set_k_channel_quant(torch.from_numpy(mn.view(np.int16)).view(torch.float16).to(dev()),
                               torch.from_numpy(rg.view(np.int16)).view(torch.float16).to(dev()))
-    with env(KVQ_APPEND_BLOCK_MIN_T=block_min_T):
+    with tuning(append_block_min_T=block_min_T):
         kvq.kvq_append(cache, -1, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
     for l in range(L):
         oc = OracleKch(B, Hkv, mn[l], rg[l])

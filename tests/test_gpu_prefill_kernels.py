@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import OracleCache, assert_attn_close, assert_export_equals, dev, env, gpu_f16, make_kv
+from helpers import OracleCache, assert_attn_close, assert_export_equals, dev, tuning, gpu_f16, make_kv
 from paper_2604_04722_amd import binding as kvq
 
 pytestmark = pytest.mark.gpu
@@ -33,7 +33,7 @@ def test_chunked_prompts_start_every_class_at_any_slot(kernel, chunks):
     rng = np.random.default_rng(sum(chunks) + len(chunks))
     cache = kvq.Cache(n_layers, B, Hq, Hkv, total)
     ocs = [OracleCache(B, Hkv) for _ in range(n_layers)]
-    with env(KVQ_APPEND_BLOCK_MIN_T=KERNELS[kernel]):
+    with tuning(append_block_min_T=KERNELS[kernel]):
         for ci, T in enumerate(chunks):
             bits = mix(rng, (B, T))
             K = make_kv((n_layers, B, T, Hkv, 64), 900 + ci)
@@ -62,7 +62,7 @@ def test_absent_and_rare_classes(kernel, p):
     rng = np.random.default_rng(int(1000 * p[0]) + 7)
     cache = kvq.Cache(1, B, Hq, Hkv, 2 * T)
     oc = OracleCache(B, Hkv)
-    with env(KVQ_APPEND_BLOCK_MIN_T=KERNELS[kernel]):
+    with tuning(append_block_min_T=KERNELS[kernel]):
         for ci in range(2):
             bits = mix(rng, (B, T), p)
             K, V = make_kv((B, T, Hkv, 64), 1000 + ci), make_kv((B, T, Hkv, 64), 1010 + ci)
@@ -81,7 +81,7 @@ def test_listed_sequences_a_skipped_one_and_attention_afterwards(kernel):
     cache = kvq.Cache(1, 4, Hq, Hkv, max_ctx)
     oc = OracleCache(4, Hkv)
     rng = np.random.default_rng(77)
-    with env(KVQ_APPEND_BLOCK_MIN_T=KERNELS[kernel]):
+    with tuning(append_block_min_T=KERNELS[kernel]):
         # sequence 1 is filled to 300 first: a further 150 do not fit
         bits = mix(rng, (1, 300))
         K, V = make_kv((1, 300, Hkv, 64), 1100), make_kv((1, 300, Hkv, 64), 1101)
@@ -120,7 +120,7 @@ def test_an_empty_pool_sends_blocks_to_the_sink_page_without_a_fault(kernel):
     rng = np.random.default_rng(5)
     bits = mix(rng, (B, T), (0.25, 0.25, 0.25, 0.25))
     K, V = make_kv((B, T, Hkv, 64), 1200), make_kv((B, T, Hkv, 64), 1201)
-    with env(KVQ_APPEND_BLOCK_MIN_T=KERNELS[kernel]):
+    with tuning(append_block_min_T=KERNELS[kernel]):
         kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
     flags, free = cache.status()
     assert flags == kvq.FLAG_POOL_EXHAUSTED and free == [0, 0, 0, 0]

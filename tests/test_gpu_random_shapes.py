@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import OracleCache, assert_attn_close, assert_export_equals, dev, env, gpu_f16, make_kv
+from helpers import OracleCache, assert_attn_close, assert_export_equals, dev, tuning, gpu_f16, make_kv
 from paper_2604_04722_amd import binding as kvq
 
 pytestmark = pytest.mark.gpu
@@ -53,7 +53,7 @@ def test_random_case(case):
             K = make_kv((1, tc, Hkv, 64), 10000 * case + 100 * s + t0, outlier=bool(rng.integers(0, 2)))
             V = make_kv((1, tc, Hkv, 64), 10000 * case + 100 * s + t0 + 50, outlier=False)
             ids = torch.tensor([s], dtype=torch.int32, device=dev())
-            with env(KVQ_APPEND_BLOCK_MIN_T=block_min_T):
+            with tuning(append_block_min_T=block_min_T):
                 kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits[None, t0:t0 + tc].copy()).to(dev()), ids, 1, tc)
             oc.append(s, K[0], V[0], bits[t0:t0 + tc])
             t0 += tc
@@ -68,7 +68,7 @@ def test_random_case(case):
     out = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=dev())
     lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
     p2 = torch.zeros((B, Hq), dtype=torch.float32, device=dev())
-    with env(KVQ_ATTN_WAVES=waves, KVQ_ATTN_SPLITS=splits, KVQ_ATTN_LONGEST_FIRST=lf):
+    with tuning(attn_waves=waves, attn_splits=splits, attn_longest_first=lf):
         if fused:
             kn, vn = make_kv((B, 1, Hkv, 64), 888 + case), make_kv((B, 1, Hkv, 64), 999 + case)
             nb = rng.choice([2, 4, 8, 16], B).astype(np.uint8)

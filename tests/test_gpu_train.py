@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import env, dev
+from helpers import tuning, dev
 from oracle import train as T
 from paper_2604_04722_amd import binding as kvq
 
@@ -104,8 +104,8 @@ def test_train_step_matches_the_oracle(dims, n):
 
 
 def test_train_step_on_the_vector_alu_when_the_matrix_core_path_is_switched_off():
-    print("train step 4-128-128-4, n=500, KVQ_TRAIN_NO_MFMA=1", flush=True)
-    with env(KVQ_TRAIN_NO_MFMA=1):
+    print("train step 4-128-128-4, n=500, train_no_mfma=1", flush=True)
+    with tuning(train_no_mfma=1):
         check_step((4, 128, 128, 4), 500, seed=99)
 
 
