@@ -25,7 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-EVENT_EVERY = 10       # timed steps between two steps whose launches are bracketed by events (fewer for short runs)
+EVENT_STEPS = 5        # timed steps whose launches are bracketed by events (spread evenly over the run)
 
 
 def parse():
@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (4 = SmolLM-1.7B-shaped, the metric's config)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (profiling runs only)")
+    ap.add_argument("--variant", default="mixed", choices=["mixed", "static4", "fp16", "kchannel"],
+                    help="cache the timed loops run on (profiling runs: the same config stored as static 4-bit, FP16, or with "
+                         "per-channel keys); anything but 'mixed' is not the metric and is named in config.variant")
     ap.add_argument("--no-compare", action="store_true", help="skip the static-4-bit, FP16, rule-policy and per-channel-key caches")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-events", action="store_true", help="do not bracket attention launches with events")
@@ -249,9 +252,9 @@ def main():
             if replay is not None:
                 replay()
             else:
-                # event brackets on every EVENT_EVERY-th timed step only: an event record costs ~3 us of device time, and
-                # bracketing every launch of every step would inflate the step by 5 %, every fifth by 1 %
-                every = max(1, min(EVENT_EVERY, timed_steps // 2))
+                # event brackets on EVENT_STEPS of the timed steps only: an event record costs ~3 us of device time, and
+                # bracketing every launch of every step would inflate the step by 5 %, every fourth by about 1 %
+                every = max(1, timed_steps // EVENT_STEPS)
                 step(s, events and (s - warm_steps) % every == every // 2)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
@@ -276,6 +279,7 @@ def main():
                 # (layers >= 1: no bookkeeping), plus one event record (~3 us)
                 gaps = [ev_pairs[i][1].elapsed_time(ev_pairs[i + 1][0]) * 1e3 for i in range(len(ev_pairs) - 1) if i % L != L - 1]
                 res["append_us_per_layer"] = float(np.median(gaps))
+            res["attn_launches_timed"] = len(attn_us)
             res["attn_us_per_layer"] = float(np.mean(attn_us))
             res["attn_us_min"] = float(np.min(attn_us))
             res["attn_us_median"] = float(np.median(attn_us))
@@ -286,19 +290,19 @@ def main():
         return cache, res
 
     # ---------------- mixed-precision path: the metric ----------------------------------------------
-    cache, mixed = run_variant("mixed", args.steps, args.warmup, not args.no_events)
+    cache, mixed = run_variant(args.variant, args.steps, args.warmup, not args.no_events)
     # the same step with append fused into the attention launch (one kernel per layer instead of two), continuing on
     # the same cache; its token count stays below max_context because n_steps covers both loops
     fused = None
     if not args.no_fused:
-        _, fused = run_variant("mixed", args.steps, args.warmup, not args.no_events, fused=True, cache=cache)
+        _, fused = run_variant(args.variant, args.steps, args.warmup, not args.no_events, fused=True, cache=cache)
     # small configs stay resident in the 256 MB Infinity Cache: time the same loop over rotating copies of the cache
     rotating = None
     total_bytes = mixed["attn_bytes_per_layer"] * L
     if total_bytes < 256e6 and not args.no_rotate:
         n_copies = int(min(64, math.ceil(512e6 / total_bytes)))
-        copies = [build_cache("mixed") for _ in range(n_copies - 1)]
-        _, rot = run_variant("mixed", args.steps, args.warmup, not args.no_events, cache=cache, rotate=copies)
+        copies = [build_cache(args.variant) for _ in range(n_copies - 1)]
+        _, rot = run_variant(args.variant, args.steps, args.warmup, not args.no_events, cache=cache, rotate=copies)
         rotating = {"copies": n_copies, "total_MB": n_copies * total_bytes / 1e6, "us_per_step": rot["ms_per_step"] * 1e3,
                     "attn_us_per_layer": rot.get("attn_us_per_layer"),
                     "note": "four-call path, step s on copy s mod copies (at most 64 copies are built)"}
@@ -307,7 +311,7 @@ def main():
         del copies
     graph_res = None
     if not args.no_fused and not args.no_graph:
-        _, graph_res = run_variant("mixed", args.steps, args.warmup, False, fused=True, cache=cache, graph=True)
+        _, graph_res = run_variant(args.variant, args.steps, args.warmup, False, fused=True, cache=cache, graph=True)
 
     # measured streaming-read rate of a trivial kernel on this device (context for the 8 TB/s nominal peak)
     probe = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
@@ -456,26 +460,34 @@ def main():
         ld = int(lens_h.max())
         probs = rng_c.random((B, Hq, ld))
         probs /= probs.sum(axis=2, keepdims=True)
-        c0 = time.perf_counter()
-        f_h = oracle.features(lg, ids_h, counts_np, N, Vobs, probs, np.full(B, ld, np.int32))
-        oracle.counts_update(ids_h, counts_np, N, Vobs)
-        t_feat = time.perf_counter() - c0
-        c0 = time.perf_counter()
-        b_h, _ = oracle.controller(f_h, Ws, bs)
-        t_ctrl = time.perf_counter() - c0
-        k1 = step_k[0][0][0].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)   # [B,1,Hkv,64]
-        v1 = step_k[0][0][1].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
-        c0 = time.perf_counter()
-        for s_ in range(B):
-            oracle.append(k1[s_], v1[s_], np.asarray(b_h[s_:s_ + 1], np.uint8))
-        t_app = (time.perf_counter() - c0) * L
+        # these three legs are spread over the host cores row by row / sequence by sequence (the oracle's calls release
+        # the interpreter lock), like the attention leg
+        from concurrent.futures import ThreadPoolExecutor
+        nw = max(1, min(nthr, B))
+        cuts = np.linspace(0, B, nw + 1).astype(int)
+        parts = [(int(a), int(b)) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+        with ThreadPoolExecutor(max_workers=nw) as pool:
+            c0 = time.perf_counter()
+            f_h = np.concatenate(list(pool.map(
+                lambda ab: oracle.features(lg[ab[0]:ab[1]], ids_h[ab[0]:ab[1]], counts_np, N, Vobs, probs[ab[0]:ab[1]],
+                                           np.full(ab[1] - ab[0], ld, np.int32)), parts)))
+            oracle.counts_update(ids_h, counts_np, N, Vobs)
+            t_feat = time.perf_counter() - c0
+            c0 = time.perf_counter()
+            b_h, _ = oracle.controller(f_h, Ws, bs)
+            t_ctrl = time.perf_counter() - c0
+            k1 = step_k[0][0][0].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)   # [B,1,Hkv,64]
+            v1 = step_k[0][0][1].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+            c0 = time.perf_counter()
+            list(pool.map(lambda s_: oracle.append(k1[s_], v1[s_], np.asarray(b_h[s_:s_ + 1], np.uint8)), range(B)))
+            t_app = (time.perf_counter() - c0) * L
         del probs
         total = best * scale + t_feat + t_ctrl + t_app
         cpu = {"value": total * 1e6, "unit": "us/step", "cores": nthr, "kind": "oracle",
                "sample": "decode attention of %d of %d sequences of ONE layer at full context (min of 3 runs, %.2f s each on %d "
                          "threads), scaled by tokens to the batch and by %d layers = %.2f s; plus, timed once: features of the "
                          "batch %.3f s, controller %.4f s, quantize-and-append of one token per sequence x %d layers %.3f s "
-                         "(these three single-threaded)" % (ns, B, best, nthr, L, best * scale, t_feat, t_ctrl, L, t_app)}
+                         "(features and append spread over %d threads by rows / sequences, the controller's %d rows on one)" % (ns, B, best, nthr, L, best * scale, t_feat, t_ctrl, L, t_app, nw, B)}
     cache.destroy()
     del cache
     torch.cuda.empty_cache()
@@ -506,14 +518,14 @@ def main():
         "vs_baseline": None,
         "dtype": "u2/u4/u8 codes + f16 scale/min, f16 storage class, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "config_index": cfg.index, "layers": L, "batch": B, "context": cfg.context,
+        "config": {"workload": cfg.name, "variant": args.variant, "config_index": cfg.index, "layers": L, "batch": B, "context": cfg.context,
                    "q_heads": Hq, "kv_heads": Hkv, "head_dim": 64,
                    "mix_2_4_8_16": [round(x / tot, 4) for x in tok],
                    "expected_bits": round(sum(x * w for x, w in zip(tok, (2, 4, 8, 16))) / tot, 3)},
         "stages_us": {"features": mixed.get("features_us"), "controller": mixed.get("controller_us"),
                       "append_per_layer": mixed.get("append_us_per_layer"),
                       "attn_per_layer": mixed.get("attn_us_per_layer"), "attn_per_layer_median": mixed.get("attn_us_median"),
-                      "attn_per_layer_min": mixed.get("attn_us_min")},
+                      "attn_per_layer_min": mixed.get("attn_us_min"), "attn_launches_timed": mixed.get("attn_launches_timed")},
         "stream_read_GBps": stream_gbps,
         "fused_path": None if fused is None else {
             "us_per_step": fused["ms_per_step"] * 1e3, "launch_us_per_layer": fused.get("attn_us_per_layer"),
@@ -527,17 +539,25 @@ def main():
         "prefill": prefill,
         "compare": compare,
     }
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "k_decode_split_cfg%d_traffic.txt" % cfg.index)
+    # HBM bytes per launch by the hardware counters: taken in rocprofv3 --pmc runs of this command and condensed by
+    # benchprobe/pmc_summary.py into profiles/; printed only while the attention kernel's sources are the ones profiled
+    traffic, traffic_note = None, None
+    tname = "k_decode_split_cfg%d%s_traffic.txt" % (cfg.index, "" if args.variant == "mixed" else "_" + args.variant)
+    tpath = os.path.join(ROOT, "profiles", tname)
     if os.path.exists(tpath) and L == cfg.n_layers:
-        for line in open(tpath):
-            if line.startswith("traffic_bytes_per_launch="):
-                traffic = float(line.split("=", 1)[1])
+        from benchprobe.pmc_summary import sources_sha256
+        kv = dict(line.strip().split("=", 1) for line in open(tpath) if "=" in line and not line.startswith("#"))
+        if kv.get("sources_sha256") == sources_sha256():
+            traffic = float(kv["traffic_bytes_per_launch"])
+        else:
+            traffic_note = "profiles/%s was taken from other kernel sources than the ones in this tree" % tname
     if "attn_GBps" in mixed:
         result["roofline"] = {"bound": "hbm", "achieved": mixed["attn_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": mixed["attn_GBps"] / HBM_PEAK_GBPS, "traffic": traffic,
                               "kernel": "k_decode_split", "bytes_per_launch": mixed["attn_bytes_per_layer"],
                               "frac_of_stream_read": mixed["attn_GBps"] / stream_gbps}
+        if traffic_note:
+            result["roofline"]["traffic_note"] = traffic_note
     if cpu is not None:
         result["cpu_baseline"] = cpu
     print(json.dumps(result))

@@ -162,6 +162,34 @@ def test_ragged_lengths_empty_sequence_and_seq_ids():
         np.testing.assert_allclose(lse[i], want_lse, rtol=1e-4, atol=1e-4)
 
 
+@pytest.mark.parametrize("mu", [2.0, 5.0, -3.0])
+@pytest.mark.parametrize("width", [2, 4, 8, 0])
+def test_queries_with_a_nonzero_mean_on_heavy_tailed_keys(mu, width):
+    """The kernel reads a code as h = 1 + c/M and subtracts the constant part M * sum(q) afterwards, so its rounding error
+    grows with |sum(q)|: queries ~ N(mu, 1) (sum q in the hundreds) on keys with Student-t channel scales, every width
+    alone and the mix (width 0), against the same tolerance as everything else."""
+    say("attention with q ~ N(%g, 1), width %s" % (mu, width or "mixed"))
+    B, T, Hq, Hkv = 2, 900, 6, 2
+    rng = np.random.default_rng(int(100 + 10 * mu + width))
+    bits = (rng.choice([2, 4, 8, 16], (B, T), p=[0.4, 0.3, 0.2, 0.1]) if width == 0 else np.full((B, T), width)).astype(np.uint8)
+    cache = kvq.Cache(1, B, Hq, Hkv, T)
+    oc = OracleCache(B, Hkv)
+    t3 = np.abs(rng.standard_normal((Hkv, 64)) / np.sqrt((rng.standard_normal((3, Hkv, 64)) ** 2).sum(axis=0) / 3.0)).clip(0.1, 50.0)
+    K = (rng.standard_normal((B, T, Hkv, 64)) * t3).astype(np.float16)
+    V = (rng.standard_normal((B, T, Hkv, 64)) * t3[::-1]).astype(np.float16)
+    kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), None, B, T)
+    for b in range(B):
+        oc.append(b, K[b], V[b], bits[b])
+    q = (rng.standard_normal((B, Hq, 64)) + mu).astype(np.float16)
+    for waves, splits in ((0, 0), (2, 1), (4, 3)):
+        with tuning(attn_waves=waves, attn_splits=splits):
+            out, lse, _ = run_attn(cache, 0, q, B, Hq)
+        for b in range(B):
+            want, want_lse, _ = oc.attn(b, q[b], Hq)
+            assert_attn_close(out[b], want, "mu %g width %d seq %d (waves %d, splits %d)" % (mu, width, b, waves, splits))
+            np.testing.assert_allclose(lse[b], want_lse, rtol=1e-4, atol=2e-4)
+
+
 @pytest.mark.parametrize("B,fused", [(8, False), (16, False), (16, True), (64, False)])
 def test_longest_first_launch_order_on_a_ragged_batch(B, fused):
     say("longest-first launch order, ragged batch of %d, fused=%s" % (B, fused))

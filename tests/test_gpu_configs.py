@@ -38,8 +38,11 @@ def controller_bits_both(cfg, feats):
     return want
 
 
-def prefill(cfg, cache, layer_count, bits, lens, chunk=512):
-    """Append bits[s, :lens[s]] tokens of every sequence, all layers, from kv_chunk_fast draws."""
+def prefill(cfg, cache, layer_count, bits, lens, chunk=512, layers=None):
+    """Append bits[s, :lens[s]] tokens of every sequence, all layers (or `layers`, which must start with 0: the layer-0
+    call does the bookkeeping), from kv_chunk_fast draws."""
+    layers = list(range(layer_count)) if layers is None else list(layers)
+    assert layers[0] == 0
     B = bits.shape[0]
     d = dev()
     Tmax = int(lens.max())
@@ -52,7 +55,7 @@ def prefill(cfg, cache, layer_count, bits, lens, chunk=512):
             idx = np.where(rem == r)[0]
             ids = torch.from_numpy(idx.astype(np.int32)).to(d)
             bt = torch.from_numpy(np.ascontiguousarray(bits[idx, t:t + r])).to(d)
-            for layer in range(layer_count):
+            for layer in layers:
                 K, V = wl.kv_chunk_fast(cfg, layer, ci, B, tc, d)
                 if len(idx) == B and r == tc:
                     kvq.kvq_append(cache, layer, K, V, bt if layer == 0 else None, None, B, tc)
@@ -161,9 +164,31 @@ def test_config4_prefill_in_the_2048_token_calls_the_benchmark_times():
     cache.destroy()
 
 
-def test_config5_ragged_long_context_run_clustered_widths_one_layer():
+def test_config4_last_layer_of_the_full_24_layer_cache():
+    """Layer addressing with multi-GB strides: the cache is created with all 24 layers and the pools bench.py gives it,
+    layers 0 and 23 are written, and the LAST layer is compared with the oracle (export and attention, one sequence)."""
+    cfg = wl.CONFIGS[4]
+    B, T, L = cfg.batch, cfg.context, cfg.n_layers
+    say("config 4: %d-layer cache (%d sequences x %d tokens), layers 0 and %d written, layer %d checked" % (L, B, T, L - 1, L - 1))
+    lens = np.full(B, T, np.int64)
+    bits = np.stack([controller_bits_both(cfg, wl.bulk_features(cfg, T, chunk=100 + s)) for s in range(B)])
+    pools = [int(sum(-(-int((bits[s] == w).sum() + 64) // 256) + 1 for s in range(B))) for w in (2, 4, 8, 16)]
+    cache = kvq.Cache(L, B, cfg.n_q_heads, cfg.n_kv_heads, T + 64, pool_pages=pools)
+    prefill(cfg, cache, L, bits, lens, layers=[0, L - 1])
+    assert cache.status()[0] == 0
+    seqs = [B - 1]
+    codes, meta = oracle_cache_for(cfg, L - 1, seqs, bits, lens)
+    q = wl.queries(cfg, L - 1, 0, B, dev())
+    check_sampled(cfg, cache, L - 1, seqs, bits, lens, codes, meta, q)
+    cache.destroy()
+
+
+@pytest.mark.parametrize("B", [16, 64])
+def test_config5_ragged_long_context_run_clustered_widths_one_layer(B):
+    """B = 64 is the config's real batch: 4096 waves for 2048 places, two waves per workgroup, longest-first launch
+    order (the launch the benchmark times).  B = 16 is the same workload in the four-waves-per-workgroup, single-round
+    regime."""
     cfg = wl.CONFIGS[5]
-    B = 16                                                   # a quarter of the batch keeps the test at ~1 GB
     say("config 5 shape: B=%d of %d, ragged ctx in [%d, %d], runs of equal width, one layer" % (B, cfg.batch, cfg.min_context, cfg.context))
     lens = wl.ragged_lengths(cfg).astype(np.int64)[:B]
     Tmax = int(lens.max())
@@ -174,7 +199,12 @@ def test_config5_ragged_long_context_run_clustered_widths_one_layer():
     assert cache.status()[0] == 0
     counts = cache.counts()
     assert np.array_equal(counts[:B, 4].numpy(), lens)
-    seqs = [int(np.argmin(lens)), int(np.argmax(lens))]
+    order = np.argsort(lens)
+    seqs = [int(order[0]), int(order[-1])]
+    if B == cfg.batch:
+        seqs += [int(order[B // 3]), int(order[2 * B // 3])]           # shortest, longest and two in between
+        mix = np.array([sum(int((bits[s, :lens[s]] == w).sum()) for s in range(B)) for w in (2, 4, 8, 16)], np.float64)
+        assert np.max(np.abs(mix / mix.sum() - np.array(cfg.mix))) < 0.03
     codes, meta = oracle_cache_for(cfg, 0, seqs, bits, lens, chunk=1024)
     q = wl.queries(cfg, 0, 0, B, dev())
     check_sampled(cfg, cache, 0, seqs, bits, lens, codes, meta, q)

@@ -242,6 +242,76 @@ def test_end_to_end_step_features_controller_append_attention():
     assert set(got_bits.tolist()) <= {2, 4, 8, 16}
 
 
+@pytest.mark.parametrize("cfg_index", [1, 2, 4])
+def test_assignment_chain_gpu_features_into_gpu_controller_against_the_oracle_chain(cfg_index):
+    """Precision assignments end to end (Sec. 3.5 features -> Sec. 3.6 controller): GPU features fed to the GPU controller
+    against oracle features fed to the oracle controller, on 10 240 rows of logits over the 49152-token vocabulary.  A row
+    may disagree only inside the widened tie gap 1e-5 + |W3||W2||W1| * |s_gpu - s_oracle| (spectral norms: the most the
+    feature error can move a logit difference, up to the factor 2 of a difference of two logits)."""
+    cfg = wl.CONFIGS[cfg_index]
+    say("assignment chain, controller %s, 10240 rows" % (cfg.mlp_dims,))
+    Ws, bs = wl.calibrated_mlp(cfg) if cfg_index >= 2 else wl.xavier_mlp(cfg)
+    lip = float(np.prod([np.linalg.norm(w.astype(np.float64), 2) for w in Ws]))
+    d = dev()
+    mlp = kvq.MlpWeights([torch.from_numpy(w).to(d) for w in Ws], [torch.from_numpy(b).to(d) for b in bs])
+    counts, N, Vobs, probs_tab = wl.zipf_table(wl.CONFIGS[4])
+    Hq, CH, n_total = 8, 1024, 10240
+    rng = np.random.default_rng(4722 + cfg_index)
+    differ = inside = 0
+    worst_df = 0.0
+    for c0 in range(0, n_total, CH):
+        # config-4-style rows (sigma 2) in the first half; the second half with a temperature of its own per row, so
+        # that the entropy and confidence features (and with them the decisions) spread over their range
+        g = torch.Generator(device="cpu").manual_seed(int(rng.integers(1 << 40)))
+        z = torch.randn((CH, wl.VOCAB), generator=g, dtype=torch.float32)
+        sig = np.full(CH, 2.0) if c0 < n_total // 2 else rng.uniform(0.3, 7.0, CH)
+        z *= torch.from_numpy(sig.astype(np.float32))[:, None]
+        logits = z.numpy()
+        ids = wl.zipf_ids(wl.CONFIGS[4], probs_tab, 50 + c0 // CH, CH)
+        lens = rng.integers(16, 1025, CH).astype(np.int32)
+        p2 = (np.exp(rng.normal(0.0, 1.0, (CH, Hq))) / lens[:, None]).clip(max=1.0)       # sum p^2 in [1/l, 1]
+        p2 = np.maximum(p2, 1.0 / lens[:, None])
+        got_f, _, _ = run_features(logits, ids, counts, N, Vobs, lens, Hq, sum_p2=p2)
+        # the oracle takes explicit attention rows; rows with the same sum of squares: one entry a, the rest equal
+        want_f = oracle.features(logits, ids, counts, N, Vobs, _rows_with_sum_p2(p2, lens), lens)
+        got_b = torch.zeros(CH, dtype=torch.uint8, device=d)
+        kvq.kvq_controller(torch.from_numpy(got_f).to(d), mlp, got_b)
+        got_b = got_b.cpu().numpy()
+        want_b, want_logits = oracle.controller(want_f, Ws, bs)
+        srt = np.sort(want_logits, axis=1)
+        gap = srt[:, -1] - srt[:, -2]
+        df = np.linalg.norm(got_f.astype(np.float64) - want_f.astype(np.float64), axis=1)
+        worst_df = max(worst_df, float(df.max()))
+        allowed = 1e-5 + 2.0 * lip * df
+        bad = got_b != want_b
+        assert not np.any(bad & (gap > allowed)), "assignment differs outside the widened gap at rows %s" % (c0 + np.where(bad & (gap > allowed))[0][:5])
+        differ += int(bad.sum())
+        inside += int((gap <= allowed).sum())
+    say("assignment chain cfg %d: %d of %d rows differ (%.4f %%); %d rows lie inside their widened gap; largest |ds| %.3g; |W3||W2||W1| = %.3g"
+        % (cfg_index, differ, n_total, 100.0 * differ / n_total, inside, worst_df, lip))
+
+
+def _rows_with_sum_p2(p2, lens):
+    """Attention rows [n, Hq, max l] (fp64) whose squares sum to p2: one entry a, the other l-1 entries (1-a)/(l-1), with
+    a the larger root of a^2 + (1-a)^2/(l-1) = p2."""
+    n, Hq = p2.shape
+    ld = int(lens.max())
+    rows = np.zeros((n, Hq, ld))
+    for t in range(n):
+        l = int(lens[t])
+        if l == 1:
+            rows[t, :, 0] = 1.0
+            continue
+        k = l - 1.0
+        # a^2 (1 + 1/k) - 2a/k + 1/k - p2 = 0
+        A, Bq, C = 1.0 + 1.0 / k, -2.0 / k, 1.0 / k - p2[t]
+        disc = np.maximum(Bq * Bq - 4.0 * A * C, 0.0)
+        a = (-Bq + np.sqrt(disc)) / (2.0 * A)
+        rows[t, :, :l] = ((1.0 - a) / k)[:, None]
+        rows[t, :, 0] = a
+    return rows
+
+
 def _front_inputs(n, vocab, Hq, seed, dup=True):
     rng = np.random.default_rng(seed)
     logits = (rng.standard_normal((n, vocab)) * 2.0).astype(np.float32)
