@@ -299,6 +299,19 @@ int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void *q, const 
                     int32_t n_seq, float *out, float *lse_out, float *sum_p2_out,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same call for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  It takes no workspace: the partial results of a
+ * launch that splits sequences over workgroups go to a fixed array of kvq_decode_attn_static_capacity() bytes (8 MiB)
+ * inside the library's device image, one copy per GPU, held until the process ends.  The call allocates and frees
+ * nothing and only enqueues kernels.  Results equal kvq_decode_attn's.  A launch whose partial results would not fit
+ * (n_seq x n_q_heads x splits x 272 bytes, with the split count the library picks for the cache's lengths) returns
+ * KVQ_ERR_CAPACITY and launches nothing.  All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams) race; calls on one stream are ordered and safe.  Nothing in the array has to be
+ * cleared between calls (every partial result a launch reads, it has written itself). */
+size_t kvq_decode_attn_static_capacity(void);
+int kvq_decode_attn_static(const kvq_cache *cache, int32_t layer, const void *q, const int32_t *seq_ids,
+                           int32_t n_seq, float *out, float *lse_out, float *sum_p2_out, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Stages 3 + 4 in one launch, for the decode step (one new token per sequence): the Concat update of
  * Sec. 3.2 followed by the attention of the same section, exactly as kvq_append(T = 1) followed by

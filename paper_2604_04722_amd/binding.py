@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export", "kvq_cache_import", "kvq_cache_set_k_channel_quant",
     "kvq_features_workspace", "kvq_features", "kvq_features_typed", "kvq_controller", "kvq_features_controller", "kvq_features_controller_typed", "kvq_rule_policy", "kvq_controller_param_count", "kvq_controller_train_workspace",
     "kvq_controller_train_step", "kvq_append", "kvq_decode_attn_workspace",
-    "kvq_decode_attn", "kvq_append_decode_attn", "kvq_tuning_set", "kvq_tuning_get",
+    "kvq_decode_attn", "kvq_decode_attn_static_capacity", "kvq_decode_attn_static", "kvq_append_decode_attn", "kvq_tuning_set", "kvq_tuning_get",
 )
 
 
@@ -113,6 +113,9 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_decode_attn_workspace.restype = sz
     lib.kvq_decode_attn_workspace.argtypes = [vp, i32]
     lib.kvq_decode_attn.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.kvq_decode_attn_static_capacity.restype = sz
+    lib.kvq_decode_attn_static_capacity.argtypes = []
+    lib.kvq_decode_attn_static.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp]
     lib.kvq_append_decode_attn.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.kvq_tuning_set.argtypes = [ctypes.c_char_p, i32]
     lib.kvq_tuning_get.argtypes = [ctypes.c_char_p, ctypes.POINTER(i32)]
@@ -409,6 +412,20 @@ def kvq_decode_attn(cache: Cache, layer: int, q: torch.Tensor, seq_ids: Optional
                                           _ptr(out, torch.float32, "out"), _ptr(lse_out, torch.float32, "lse_out"),
                                           _ptr(sum_p2_out, torch.float32, "sum_p2_out"),
                                           _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+def kvq_decode_attn_static_capacity() -> int:
+    return int(load_library().kvq_decode_attn_static_capacity())
+
+
+def kvq_decode_attn_static(cache: Cache, layer: int, q: torch.Tensor, seq_ids: Optional[torch.Tensor], n_seq: int,
+                           out: torch.Tensor, lse_out: Optional[torch.Tensor] = None,
+                           sum_p2_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """kvq_decode_attn without a workspace argument (the library's fixed scratch array); allocates nothing."""
+    _check(load_library().kvq_decode_attn_static(cache.handle, layer, _ptr(q, torch.float16, "q"),
+                                                 _ptr(seq_ids, torch.int32, "seq_ids"), n_seq,
+                                                 _ptr(out, torch.float32, "out"), _ptr(lse_out, torch.float32, "lse_out"),
+                                                 _ptr(sum_p2_out, torch.float32, "sum_p2_out"), _stream(stream)))
 
 
 def kvq_append_decode_attn(cache: Cache, layer: int, k: torch.Tensor, v: torch.Tensor, bits: Optional[torch.Tensor],

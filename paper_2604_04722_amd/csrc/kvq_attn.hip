@@ -26,6 +26,8 @@
 #include "kvq_internal.h"
 #include "kvq_quant.h"
 
+#include <mutex>
+
 namespace kvq {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -1165,6 +1167,61 @@ extern "C" int kvq_decode_attn(const kvq_cache *cache, int32_t layer, const void
     const int rc = plan_attn(cache, n_seq, 0, workspace, workspace_bytes, &plan);
     if (rc != KVQ_OK) return rc;
     return launch_attn(cache, plan, layer, q, nullptr, nullptr, seq_ids, n_seq, out, lse_out, sum_p2_out, workspace, stream);
+}
+
+// ---- the same call for callers that cannot allocate ---------------------------------------------------------------
+// The split launch's partial results go to a fixed array in the library's own device image instead of a caller
+// workspace.  Every GPU the library runs on holds its own copy of the array, at its own address, until the process
+// ends; the array's name is only a host-side handle, so the address is looked up once per device (with that device
+// current) and that pointer is what the kernels get.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];          // per device, filled on the first call there
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    KVQ_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device index %d is beyond the %d this library keeps a scratch address for", dev, kMaxDevices); return KVQ_ERR_UNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        KVQ_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { set_error("the scratch array has no device address"); return KVQ_ERR_DEVICE; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return KVQ_OK;
+}
+
+extern "C" size_t kvq_decode_attn_static_capacity(void) { return kStaticScratchBytes; }
+
+extern "C" int kvq_decode_attn_static(const kvq_cache *cache, int32_t layer, const void *q, const int32_t *seq_ids,
+                                      int32_t n_seq, float *out, float *lse_out, float *sum_p2_out, void *stream)
+{
+    if (!cache || !q || !out) { set_error("cache, q or out is NULL"); return KVQ_ERR_INVALID_ARG; }
+    const kvq_cache_desc &d = cache->desc;
+    if (layer < 0 || layer >= d.n_layers) { set_error("layer %d out of range", layer); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq < 0 || n_seq > d.max_seqs) { set_error("n_seq %d out of range (max_seqs %d)", n_seq, d.max_seqs); return KVQ_ERR_INVALID_ARG; }
+    if (n_seq == 0) return KVQ_OK;
+    void *ws = nullptr;
+    const int rc_s = static_scratch(&ws);
+    if (rc_s != KVQ_OK) return rc_s;
+    AttnPlan plan;
+    const int rc = plan_attn(cache, n_seq, 0, ws, kStaticScratchBytes, &plan);
+    if (rc != KVQ_OK) {
+        if (rc == KVQ_ERR_INVALID_ARG) {           // the only argument plan_attn can object to here is the scratch size
+            set_error("this launch needs more than the %zu bytes of the library's fixed scratch array "
+                      "(%d sequences x %d query heads x its split count x %zu bytes): use kvq_decode_attn with a workspace",
+                      kStaticScratchBytes, n_seq, d.n_q_heads, (size_t)kPartialFloats * sizeof(float));
+            return KVQ_ERR_CAPACITY;
+        }
+        return rc;
+    }
+    return launch_attn(cache, plan, layer, q, nullptr, nullptr, seq_ids, n_seq, out, lse_out, sum_p2_out, ws, stream);
 }
 
 extern "C" int kvq_append_decode_attn(kvq_cache *cache, int32_t layer, const void *k, const void *v, const uint8_t *bits,
