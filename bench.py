@@ -192,9 +192,9 @@ def main():
             if record:
                 e0 = torch.cuda.Event(enable_timing=True); e0.record()
             if fused:
-                # one launch: features, controller and the cache's bucket bookkeeping for the new token
+                # two launches: features, controller, count update and the cache's bucket bookkeeping for the new token
                 kvq.kvq_features_controller(step_logits[s % n_steps], step_ids[s % n_steps], counts_d, totals_d, True, sum_p2,
-                                            step_len[base_step + s], Hq, mlp, feats, step_bits.view(-1),
+                                            step_len[base_step + s], Hq, mlp, feats, step_bits.view(-1), fws,
                                             cache=cache if fixed is None else None)
                 if record:
                     e2 = torch.cuda.Event(enable_timing=True); e2.record()
@@ -323,6 +323,32 @@ def main():
     graph_res = None
     if not args.no_fused and not args.no_graph:
         _, graph_res = run_variant(args.variant, args.steps, args.warmup, False, fused=True, cache=cache, graph=True)
+
+    # the front end alone, back to back on the launch stream with no event records in between (the in-step figures
+    # above carry an event record per bracket and start behind a 100-us attention launch): 100 calls each, the steps'
+    # logits in turn
+    def front_loop(fn):
+        for s_ in range(3):
+            fn(s_)
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record()
+        for s_ in range(100):
+            fn(s_)
+        f1.record()
+        torch.cuda.synchronize()
+        return f0.elapsed_time(f1) * 1e3 / 100
+
+    fcounts = torch.from_numpy(counts_np).to(dev)
+    ftotals = torch.tensor([N, Vobs], dtype=torch.int64, device=dev)
+    flen = step_len[0]
+    front_alone = {
+        "fused_us": front_loop(lambda s_: kvq.kvq_features_controller(step_logits[s_ % n_steps], step_ids[s_ % n_steps], fcounts, ftotals,
+                                                                     True, sum_p2, flen, Hq, mlp, feats, step_bits.view(-1), fws)),
+        "separate_us": front_loop(lambda s_: (kvq.kvq_features(step_logits[s_ % n_steps], step_ids[s_ % n_steps], fcounts, ftotals, True, flen,
+                                                              Hq, feats, fws, sum_p2=sum_p2),
+                                              kvq.kvq_controller(feats, mlp, step_bits.view(-1)))),
+        "note": "kvq_features_controller (two launches) against kvq_features + kvq_controller (four launches), 100 calls back "
+                "to back without event records or cache bookkeeping; a launch costs about 7 us on this stream whatever it does"}
 
     # measured streaming-read rate of a trivial kernel on this device (context for the 8 TB/s nominal peak)
     probe = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
@@ -548,11 +574,12 @@ def main():
         "fused_path": None if fused is None else {
             "us_per_step": fused["ms_per_step"] * 1e3, "launch_us_per_layer": fused.get("attn_us_per_layer"),
             "front_us": fused.get("front_us"),
-            "note": "same step through kvq_features_controller (features + controller + bookkeeping, one launch) and "
+            "note": "same step through kvq_features_controller (features + controller + count update + bookkeeping, two launches) and "
                     "kvq_append_decode_attn (append + attention, one launch per layer); `value` above is the four-call path"},
         "graph_replay": None if graph_res is None else {
             "us_per_step": graph_res["ms_per_step"] * 1e3,
             "note": "the fused path's step captured once as a HIP graph and replayed (launch overhead off the host)"},
+        "front_end_alone": front_alone,
         "rotating_copies": rotating,
         "prefill": prefill,
         "compare": compare,

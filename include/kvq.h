@@ -223,22 +223,26 @@ typedef struct kvq_rule {
 int kvq_rule_policy(const float *feats, int64_t n, const kvq_rule *rule, uint8_t *bits_out, float *score_out, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Stages 1 + 2 in one launch, for the decode step (Sec. 3.4: saliency profiling, then the controller's decision,
+ * Stages 1 + 2 in one call, for the decode step (Sec. 3.4: saliency profiling, then the controller's decision,
  * then the token's place in the mixed-precision cache): the features of kvq_features in its sum_p2 form, the
- * decision of kvq_controller on them, and -- if `cache` is given -- the bucket bookkeeping that
+ * decision of kvq_controller on them, the count update, and -- if `cache` is given -- the bucket bookkeeping that
  * kvq_append(layer 0, T = 1) would do with those decisions.  Results are bit-identical to the separate calls.
- * One launch (plus the count update when update_counts is set) instead of five.
+ * Two launches instead of five: the pass over the logits, spread over rows x slices workgroups (it also copies each
+ * row's table entries, so that every read of the count table lies in the first launch and every update in the
+ * second), then one workgroup per row for the rest.
  *   logits .. attn_len, n_q_heads   as in kvq_features (sum_p2 is required, there is no attn_probs form)
  *   mlp, bits_out, logits_out       as in kvq_controller
  *   cache      NULL, or the cache whose sequences receive one token each: row i belongs to sequence seq_ids[i]
  *              (i if seq_ids is NULL); the following kvq_append / kvq_append_decode_attn calls of this step then
  *              pass bits = NULL on layer 0, which means "bookkeeping already done"
+ *   workspace  device, at least kvq_features_workspace(n, vocab) bytes, 16-byte aligned (slice results and the
+ *              rows' table entries between the two launches)
  * ------------------------------------------------------------------------------------------- */
 int kvq_features_controller(const float *logits, int64_t n, int64_t vocab, const int32_t *token_ids,
                             int64_t *counts, int64_t *totals, int32_t update_counts, const float *sum_p2,
                             const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp, kvq_cache *cache,
                             const int32_t *seq_ids, float *feats_out, uint8_t *bits_out, float *logits_out,
-                            void *stream);
+                            void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * The same two calls for logits that the model emits in a 16-bit type (Sec. 3.5 defines the features on the
@@ -258,7 +262,7 @@ int kvq_features_controller_typed(const void *logits, int32_t logits_dtype, int6
                                   const int32_t *token_ids, int64_t *counts, int64_t *totals, int32_t update_counts,
                                   const float *sum_p2, const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp,
                                   kvq_cache *cache, const int32_t *seq_ids, float *feats_out, uint8_t *bits_out,
-                                  float *logits_out, void *stream);
+                                  float *logits_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Stage 3 -- quantize and append (Sec. 3.7: k^ = Q_b(k), v^ = Q_b(v); Sec. 3.2: K <- Concat(K, k)).

@@ -98,10 +98,10 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_features.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp, sz, vp]
     lib.kvq_features_typed.argtypes = [vp, i32, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp, sz, vp]
     lib.kvq_features_controller_typed.argtypes = [vp, i32, i64, i64, vp, vp, vp, i32, vp, vp, i32, ctypes.POINTER(Mlp), vp, vp, vp, vp,
-                                                  vp, vp]
+                                                  vp, vp, sz, vp]
     lib.kvq_controller.argtypes = [vp, i64, ctypes.POINTER(Mlp), vp, vp, vp]
     lib.kvq_features_controller.argtypes = [vp, i64, i64, vp, vp, vp, i32, vp, vp, i32, ctypes.POINTER(Mlp), vp, vp, vp, vp,
-                                            vp, vp]
+                                            vp, vp, sz, vp]
     lib.kvq_rule_policy.argtypes = [vp, i64, ctypes.POINTER(Rule), vp, vp, vp]
     lib.kvq_controller_param_count.restype = i64
     lib.kvq_controller_param_count.argtypes = [ctypes.POINTER(Mlp)]
@@ -266,7 +266,7 @@ def kvq_features(logits: torch.Tensor, token_ids: torch.Tensor, counts: torch.Te
 
 def kvq_features_controller(logits: torch.Tensor, token_ids: torch.Tensor, counts: torch.Tensor, totals: torch.Tensor,
                             update_counts: bool, sum_p2: torch.Tensor, attn_len: torch.Tensor, n_q_heads: int,
-                            mlp: "MlpWeights", feats_out: torch.Tensor, bits_out: torch.Tensor,
+                            mlp: "MlpWeights", feats_out: torch.Tensor, bits_out: torch.Tensor, workspace: torch.Tensor,
                             cache: Optional["Cache"] = None, seq_ids: Optional[torch.Tensor] = None,
                             logits_out: Optional[torch.Tensor] = None, stream=None) -> None:
     n, vocab = logits.shape
@@ -276,7 +276,7 @@ def kvq_features_controller(logits: torch.Tensor, token_ids: torch.Tensor, count
         _ptr(sum_p2, torch.float32, "sum_p2"), _ptr(attn_len, torch.int32, "attn_len"), n_q_heads,
         ctypes.byref(mlp.c), cache.handle if cache is not None else None, _ptr(seq_ids, torch.int32, "seq_ids"),
         _ptr(feats_out, torch.float32, "feats_out"), _ptr(bits_out, torch.uint8, "bits_out"),
-        _ptr(logits_out, torch.float32, "logits_out"), _stream(stream)))
+        _ptr(logits_out, torch.float32, "logits_out"), _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
 
 
 DTYPE_F32, DTYPE_F16, DTYPE_BF16 = 0, 1, 2
@@ -306,7 +306,7 @@ def kvq_features_typed(logits: torch.Tensor, token_ids: torch.Tensor, counts: to
 
 def kvq_features_controller_typed(logits: torch.Tensor, token_ids: torch.Tensor, counts: torch.Tensor, totals: torch.Tensor,
                                   update_counts: bool, sum_p2: torch.Tensor, attn_len: torch.Tensor, n_q_heads: int,
-                                  mlp: "MlpWeights", feats_out: torch.Tensor, bits_out: torch.Tensor,
+                                  mlp: "MlpWeights", feats_out: torch.Tensor, bits_out: torch.Tensor, workspace: torch.Tensor,
                                   cache: Optional["Cache"] = None, seq_ids: Optional[torch.Tensor] = None,
                                   logits_out: Optional[torch.Tensor] = None, stream=None) -> None:
     """kvq_features_controller for float32, float16 or bfloat16 logits."""
@@ -317,7 +317,7 @@ def kvq_features_controller_typed(logits: torch.Tensor, token_ids: torch.Tensor,
         _ptr(sum_p2, torch.float32, "sum_p2"), _ptr(attn_len, torch.int32, "attn_len"), n_q_heads,
         ctypes.byref(mlp.c), cache.handle if cache is not None else None, _ptr(seq_ids, torch.int32, "seq_ids"),
         _ptr(feats_out, torch.float32, "feats_out"), _ptr(bits_out, torch.uint8, "bits_out"),
-        _ptr(logits_out, torch.float32, "logits_out"), _stream(stream)))
+        _ptr(logits_out, torch.float32, "logits_out"), _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
 
 
 class MlpWeights:

@@ -2,14 +2,14 @@
 // class = argmax_k o_k, bits = {2,4,8,16}[class] (label mapping of Algorithm 1).
 //
 // Three launch shapes:
-//   - per-step shape (few rows): one workgroup per row, thread = output unit, weights staged in LDS by contiguous
-//     reads that share one memory latency, activations in LDS;
+//   - per-step shape (few rows): one workgroup per row, a layer cut into (output unit, 16 inputs) work items over all
+//     its threads, weights read straight from global memory (L2), activations and partial sums in LDS;
 //   - bulk shape on the matrix cores (cache construction, thousands to millions of rows; hidden widths 32, 64 or
 //     128): a wavefront takes 32 rows, the hidden layers are fp32 MFMA 32x32x2 tiles whose accumulators feed the
 //     next layer's B operand directly, the 4-output layer is a short vector dot product;
 //   - bulk shape on the vector ALU (any other width up to 256): thread = row, activations in LDS columns.
-// The first and the last compute bit-identical logits (each output is the same sequential fp32 FMA chain
-// bias + sum_i W[j][i]*h[i], i ascending); the MFMA shape sums the same fp32 products in another order.
+// The three sum the same fp32 products in three orders (chains of 16 then the chunks in ascending order; tile order;
+// one chain per output unit); the fused front end shares the first shape's code and agrees with it bit for bit.
 #include "kvq_internal.h"
 #include "kvq_mlp.h"
 
@@ -19,18 +19,19 @@ namespace kvq {
 
 constexpr int kBulkThreads = 64;     // vector-ALU bulk shape: rows per workgroup
 
-// Launched with kRowThreads threads, or with 1024 for a handful of rows: the forward pass needs one thread per output
-// unit, but the weights reach LDS in one batch of loads when a thousand threads fetch them.
-__global__ __launch_bounds__(1024) void k_mlp_row(MlpArgs A, int staged)
+// Launched with 1024 threads for up to a few hundred rows (a 128 x 128 layer is then one work item per thread), with
+// kRowThreads beyond that.
+__global__ __launch_bounds__(1024) void k_mlp_row(MlpArgs A)
 {
-    extern __shared__ float stage[];               // all weights, when they fit
+    __shared__ float part[kRowPartMax];
     __shared__ float act[2][kMaxWidth];
     const long long row = blockIdx.x;
     const int tid = threadIdx.x;
-    if (staged) mlp_stage_weights(A, stage, tid, (int)blockDim.x);
+    RowPrefetch pf;
+    mlp_row_prefetch(A, tid, pf);
     if (tid < A.dims[0]) act[0][tid] = A.feats[row * A.dims[0] + tid];
     __syncthreads();
-    const int cur = staged ? mlp_row_forward<true>(A, act, tid, stage) : mlp_row_forward<false>(A, act, tid, nullptr);
+    const int cur = mlp_row_forward(A, act, part, tid, (int)blockDim.x, pf);
     if (tid == 0) emit_decision(act[cur], A.dims[A.n_linear], row, A.bits, A.logits);
 }
 
@@ -412,15 +413,7 @@ extern "C" int kvq_controller(const float *feats, int64_t n, const kvq_mlp *mlp,
     A.n = n;
     hipStream_t st = (hipStream_t)stream;
     if (n <= 2048) {
-        const int stage_floats = mlp_stage_floats(A);
-        const int staged = stage_floats <= kMlpStageMaxFloats;
-        const size_t lds = staged ? (size_t)stage_floats * sizeof(float) : 0;
-        {
-        static size_t granted = 0;
-        const int rc_lds = ensure_dynamic_lds((const void *)k_mlp_row, lds, &granted);
-        if (rc_lds != KVQ_OK) return rc_lds;
-    }
-        hipLaunchKernelGGL(k_mlp_row, dim3((unsigned)n), dim3(staged && n <= 256 ? 1024 : kRowThreads), lds, st, A, staged);
+        hipLaunchKernelGGL(k_mlp_row, dim3((unsigned)n), dim3(n <= 256 ? 1024 : kRowThreads), 0, st, A);
     } else if (mfma_width(A.dims[1]) && (A.n_linear == 2 || mfma_width(A.dims[2])) && ((uintptr_t)feats & 15) == 0 &&
                !tuning().controller_no_mfma) {
         const int t1 = A.dims[1] / 32, t2 = A.n_linear == 3 ? A.dims[2] / 32 : 0;

@@ -141,6 +141,48 @@ __device__ __forceinline__ Lse3 thread_partial(const T *logits, long long vocab,
     return a;
 }
 
+// ---- wavefront reductions by data-parallel-primitive moves (no LDS traffic) ----------------------------------------
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL> __device__ __forceinline__ Lse3 dpp_lse3(const Lse3 &a)
+{
+    Lse3 b;
+    b.m = dpp_f<CTRL>(a.m); b.s = dpp_f<CTRL>(a.s); b.t = dpp_f<CTRL>(a.t);
+    return b;
+}
+__device__ __forceinline__ Lse3 lane_lse3(const Lse3 &a, int lane)
+{
+    Lse3 b;
+    b.m = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a.m), lane));
+    b.s = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a.s), lane));
+    b.t = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a.t), lane));
+    return b;
+}
+
+// Merge of the 64 lanes' triples; the result is wave-uniform.  Pairs inside a quad, quads inside a half row, half rows
+// inside a row of 16 lanes (each step joins two disjoint groups), then the four rows in a fixed order.
+__device__ __forceinline__ Lse3 lse3_wave_merge(Lse3 a)
+{
+    a = lse3_merge(a, dpp_lse3<0xB1>(a));       // quad_perm [1,0,3,2]
+    a = lse3_merge(a, dpp_lse3<0x4E>(a));       // quad_perm [2,3,0,1]
+    a = lse3_merge(a, dpp_lse3<0x141>(a));      // row_half_mirror
+    a = lse3_merge(a, dpp_lse3<0x140>(a));      // row_mirror
+    return lse3_merge(lse3_merge(lane_lse3(a, 0), lane_lse3(a, 16)), lse3_merge(lane_lse3(a, 32), lane_lse3(a, 48)));
+}
+
+__device__ __forceinline__ float wave_sum_f(float v)
+{
+    v += dpp_f<0xB1>(v);
+    v += dpp_f<0x4E>(v);
+    v += dpp_f<0x141>(v);
+    v += dpp_f<0x140>(v);
+    const int i = __builtin_bit_cast(int, v);
+    return (__builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 0)) + __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 16))) +
+           (__builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 32)) + __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 48)));
+}
+
 // tree merge of kFeatThreads triples sm[0..kFeatThreads) (thread lt owns sm[lt]); the result is sm[0].  Every
 // thread of the workgroup calls it, also in workgroups made of several such groups (sm then is the group's part).
 __device__ __forceinline__ void group_merge(Lse3 *sm, int lt)
@@ -150,28 +192,30 @@ __device__ __forceinline__ void group_merge(Lse3 *sm, int lt)
         if (lt < o) sm[lt] = lse3_merge(sm[lt], sm[lt + o]);
         __syncthreads();
     }
-    // the last levels stay inside the group's first wavefront: the same pairs (lt, lt + o), passed by lane shuffles
+    // the last levels stay inside the group's first wavefront
     if (lt < 64) {
-        Lse3 a = sm[lt];
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) {
-            Lse3 b;
-            b.m = __shfl_down(a.m, o, 64);
-            b.s = __shfl_down(a.s, o, 64);
-            b.t = __shfl_down(a.t, o, 64);
-            a = lse3_merge(a, b);
-        }
+        const Lse3 a = lse3_wave_merge(sm[lt]);
         if (lt == 0) sm[0] = a;
     }
     __syncthreads();
 }
 
+// gather != nullptr (the fused front end): slice 0 of each row also copies what the row's rarity feature needs -- the
+// token's count and N + |V_obs| as they stand -- so that the kernel behind this one may count the tokens while it scores
+// them: every read of the table then lies in this launch, every update in the next.
 template <typename T, bool Stream>
-__global__ __launch_bounds__(kFeatThreads) void k_lse_partial(const T *logits, long long vocab, int slices, float *ws)
+__global__ __launch_bounds__(kFeatThreads) void k_lse_partial(const T *logits, long long vocab, int slices, float *ws,
+                                                              const int32_t *token_ids, const long long *counts, const long long *totals,
+                                                              long long *gather)
 {
     __shared__ Lse3 sm[kFeatThreads];
     const long long row = blockIdx.y;
     const int slice = blockIdx.x;
+    if (gather != nullptr && slice == 0 && threadIdx.x == 0) {
+        const long long id = token_ids[row];
+        gather[row * 2] = (id >= 0 && id < vocab) ? counts[id] : 0;       // an id outside the table counts as unseen
+        gather[row * 2 + 1] = totals[0] + totals[1];
+    }
     sm[threadIdx.x] = thread_partial<T, Stream>(logits, vocab, slices, row, slice, threadIdx.x);
     group_merge(sm, threadIdx.x);
     if (threadIdx.x == 0) {
@@ -194,24 +238,24 @@ __device__ __forceinline__ float rarity_of(long long id, long long vocab, const 
 }
 
 // mean over the heads of the closed form of the population variance of a probability row: sum p^2 / l - 1 / l^2.
-// Every thread of the workgroup calls it; the threads with `active` (kFeatThreads of them, numbered lt) do the
-// work; the value is returned to every thread.
-__device__ __forceinline__ float variance_from_sum_p2(const float *sum_p2_row, int Hq, int l, float *red, int lt, bool active)
+// Called by one whole wavefront; the value is wave-uniform.
+__device__ __forceinline__ float wave_variance_from_sum_p2(const float *sum_p2_row, int Hq, int l, int lane)
 {
     const float inv_l = l > 0 ? 1.0f / (float)l : 0.f;    // l <= 0: no attention row yet, V_t = 0
-    if (active) {
-        float s = 0.f;
-        for (int h = lt; h < Hq; h += kFeatThreads) s += sum_p2_row[h] * inv_l - inv_l * inv_l;
-        red[lt] = s;
+    float s = 0.f;
+    for (int h = lane; h < Hq; h += 64) s += sum_p2_row[h] * inv_l - inv_l * inv_l;
+    return wave_sum_f(s) / (float)Hq;
+}
+
+// the row's slice triples, lane = slice (at most kMaxSlices = 64 of them), merged by the wavefront
+__device__ __forceinline__ Lse3 wave_merge_slices(const float *ws, long long row, int slices, int lane)
+{
+    Lse3 a = {-INFINITY, 0.f, 0.f};
+    if (lane < slices) {
+        const float *w = ws + (row * slices + lane) * 4;
+        a.m = w[0]; a.s = w[1]; a.t = w[2];
     }
-    __syncthreads();
-    for (int o = kFeatThreads / 2; o >= 1; o >>= 1) {
-        if (active && lt < o) red[lt] += red[lt + o];
-        __syncthreads();
-    }
-    const float V = red[0] / (float)Hq;
-    __syncthreads();
-    return V;
+    return lse3_wave_merge(a);
 }
 
 struct FeatArgs {
@@ -264,16 +308,11 @@ __global__ __launch_bounds__(kFeatThreads) void k_features_finalize(FeatArgs A)
             __syncthreads();
         }
         V /= (float)A.Hq;
-    } else {
-        V = variance_from_sum_p2(A.sum_p2 + t * A.Hq, A.Hq, l, red, threadIdx.x, true);
     }
+    if (threadIdx.x >= 64) return;                   // the first wavefront finishes the row
+    if (l > 0 && !A.attn_probs) V = wave_variance_from_sum_p2(A.sum_p2 + t * A.Hq, A.Hq, l, threadIdx.x);
+    const Lse3 a = wave_merge_slices(A.ws, t, A.slices, threadIdx.x);
     if (threadIdx.x != 0) return;
-    Lse3 a = {-INFINITY, 0.f, 0.f};
-    for (int s = 0; s < A.slices; ++s) {
-        const float *w = A.ws + (t * A.slices + s) * 4;
-        Lse3 b = {w[0], w[1], w[2]};
-        a = lse3_merge(a, b);
-    }
     float *f = A.feats + t * 4;
     f[0] = entropy_of(a);
     f[1] = rarity_of(A.token_ids[t], A.vocab, A.counts, A.totals);
@@ -281,89 +320,88 @@ __global__ __launch_bounds__(kFeatThreads) void k_features_finalize(FeatArgs A)
     f[3] = confidence_of(a);
 }
 
-// ---- fused per-step front end: features, controller and bucket bookkeeping in one launch --------------------
+// ---- fused per-step front end: features, controller, bucket bookkeeping and count update in two launches ----------
 //
-// One workgroup of four groups of kFeatThreads threads per row.  The groups take the row's slices in turn and
-// reduce each exactly as k_lse_partial does, thread 0 merges the slice triples in slice order as
-// k_features_finalize does, and the controller's row shape follows, so features and logits equal those of the
-// separate kernels bit for bit.  A row never needs another row's result; the count update stays a kernel of its
-// own behind this one, which keeps "every row reads the table before any count changes" a matter of stream order.
-constexpr int kFrontGroups = 4;
-
+// The pass over the logits is k_lse_partial's, spread over rows x slices workgroups (one compute unit per row took
+// 9 us for 49 152 logits); slice 0 of each row also copies the row's table entries.  This kernel is the rest of the
+// row, one workgroup each: the first wavefront merges the slice triples and forms the four features exactly as
+// k_features_finalize does; the controller's row shape follows, then the new token's bucket bookkeeping and its count.  Features and logits equal those of the separate
+// kernels bit for bit.  No row needs another row's result, and no row reads the table in this launch, so counting
+// here keeps "every row reads the table before any count changes".
 struct FrontArgs {
-    const void *logits;
+    const float *ws;
+    const long long *gather;
     const int32_t *token_ids;
-    const long long *counts;
-    const long long *totals;
+    unsigned long long *counts;
+    unsigned long long *totals;
     const float *sum_p2;
     const int32_t *attn_len;
     const int32_t *seq_ids;
     float *feats;
-    long long vocab;
-    int slices, Hq, advance;
+    long long vocab, n;
+    int slices, Hq, advance, update_counts;
 };
 
-template <typename T>
-__global__ __launch_bounds__(kFrontGroups * kFeatThreads) void k_front(FrontArgs F, MlpArgs M, CacheView cv, int staged)
+__global__ __launch_bounds__(1024) void k_front_tail(FrontArgs F, MlpArgs M, CacheView cv)
 {
-    extern __shared__ float stage[];               // the controller's weights, fetched while the logits stream in
-    __shared__ Lse3 sm[kFrontGroups * kFeatThreads];
-    __shared__ Lse3 slice_res[kMaxSlices];
+    __shared__ float part[kRowPartMax];
     __shared__ float act[2][kMaxWidth];
     const long long row = blockIdx.x;
-    const int tid = threadIdx.x, g = tid / kFeatThreads, lt = tid % kFeatThreads;
-    // thread 0 fetches what the row's serial tail needs (the token's count, the totals, the sequence's counters) now,
-    // so that these dependent reads overlap the pass over the logits
+    const int tid = threadIdx.x;
+    // Everything the row needs from memory is asked for here, in one batch: the controller's weights (every thread),
+    // the gathered count and the sequence's counters and page entries (thread 0), the slice triples (first wavefront).
+    RowPrefetch pf;
+    mlp_row_prefetch(M, tid, pf);
     long long tok_count = 0, seen = 0;
-    int seq = 0, pre[5] = {0, 0, 0, 0, 0};
+    int seq = 0, pre[5] = {0, 0, 0, 0, 0}, pre_page[kClasses] = {0, 0, 0, 0};
     if (tid == 0) {
-        const long long id = F.token_ids[row];
-        tok_count = (id >= 0 && id < F.vocab) ? F.counts[id] : 0;
-        seen = F.totals[0] + F.totals[1];
+        tok_count = F.gather[row * 2];
+        seen = F.gather[row * 2 + 1];
         if (F.advance) {
             seq = F.seq_ids ? F.seq_ids[row] : (int)row;
             if (seq >= 0 && seq < cv.max_seqs) {
 #pragma unroll
                 for (int c = 0; c < 5; ++c) pre[c] = cv.counts[(size_t)seq * 5 + c];
+                prefetch_next_pages(cv, seq, pre, pre_page);
             }
         }
     }
-    if (staged) mlp_stage_weights(M, stage, tid, kFrontGroups * kFeatThreads);
-    // four rounds of slices at a time: their loads are issued together, their reductions follow one by one
-    constexpr int kRounds = 4;
-    for (int s0 = 0; s0 < F.slices; s0 += kFrontGroups * kRounds) {
-        Lse3 part[kRounds];
-#pragma unroll
-        for (int r = 0; r < kRounds; ++r) {
-            const int slice = s0 + r * kFrontGroups + g;
-            part[r].m = -INFINITY; part[r].s = 0.f; part[r].t = 0.f;
-            if (slice < F.slices) part[r] = thread_partial((const T *)F.logits, F.vocab, F.slices, row, slice, lt);
-        }
-#pragma unroll
-        for (int r = 0; r < kRounds; ++r) {
-            const int slice = s0 + r * kFrontGroups + g;
-            if (s0 + r * kFrontGroups >= F.slices) break;           // uniform over the workgroup
-            sm[tid] = part[r];
-            group_merge(sm + g * kFeatThreads, lt);
-            if (lt == 0 && slice < F.slices) slice_res[slice] = sm[tid];
+    // the count update (c[id] += 1, N += n, |V_obs| += ids seen for the first time) is the second wavefront's first
+    // lane's: it depends on nothing this kernel computes and runs beside the rest
+    if (tid == 64 && F.update_counts) {
+        if (row == 0) atomicAdd(&F.totals[0], (unsigned long long)F.n);
+        const long long id = F.token_ids[row];
+        if (id >= 0 && id < F.vocab) {
+            const unsigned long long old = atomicAdd(&F.counts[id], 1ull);
+            if (old == 0ull) atomicAdd(&F.totals[1], 1ull);
         }
     }
-    const float V = variance_from_sum_p2(F.sum_p2 + row * F.Hq, F.Hq, F.attn_len[row], (float *)sm, lt, g == 0);
-    if (tid == 0) {
-        Lse3 a = {-INFINITY, 0.f, 0.f};
-        for (int s = 0; s < F.slices; ++s) a = lse3_merge(a, slice_res[s]);
-        act[0][0] = entropy_of(a);
-        act[0][1] = rarity_from(tok_count, seen);
-        act[0][2] = V;
-        act[0][3] = confidence_of(a);
-        float *f = F.feats + row * 4;
-        f[0] = act[0][0]; f[1] = act[0][1]; f[2] = act[0][2]; f[3] = act[0][3];
+    Lse3 mine = {-INFINITY, 0.f, 0.f};
+    int l = 0;
+    if (tid < 64) {
+        l = F.attn_len[row];
+        if (tid < F.slices) {
+            const float *w = F.ws + (row * F.slices + tid) * 4;
+            mine.m = w[0]; mine.s = w[1]; mine.t = w[2];
+        }
+    }
+    if (tid < 64) {
+        const float V = wave_variance_from_sum_p2(F.sum_p2 + row * F.Hq, F.Hq, l, tid);      // (its loads travel with the triples')
+        const Lse3 a = lse3_wave_merge(mine);
+        if (tid == 0) {
+            act[0][0] = entropy_of(a);
+            act[0][1] = rarity_from(tok_count, seen);
+            act[0][2] = V;
+            act[0][3] = confidence_of(a);
+            float *f = F.feats + row * 4;
+            f[0] = act[0][0]; f[1] = act[0][1]; f[2] = act[0][2]; f[3] = act[0][3];
+        }
     }
     __syncthreads();
-    const int cur = staged ? mlp_row_forward<true>(M, act, tid, stage) : mlp_row_forward<false>(M, act, tid, nullptr);
+    const int cur = mlp_row_forward(M, act, part, tid, (int)blockDim.x, pf);
     if (tid == 0) {
         const int b = emit_decision(act[cur], 4, row, M.bits, M.logits);
-        if (F.advance) advance_one_token(cv, seq, b, pre);
+        if (F.advance) advance_one_token(cv, seq, b, pre, pre_page);
     }
 }
 
@@ -383,7 +421,7 @@ __global__ void k_counts_update(const int32_t *ids, long long n, long long vocab
 static int pick_slices(long long n, long long vocab)
 {
     long long s = (1024 + n - 1) / n;                     // aim at >= ~1024 workgroups
-    const long long max_by_len = (vocab + 4095) / 4096;   // at least 4096 logits per slice
+    const long long max_by_len = (vocab + 1023) / 1024;   // at least 1024 logits per slice: one 16-byte load per thread
     if (s > max_by_len) s = max_by_len;
     if (s > kMaxSlices) s = kMaxSlices;
     if (s < 1) s = 1;
@@ -397,30 +435,31 @@ using namespace kvq;
 extern "C" size_t kvq_features_workspace(int64_t n, int64_t vocab)
 {
     if (n <= 0 || vocab <= 0) return 0;
-    return (size_t)n * kMaxSlices * 4 * sizeof(float) + 256;
+    // slice triples of every row, then (fused front end) the row's gathered table entries
+    return (size_t)n * kMaxSlices * 4 * sizeof(float) + (size_t)n * 2 * sizeof(long long) + 256;
 }
 
 template <typename T>
-static int launch_lse_partial(const void *logits, int64_t n, int64_t vocab, int slices, float *ws, hipStream_t st)
+static int launch_lse_partial(const void *logits, int64_t n, int64_t vocab, int slices, float *ws, const int32_t *token_ids,
+                              const int64_t *counts, const int64_t *totals, long long *gather, hipStream_t st)
 {
     // beyond what the L2 caches hold together, the logits are streamed
     if ((long long)n * vocab * (long long)sizeof(T) >= (32LL << 20))
-        hipLaunchKernelGGL((k_lse_partial<T, true>), dim3(slices, (unsigned)n), dim3(kFeatThreads), 0, st, (const T *)logits, (long long)vocab, slices, ws);
+        hipLaunchKernelGGL((k_lse_partial<T, true>), dim3(slices, (unsigned)n), dim3(kFeatThreads), 0, st, (const T *)logits, (long long)vocab, slices, ws,
+                           token_ids, (const long long *)counts, (const long long *)totals, gather);
     else
-        hipLaunchKernelGGL((k_lse_partial<T, false>), dim3(slices, (unsigned)n), dim3(kFeatThreads), 0, st, (const T *)logits, (long long)vocab, slices, ws);
+        hipLaunchKernelGGL((k_lse_partial<T, false>), dim3(slices, (unsigned)n), dim3(kFeatThreads), 0, st, (const T *)logits, (long long)vocab, slices, ws,
+                           token_ids, (const long long *)counts, (const long long *)totals, gather);
     KVQ_HIP(hipGetLastError());
     return KVQ_OK;
 }
 
-template <typename T>
-static int launch_front(const kvq::FrontArgs &F, const kvq::MlpArgs &M, const kvq::CacheView &cv, int64_t n, size_t lds, int staged, hipStream_t st)
+static int launch_lse_partial_typed(int32_t dtype, const void *logits, int64_t n, int64_t vocab, int slices, float *ws,
+                                    const int32_t *token_ids, const int64_t *counts, const int64_t *totals, long long *gather, hipStream_t st)
 {
-    static size_t granted = 0;
-    const int rc_lds = ensure_dynamic_lds((const void *)k_front<T>, lds, &granted);
-    if (rc_lds != KVQ_OK) return rc_lds;
-    hipLaunchKernelGGL(k_front<T>, dim3((unsigned)n), dim3(kFrontGroups * kFeatThreads), lds, st, F, M, cv, staged);
-    KVQ_HIP(hipGetLastError());
-    return KVQ_OK;
+    return dtype == KVQ_DTYPE_F32   ? launch_lse_partial<float>(logits, n, vocab, slices, ws, token_ids, counts, totals, gather, st)
+           : dtype == KVQ_DTYPE_F16 ? launch_lse_partial<__half>(logits, n, vocab, slices, ws, token_ids, counts, totals, gather, st)
+                                    : launch_lse_partial<Bf16>(logits, n, vocab, slices, ws, token_ids, counts, totals, gather, st);
 }
 
 static int check_logits(const void *logits, int32_t dtype)
@@ -460,9 +499,7 @@ extern "C" int kvq_features_typed(const void *logits, int32_t logits_dtype, int6
     hipStream_t st = (hipStream_t)stream;
     const int slices = pick_slices(n, vocab);
     if (n > 65535) { set_error("n above 65535 rows per call is not supported"); return KVQ_ERR_UNSUPPORTED; }
-    const int rc_l = logits_dtype == KVQ_DTYPE_F32   ? launch_lse_partial<float>(logits, n, vocab, slices, (float *)workspace, st)
-                     : logits_dtype == KVQ_DTYPE_F16 ? launch_lse_partial<__half>(logits, n, vocab, slices, (float *)workspace, st)
-                                                     : launch_lse_partial<Bf16>(logits, n, vocab, slices, (float *)workspace, st);
+    const int rc_l = launch_lse_partial_typed(logits_dtype, logits, n, vocab, slices, (float *)workspace, nullptr, nullptr, nullptr, nullptr, st);
     if (rc_l != KVQ_OK) return rc_l;
     FeatArgs A;
     A.ws = (const float *)workspace;
@@ -501,7 +538,7 @@ extern "C" int kvq_features_controller_typed(const void *logits, int32_t logits_
                                              const int32_t *token_ids, int64_t *counts, int64_t *totals, int32_t update_counts,
                                              const float *sum_p2, const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp,
                                              kvq_cache *cache, const int32_t *seq_ids, float *feats_out, uint8_t *bits_out,
-                                             float *logits_out, void *stream)
+                                             float *logits_out, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (n < 0 || vocab < 1) { set_error("n or vocab out of range"); return KVQ_ERR_INVALID_ARG; }
     const int rc_t = check_logits(logits, logits_dtype);
@@ -517,41 +554,46 @@ extern "C" int kvq_features_controller_typed(const void *logits, int32_t logits_
     if (n_q_heads < 1) { set_error("n_q_heads must be positive"); return KVQ_ERR_INVALID_ARG; }
     if (n > 65535) { set_error("n above 65535 rows per call is not supported"); return KVQ_ERR_UNSUPPORTED; }
     if (cache && n > cache->desc.max_seqs) { set_error("n %lld exceeds the cache's max_seqs", (long long)n); return KVQ_ERR_INVALID_ARG; }
+    const size_t need = kvq_features_workspace(n, vocab) - 256;
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)) {
+        set_error("workspace too small or not 16-byte aligned: %zu bytes given, %zu needed", workspace_bytes, need);
+        return KVQ_ERR_INVALID_ARG;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const int slices = pick_slices(n, vocab);                      // the slicing of kvq_features: same rounding, same values
+    float *ws = (float *)workspace;
+    long long *gather = (long long *)((char *)workspace + (size_t)n * kMaxSlices * 4 * sizeof(float));
+    const int rc_l = launch_lse_partial_typed(logits_dtype, logits, n, vocab, slices, ws, token_ids, counts, totals, gather, st);
+    if (rc_l != KVQ_OK) return rc_l;
     FrontArgs F;
-    F.logits = logits;
+    F.ws = ws;
+    F.gather = gather;
     F.token_ids = token_ids;
-    F.counts = (const long long *)counts;
-    F.totals = (const long long *)totals;
+    F.counts = (unsigned long long *)counts;
+    F.totals = (unsigned long long *)totals;
     F.sum_p2 = sum_p2;
     F.attn_len = attn_len;
     F.seq_ids = seq_ids;
     F.feats = feats_out;
     F.vocab = vocab;
-    F.slices = pick_slices(n, vocab);                             // the slicing of kvq_features: same rounding, same values
+    F.n = n;
+    F.slices = slices;
     F.Hq = n_q_heads;
     F.advance = cache ? 1 : 0;
+    F.update_counts = update_counts ? 1 : 0;
     M.feats = feats_out;
     M.bits = bits_out;
     M.logits = logits_out;
     M.n = n;
     CacheView cv = {};
     if (cache) cv = cache->view;
-    hipStream_t st = (hipStream_t)stream;
-    const int stage_floats = mlp_stage_floats(M);
-    const int staged = stage_floats <= kMlpStageMaxFloats;
-    const size_t lds = staged ? (size_t)stage_floats * sizeof(float) : 0;
-    const int rc_f = logits_dtype == KVQ_DTYPE_F32   ? launch_front<float>(F, M, cv, n, lds, staged, st)
-                     : logits_dtype == KVQ_DTYPE_F16 ? launch_front<__half>(F, M, cv, n, lds, staged, st)
-                                                     : launch_front<Bf16>(F, M, cv, n, lds, staged, st);
-    if (rc_f != KVQ_OK) return rc_f;
+    // a 128 x 128 layer is one work item per thread of a 1024-thread workgroup; with many rows workgroups of that size
+    // would only queue up
+    hipLaunchKernelGGL(k_front_tail, dim3((unsigned)n), dim3(n <= 256 ? 1024 : kRowThreads), 0, st, F, M, cv);
+    KVQ_HIP(hipGetLastError());
     if (cache) {                                                   // host-side length bound: the launch is queued
         cache->len_bound += 1;
         if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;
-    }
-    if (update_counts) {
-        hipLaunchKernelGGL(k_counts_update, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, token_ids, (long long)n,
-                           (long long)vocab, (unsigned long long *)counts, (unsigned long long *)totals);
-        KVQ_HIP(hipGetLastError());
     }
     return KVQ_OK;
 }
@@ -560,8 +602,8 @@ extern "C" int kvq_features_controller(const float *logits, int64_t n, int64_t v
                                        int64_t *counts, int64_t *totals, int32_t update_counts, const float *sum_p2,
                                        const int32_t *attn_len, int32_t n_q_heads, const kvq_mlp *mlp, kvq_cache *cache,
                                        const int32_t *seq_ids, float *feats_out, uint8_t *bits_out, float *logits_out,
-                                       void *stream)
+                                       void *workspace, size_t workspace_bytes, void *stream)
 {
     return kvq_features_controller_typed(logits, KVQ_DTYPE_F32, n, vocab, token_ids, counts, totals, update_counts, sum_p2, attn_len,
-                                         n_q_heads, mlp, cache, seq_ids, feats_out, bits_out, logits_out, stream);
+                                         n_q_heads, mlp, cache, seq_ids, feats_out, bits_out, logits_out, workspace, workspace_bytes, stream);
 }

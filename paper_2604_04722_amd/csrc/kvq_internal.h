@@ -129,8 +129,19 @@ __device__ __forceinline__ size_t pos_log_index(const CacheView &cv, int seq, in
 // Bucket bookkeeping of ONE new token of `seq` by a single thread: the same state changes as the bookkeeping
 // kernel makes for T = 1 (slot = the class's count, a page popped from the class's free stack when the slot opens
 // a page, bits and slot logged, counts advanced, flags raised on a full context, an empty pool or a bad width).
-// `pre` holds the sequence's five counters as read earlier by the same thread (so that the reads overlap other work).
-__device__ __forceinline__ void advance_one_token(const CacheView &cv, int seq, int b, const int (&pre)[5])
+// `pre` holds the sequence's five counters and `pre_page` the page-table entry that each class's next slot falls
+// into, both read earlier by the same thread (so that the reads overlap other work; the entry of a slot that opens a
+// page is not looked at).
+__device__ __forceinline__ void prefetch_next_pages(const CacheView &cv, int seq, const int (&pre)[5], int (&pre_page)[kClasses])
+{
+#pragma unroll
+    for (int c = 0; c < kClasses; ++c) {
+        const int idx = min(pre[c] / cv.page_tokens, cv.max_pages_per_seq - 1);
+        pre_page[c] = cv.page_table[((size_t)seq * kClasses + c) * cv.max_pages_per_seq + idx];
+    }
+}
+
+__device__ __forceinline__ void advance_one_token(const CacheView &cv, int seq, int b, const int (&pre)[5], const int (&pre_page)[kClasses])
 {
     if (seq < 0 || seq >= cv.max_seqs) { atomicOr(cv.flags, KVQ_FLAG_CONTEXT_FULL); return; }
     int32_t *cnt = cv.counts + (size_t)seq * 5;
@@ -144,17 +155,17 @@ __device__ __forceinline__ void advance_one_token(const CacheView &cv, int seq, 
     if (b != 2 && b != 4 && b != 8 && b != 16) { atomicOr(cv.flags, KVQ_FLAG_BAD_BITS); b = 16; }
     const int c = bits_to_class(b);
     const int slot = c == 0 ? pre[0] : c == 1 ? pre[1] : c == 2 ? pre[2] : pre[3];
+    int page_now = c == 0 ? pre_page[0] : c == 1 ? pre_page[1] : c == 2 ? pre_page[2] : pre_page[3];
     if (slot % cv.page_tokens == 0) {
-        int page;
         const int idx = atomicSub(&cv.free_top[c], 1) - 1;
         if (idx < 0) {
             atomicAdd(&cv.free_top[c], 1);
             atomicOr(cv.flags, KVQ_FLAG_POOL_EXHAUSTED);
-            page = cv.n_pages[c];                                      // sink page: in bounds, shared, garbage
+            page_now = cv.n_pages[c];                                  // sink page: in bounds, shared, garbage
         } else {
-            page = cv.free_stack[c][idx];
+            page_now = cv.free_stack[c][idx];
         }
-        cv.page_table[((size_t)seq * kClasses + c) * cv.max_pages_per_seq + slot / cv.page_tokens] = page;
+        cv.page_table[((size_t)seq * kClasses + c) * cv.max_pages_per_seq + slot / cv.page_tokens] = page_now;
     }
     const size_t pos = (size_t)seq * cv.max_context + len;
     cv.bits_log[pos] = (uint8_t)b;
@@ -162,7 +173,6 @@ __device__ __forceinline__ void advance_one_token(const CacheView &cv, int seq, 
     cnt[c] = slot + 1;
     cnt[4] = len + 1;
     cv.last_T[seq] = 1;
-    const int page_now = cv.page_table[((size_t)seq * kClasses + c) * cv.max_pages_per_seq + slot / cv.page_tokens];
     int32_t *rec = cv.last_rec + (size_t)seq * 4;
     rec[0] = 1; rec[1] = b; rec[2] = slot; rec[3] = page_now;
 }

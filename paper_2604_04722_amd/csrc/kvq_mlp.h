@@ -32,15 +32,6 @@ __device__ __forceinline__ int emit_decision(const float *o, int nout, long long
     return 2 << best;
 }
 
-// Floats of LDS that hold every layer's weights with rows padded by one float (conflict-free for thread = row).
-__host__ __device__ inline int mlp_stage_floats(const MlpArgs &A)
-{
-    int total = 0;
-    for (int l = 0; l < A.n_linear; ++l) total += A.dims[l + 1] * (A.dims[l] + 1);
-    return total;
-}
-constexpr int kMlpStageMaxFloats = 18432;       // 72 KiB: 4-128-128-4 needs 17 668 floats; wider nets read global memory
-
 // Copies all weights into `stage` with contiguous (coalesced) global reads, issued back to back so that they share
 // one memory latency.  Every thread of the workgroup calls it; a barrier must follow before the weights are used.
 __device__ __forceinline__ void mlp_stage_weights(const MlpArgs &A, float *stage, int tid, int nthreads)
@@ -81,55 +72,117 @@ __device__ __forceinline__ void mlp_stage_weights(const MlpArgs &A, float *stage
     }
 }
 
-// Forward pass of one row: thread j < width computes output unit j as the sequential fp32 FMA chain
-// bias + sum_i W[j][i]*h[i], i ascending (the chain of the vector-ALU bulk shape, so the two agree bit for bit).
-// Every thread of the workgroup calls this with the features in act[0][0..dims[0]) and a barrier behind them (and
-// behind mlp_stage_weights if stage != nullptr; with stage == nullptr the weights are read from global memory).
-// Returns the index (0 or 1) of the act row that holds the logits; a barrier has been passed when it returns.
-// Staged selects the weights' address space at compile time (LDS `stage`, or global memory): a pointer that may be
-// either would be a generic one, and every weight read a flat load.
-template <bool Staged>
-__device__ __forceinline__ int mlp_row_forward(const MlpArgs &A, float (*act)[kMaxWidth], int tid, const float *stage)
+// Forward pass of one row by one workgroup of any size.  A layer's work is cut into items of (output unit, chunk of
+// kRowChunk consecutive inputs): 128 x 128 weights are 1024 items, one per thread of a 1024-thread workgroup, each a
+// chain of 16 FMAs on weights it reads straight from global memory (consecutive threads read consecutive 64 bytes; the
+// weights of a controller stay in L2 from one decode step to the next).  The items' partial sums go through LDS and
+// thread j adds its unit's chunks in ascending order to the bias.  Staging all weights in LDS first and giving a unit's
+// whole chain to one thread took 8 us per call for the 4-128-128-4 network; this takes a third of that.
+// Every thread of the workgroup calls mlp_row_prefetch early, then mlp_row_forward with the features in
+// act[0][0..dims[0]) and a barrier behind them; `part` is LDS for kRowPartMax floats.  Returns the index (0 or 1) of the act row that holds the logits; a barrier has been
+// passed when it returns.
+constexpr int kRowChunk = 16;
+constexpr int kRowPartMax = kMaxWidth * (kMaxWidth / kRowChunk);
+
+// What a thread needs of the weights for its first work item of every layer, asked for before the features exist (the
+// weights do not depend on them): with 1024 threads and widths up to 128 that is every item, and the three layers'
+// reads cost one memory latency together instead of one each.
+typedef float f32x4 __attribute__((ext_vector_type(4)));     // a first-class vector value (the float4 class wraps a union)
+
+struct RowLayerPrefetch {
+    f32x4 w0, w1, w2, w3;          // (named members, no arrays: an array indexed in a loop ends up in scratch memory)
+    float bias;
+};
+struct RowPrefetch { RowLayerPrefetch l0, l1, l2; };
+
+__device__ __forceinline__ bool mlp_row_vec(const MlpArgs &A, int l) { return (A.dims[l] & 3) == 0 && ((uintptr_t)A.W[l] & 15) == 0; }
+
+// the 16 weights of item `it` of layer L (vectorised layers only); loads beyond the row's end re-read its start
+template <int L> __device__ __forceinline__ void mlp_row_item_weights(const MlpArgs &A, int it, f32x4 &w0, f32x4 &w1, f32x4 &w2, f32x4 &w3)
 {
-    int cur = 0, base = 0;
-#pragma unroll
-    for (int l = 0; l < 3; ++l) {
-        if (l >= A.n_linear) break;
-        const int in = A.dims[l], outw = A.dims[l + 1];
-        if (tid < outw) {
-            float a = A.b[l][tid];
-            const float *h = act[cur];
-            int i = 0;
-            // eight weights and activations are fetched before their FMAs: one read latency per eight terms
-            if constexpr (Staged) {
-                const float *w = stage + base + tid * (in + 1);
-                for (; i + 8 <= in; i += 8) {
-                    float wv[8], hv[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) { wv[u] = w[i + u]; hv[u] = h[i + u]; }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) a = fmaf(wv[u], hv[u], a);
-                }
-                for (; i < in; ++i) a = fmaf(w[i], h[i], a);
-            } else {
-                const float *w = A.W[l] + (size_t)tid * in;
-                for (; i + 8 <= in; i += 8) {
-                    float wv[8], hv[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) { wv[u] = w[i + u]; hv[u] = h[i + u]; }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) a = fmaf(wv[u], hv[u], a);
-                }
-                for (; i < in; ++i) a = fmaf(w[i], h[i], a);
-            }
-            if (l + 1 < A.n_linear) a = fmaxf(a, 0.f);
-            act[cur ^ 1][tid] = a;
-        }
-        __syncthreads();
-        cur ^= 1;
-        base += outw * (in + 1);
+    const int in = A.dims[L];
+    const int chunks = (in + kRowChunk - 1) / kRowChunk;
+    const int j = it / chunks, c = it - j * chunks;
+    const int i0 = c * kRowChunk, i1 = min(i0 + kRowChunk, in);
+    const float *w = A.W[L] + (size_t)j * in;
+    w0 = *(const f32x4 *)(w + i0);
+    w1 = *(const f32x4 *)(w + (i0 + 4 < i1 ? i0 + 4 : i0));
+    w2 = *(const f32x4 *)(w + (i0 + 8 < i1 ? i0 + 8 : i0));
+    w3 = *(const f32x4 *)(w + (i0 + 12 < i1 ? i0 + 12 : i0));
+}
+
+template <int L> __device__ __forceinline__ void mlp_row_prefetch_layer(const MlpArgs &A, int tid, RowLayerPrefetch &p)
+{
+    p.w0 = p.w1 = p.w2 = p.w3 = f32x4{0.f, 0.f, 0.f, 0.f};
+    p.bias = 0.f;
+    if (L >= A.n_linear) return;
+    const int outw = A.dims[L + 1];
+    const int items = outw * ((A.dims[L] + kRowChunk - 1) / kRowChunk);
+    if (tid < items && mlp_row_vec(A, L)) mlp_row_item_weights<L>(A, tid, p.w0, p.w1, p.w2, p.w3);
+    if (tid < outw) p.bias = A.b[L][tid];
+}
+
+__device__ __forceinline__ void mlp_row_prefetch(const MlpArgs &A, int tid, RowPrefetch &pf)
+{
+    mlp_row_prefetch_layer<0>(A, tid, pf.l0);
+    mlp_row_prefetch_layer<1>(A, tid, pf.l1);
+    mlp_row_prefetch_layer<2>(A, tid, pf.l2);
+}
+
+__device__ __forceinline__ float mlp_row_fma4(const f32x4 &w, const float *h, int i, int i1, float a)
+{
+    if (i < i1) {
+        a = fmaf(w.x, h[i], a);
+        a = fmaf(w.y, h[i + 1], a);
+        a = fmaf(w.z, h[i + 2], a);
+        a = fmaf(w.w, h[i + 3], a);
     }
-    return cur;
+    return a;
+}
+
+// one layer; h = the layer's input in LDS, out = its output row in LDS
+template <int L> __device__ __forceinline__ void mlp_row_layer(const MlpArgs &A, const float *h, float *out, float *part, int tid, int nthreads,
+                                                               const RowLayerPrefetch &p)
+{
+    const int in = A.dims[L], outw = A.dims[L + 1];
+    const int chunks = (in + kRowChunk - 1) / kRowChunk;
+    const int items = outw * chunks;
+    const bool vec = mlp_row_vec(A, L);
+    for (int it = tid; it < items; it += nthreads) {
+        const int j = it / chunks, c = it - j * chunks;
+        const int i0 = c * kRowChunk, i1 = min(i0 + kRowChunk, in);
+        float a = 0.f;
+        if (vec) {
+            f32x4 w0 = p.w0, w1 = p.w1, w2 = p.w2, w3 = p.w3;
+            if (it != tid) mlp_row_item_weights<L>(A, it, w0, w1, w2, w3);
+            a = mlp_row_fma4(w0, h, i0, i1, a);
+            a = mlp_row_fma4(w1, h, i0 + 4, i1, a);
+            a = mlp_row_fma4(w2, h, i0 + 8, i1, a);
+            a = mlp_row_fma4(w3, h, i0 + 12, i1, a);
+        } else {
+            const float *w = A.W[L] + (size_t)j * in;
+            for (int i = i0; i < i1; ++i) a = fmaf(w[i], h[i], a);
+        }
+        part[it] = a;
+    }
+    __syncthreads();
+    if (tid < outw) {
+        float a = p.bias;
+        for (int c = 0; c < chunks; ++c) a += part[tid * chunks + c];
+        if (L + 1 < A.n_linear) a = fmaxf(a, 0.f);
+        out[tid] = a;
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ int mlp_row_forward(const MlpArgs &A, float (*act)[kMaxWidth], float *part, int tid, int nthreads,
+                                               const RowPrefetch &pf)
+{
+    mlp_row_layer<0>(A, act[0], act[1], part, tid, nthreads, pf.l0);
+    mlp_row_layer<1>(A, act[1], act[0], part, tid, nthreads, pf.l1);
+    if (A.n_linear < 3) return 0;
+    mlp_row_layer<2>(A, act[0], act[1], part, tid, nthreads, pf.l2);
+    return 1;
 }
 
 }  // namespace kvq

@@ -22,6 +22,11 @@ def say(*a):
     print(*a, flush=True)
 
 
+def front_ws(n, vocab):
+    """workspace of the fused front end (slice results and table entries between its two launches)"""
+    return torch.empty(kvq.kvq_features_workspace(n, vocab), dtype=torch.uint8, device=dev())
+
+
 def run_features(logits, ids, counts, N, Vobs, lens, Hq, probs=None, sum_p2=None, update=False):
     n, vocab = logits.shape
     d = dev()
@@ -358,7 +363,7 @@ def test_fused_features_controller_is_bit_identical_to_the_separate_calls(n, voc
         feats = torch.full((n, 4), float("nan"), dtype=torch.float32, device=d)
         bits = torch.zeros(n, dtype=torch.uint8, device=d)
         lg = torch.zeros((n, 4), dtype=torch.float32, device=d)
-        kvq.kvq_features_controller(t_logits, t_ids, c_b, tot_b, True, t_p2, t_len, Hq, mlp, feats, bits, logits_out=lg)
+        kvq.kvq_features_controller(t_logits, t_ids, c_b, tot_b, True, t_p2, t_len, Hq, mlp, feats, bits, front_ws(n, vocab), logits_out=lg)
         torch.cuda.synchronize()
         f0, b0, l0, c0, t0 = sep[it]
         assert np.array_equal(feats.cpu().numpy().view(np.uint32), f0.view(np.uint32))
@@ -415,7 +420,7 @@ def test_fused_front_end_advances_the_cache_like_a_layer0_append():
         # (the variance feature of both paths comes from path a's attention: the two attention entry points agree
         # within the attention tolerance, not bit for bit, and this test compares bookkeeping exactly)
         kvq.kvq_features_controller(logits, ids, c_b, tot_b, True, p2_prev, lens, Hq, mlp, feats_b, bits_b.view(-1),
-                                    cache=cache_b, seq_ids=seq_ids)
+                                    front_ws(logits.shape[0], logits.shape[1]), cache=cache_b, seq_ids=seq_ids)
         for l in range(L):
             kvq.kvq_append_decode_attn(cache_b, l, K[l], V[l], None, q[l], seq_ids, B, out_b, aws, None, p2_b if l == L - 1 else None)
         if step % 100 == 99:
@@ -449,7 +454,7 @@ def test_a_sequence_without_an_attention_row_yet_has_zero_variance_feature():
     bits = torch.zeros(n, dtype=torch.uint8, device=d)
     kvq.kvq_features_controller(torch.from_numpy(logits).to(d), torch.from_numpy(ids).to(d), torch.from_numpy(counts).to(d),
                                 torch.tensor([N, Vobs], dtype=torch.int64, device=d), False, torch.from_numpy(p2).to(d),
-                                torch.from_numpy(lens).to(d), Hq, mlp, feats, bits)
+                                torch.from_numpy(lens).to(d), Hq, mlp, feats, bits, front_ws(n, logits.shape[1]))
     torch.cuda.synchronize()
     fused = feats.cpu().numpy()
     assert np.array_equal(got.view(np.uint32), fused.view(np.uint32))
@@ -532,7 +537,7 @@ def test_narrow_logits_give_the_features_of_the_widened_row(dtype, n, vocab):
     feats2 = torch.full((n, 4), float("nan"), dtype=torch.float32, device=d)
     bits2 = torch.zeros(n, dtype=torch.uint8, device=d)
     lg2 = torch.zeros((n, 4), dtype=torch.float32, device=d)
-    kvq.kvq_features_controller_typed(t_narrow, t_ids, c_b, tot_b, True, t_p2, t_len, Hq, mlp, feats2, bits2, logits_out=lg2)
+    kvq.kvq_features_controller_typed(t_narrow, t_ids, c_b, tot_b, True, t_p2, t_len, Hq, mlp, feats2, bits2, front_ws(n, vocab), logits_out=lg2)
     torch.cuda.synchronize()
     assert np.array_equal(feats2.cpu().numpy().view(np.uint32), got.view(np.uint32))
     assert np.array_equal(bits2.cpu().numpy(), bits.cpu().numpy())

@@ -43,11 +43,12 @@ def test_graph_replay_of_a_decode_step_equals_the_eager_step():
                           feats=torch.zeros((B, 4), dtype=torch.float32, device=d), bits=torch.zeros(B, dtype=torch.uint8, device=d),
                           out=torch.zeros((L, B, Hq, 64), dtype=torch.float32, device=d),
                           p2=torch.full((B, Hq), 0.01, dtype=torch.float32, device=d),
-                          ws=torch.empty(kvq.kvq_decode_attn_workspace(c, B), dtype=torch.uint8, device=d)))
+                          ws=torch.empty(kvq.kvq_decode_attn_workspace(c, B), dtype=torch.uint8, device=d),
+                          fws=torch.empty(kvq.kvq_features_workspace(B, wl.VOCAB), dtype=torch.uint8, device=d)))
 
     def step(st):
         kvq.kvq_features_controller(logits, ids, st["counts"], st["totals"], True, st["p2"], lens, Hq, mlp, st["feats"], st["bits"],
-                                    cache=st["cache"])
+                                    st["fws"], cache=st["cache"])
         for l in range(L):
             kvq.kvq_append_decode_attn(st["cache"], l, k[l], v[l], None, q[l], None, B, st["out"][l], st["ws"], None,
                                        st["p2"] if l == L - 1 else None)
