@@ -27,8 +27,7 @@ __global__ __launch_bounds__(1024) void k_mlp_row(MlpArgs A)
     __shared__ float act[2][kMaxWidth];
     const long long row = blockIdx.x;
     const int tid = threadIdx.x;
-    RowPrefetch pf;
-    mlp_row_prefetch(A, tid, pf);
+    const RowPrefetch pf = mlp_row_prefetch(A, tid);
     if (tid < A.dims[0]) act[0][tid] = A.feats[row * A.dims[0] + tid];
     __syncthreads();
     const int cur = mlp_row_forward(A, act, part, tid, (int)blockDim.x, pf);

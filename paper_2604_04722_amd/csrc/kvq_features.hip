@@ -350,8 +350,7 @@ __global__ __launch_bounds__(1024) void k_front_tail(FrontArgs F, MlpArgs M, Cac
     const int tid = threadIdx.x;
     // Everything the row needs from memory is asked for here, in one batch: the controller's weights (every thread),
     // the gathered count and the sequence's counters and page entries (thread 0), the slice triples (first wavefront).
-    RowPrefetch pf;
-    mlp_row_prefetch(M, tid, pf);
+    const RowPrefetch pf = mlp_row_prefetch(M, tid);
     long long tok_count = 0, seen = 0;
     int seq = 0, pre[5] = {0, 0, 0, 0, 0}, pre_page[kClasses] = {0, 0, 0, 0};
     if (tid == 0) {

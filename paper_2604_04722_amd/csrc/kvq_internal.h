@@ -154,8 +154,11 @@ __device__ __forceinline__ void advance_one_token(const CacheView &cv, int seq, 
     }
     if (b != 2 && b != 4 && b != 8 && b != 16) { atomicOr(cv.flags, KVQ_FLAG_BAD_BITS); b = 16; }
     const int c = bits_to_class(b);
-    const int slot = c == 0 ? pre[0] : c == 1 ? pre[1] : c == 2 ? pre[2] : pre[3];
-    int page_now = c == 0 ? pre_page[0] : c == 1 ? pre_page[1] : c == 2 ? pre_page[2] : pre_page[3];
+    // (selected by arithmetic: a chain of conditionals over array elements becomes a select of their addresses, which
+    // puts the arrays into scratch memory)
+    const int m0 = -(int)(c == 0), m1 = -(int)(c == 1), m2 = -(int)(c == 2), m3 = -(int)(c == 3);
+    const int slot = (pre[0] & m0) | (pre[1] & m1) | (pre[2] & m2) | (pre[3] & m3);
+    int page_now = (pre_page[0] & m0) | (pre_page[1] & m1) | (pre_page[2] & m2) | (pre_page[3] & m3);
     if (slot % cv.page_tokens == 0) {
         const int idx = atomicSub(&cv.free_top[c], 1) - 1;
         if (idx < 0) {

@@ -98,35 +98,49 @@ struct RowPrefetch { RowLayerPrefetch l0, l1, l2; };
 __device__ __forceinline__ bool mlp_row_vec(const MlpArgs &A, int l) { return (A.dims[l] & 3) == 0 && ((uintptr_t)A.W[l] & 15) == 0; }
 
 // the 16 weights of item `it` of layer L (vectorised layers only); loads beyond the row's end re-read its start
-template <int L> __device__ __forceinline__ void mlp_row_item_weights(const MlpArgs &A, int it, f32x4 &w0, f32x4 &w1, f32x4 &w2, f32x4 &w3)
+struct RowItemWeights { f32x4 w0, w1, w2, w3; };
+
+template <int L> __device__ __forceinline__ RowItemWeights mlp_row_item_weights(const MlpArgs &A, int it)
 {
     const int in = A.dims[L];
     const int chunks = (in + kRowChunk - 1) / kRowChunk;
     const int j = it / chunks, c = it - j * chunks;
     const int i0 = c * kRowChunk, i1 = min(i0 + kRowChunk, in);
     const float *w = A.W[L] + (size_t)j * in;
-    w0 = *(const f32x4 *)(w + i0);
-    w1 = *(const f32x4 *)(w + (i0 + 4 < i1 ? i0 + 4 : i0));
-    w2 = *(const f32x4 *)(w + (i0 + 8 < i1 ? i0 + 8 : i0));
-    w3 = *(const f32x4 *)(w + (i0 + 12 < i1 ? i0 + 12 : i0));
+    RowItemWeights r;
+    r.w0 = *(const f32x4 *)(w + i0);
+    r.w1 = *(const f32x4 *)(w + (i0 + 4 < i1 ? i0 + 4 : i0));
+    r.w2 = *(const f32x4 *)(w + (i0 + 8 < i1 ? i0 + 8 : i0));
+    r.w3 = *(const f32x4 *)(w + (i0 + 12 < i1 ? i0 + 12 : i0));
+    return r;
 }
 
-template <int L> __device__ __forceinline__ void mlp_row_prefetch_layer(const MlpArgs &A, int tid, RowLayerPrefetch &p)
+template <int L> __device__ __forceinline__ RowLayerPrefetch mlp_row_prefetch_layer(const MlpArgs &A, int tid)
 {
-    p.w0 = p.w1 = p.w2 = p.w3 = f32x4{0.f, 0.f, 0.f, 0.f};
-    p.bias = 0.f;
-    if (L >= A.n_linear) return;
-    const int outw = A.dims[L + 1];
-    const int items = outw * ((A.dims[L] + kRowChunk - 1) / kRowChunk);
-    if (tid < items && mlp_row_vec(A, L)) mlp_row_item_weights<L>(A, tid, p.w0, p.w1, p.w2, p.w3);
-    if (tid < outw) p.bias = A.b[L][tid];
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4 w0 = zero, w1 = zero, w2 = zero, w3 = zero;
+    float bias = 0.f;
+    if (L < A.n_linear) {
+        const int outw = A.dims[L + 1];
+        const int items = outw * ((A.dims[L] + kRowChunk - 1) / kRowChunk);
+        if (tid < items && mlp_row_vec(A, L)) {
+            const RowItemWeights r = mlp_row_item_weights<L>(A, tid);
+            w0 = r.w0; w1 = r.w1; w2 = r.w2; w3 = r.w3;
+        }
+        if (tid < outw) bias = A.b[L][tid];
+    }
+    RowLayerPrefetch p;
+    p.w0 = w0; p.w1 = w1; p.w2 = w2; p.w3 = w3; p.bias = bias;
+    return p;
 }
 
-__device__ __forceinline__ void mlp_row_prefetch(const MlpArgs &A, int tid, RowPrefetch &pf)
+__device__ __forceinline__ RowPrefetch mlp_row_prefetch(const MlpArgs &A, int tid)
 {
-    mlp_row_prefetch_layer<0>(A, tid, pf.l0);
-    mlp_row_prefetch_layer<1>(A, tid, pf.l1);
-    mlp_row_prefetch_layer<2>(A, tid, pf.l2);
+    RowPrefetch pf;
+    pf.l0 = mlp_row_prefetch_layer<0>(A, tid);
+    pf.l1 = mlp_row_prefetch_layer<1>(A, tid);
+    pf.l2 = mlp_row_prefetch_layer<2>(A, tid);
+    return pf;
 }
 
 __device__ __forceinline__ float mlp_row_fma4(const f32x4 &w, const float *h, int i, int i1, float a)
@@ -148,13 +162,12 @@ template <int L> __device__ __forceinline__ void mlp_row_layer(const MlpArgs &A,
     const int chunks = (in + kRowChunk - 1) / kRowChunk;
     const int items = outw * chunks;
     const bool vec = mlp_row_vec(A, L);
-    for (int it = tid; it < items; it += nthreads) {
+    // the first item of a thread runs on the prefetched weights, any further one fetches its own
+    auto item = [&](int it, const f32x4 &w0, const f32x4 &w1, const f32x4 &w2, const f32x4 &w3) {
         const int j = it / chunks, c = it - j * chunks;
         const int i0 = c * kRowChunk, i1 = min(i0 + kRowChunk, in);
         float a = 0.f;
         if (vec) {
-            f32x4 w0 = p.w0, w1 = p.w1, w2 = p.w2, w3 = p.w3;
-            if (it != tid) mlp_row_item_weights<L>(A, it, w0, w1, w2, w3);
             a = mlp_row_fma4(w0, h, i0, i1, a);
             a = mlp_row_fma4(w1, h, i0 + 4, i1, a);
             a = mlp_row_fma4(w2, h, i0 + 8, i1, a);
@@ -164,6 +177,12 @@ template <int L> __device__ __forceinline__ void mlp_row_layer(const MlpArgs &A,
             for (int i = i0; i < i1; ++i) a = fmaf(w[i], h[i], a);
         }
         part[it] = a;
+    };
+    if (tid < items) item(tid, p.w0, p.w1, p.w2, p.w3);
+    for (int it = tid + nthreads; it < items; it += nthreads) {
+        RowItemWeights r = {p.w0, p.w0, p.w0, p.w0};
+        if (vec) r = mlp_row_item_weights<L>(A, it);
+        item(it, r.w0, r.w1, r.w2, r.w3);
     }
     __syncthreads();
     if (tid < outw) {
