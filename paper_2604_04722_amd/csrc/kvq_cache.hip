@@ -636,15 +636,19 @@ __global__ __launch_bounds__(256) void k_append_bulk(CacheView cv, int layer, co
 // Only the first and the last block of a class in a call are pieces.  A sequence's work items are the blocks its call
 // touches, widest class first; `items` (at most tiles + 7) bounds their number and the surplus wavefronts leave at once.
 constexpr int kGridY = 32768;
+// wavefronts (kv-heads of one block of slots) per workgroup: its waves read adjacent 128-byte pieces of the same token
+// rows.  Measured at the benchmark's shape (32 sequences x 2048 tokens): 4 waves 129-134 us, 8 waves 132-144 us, 2 waves
+// 143-153 us.
+constexpr int kBlkWaves = 4;
 template <bool KCH>
-__global__ __launch_bounds__(256, KCH ? 3 : 4) void k_append_blocks(CacheView cv, int layer, const __half *k, const __half *v,
+__global__ __launch_bounds__(64 * kBlkWaves, (KCH ? 12 : 16) / kBlkWaves) void k_append_blocks(CacheView cv, int layer, const __half *k, const __half *v,
                                                        const int32_t *seq_ids, int n_seq, int n_pairs, int T, int items, int P_stream_min)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][kBlockTokens * kStageRow];
+    __shared__ __attribute__((aligned(16))) uint8_t stage_all[kBlkWaves][kBlockTokens * kStageRow];
     // the wavefront's number inside the workgroup as a scalar: everything derived from it (work item, class, block
     // address) then lives in scalar registers and the class branches are uniform
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int iw = blockIdx.x * 4 + wv;                            // grid: x = (work item, kv-head), y and z = (layer, sequence)
+    const int iw = blockIdx.x * kBlkWaves + wv;                            // grid: x = (work item, kv-head), y and z = (layer, sequence)
     const int pair = blockIdx.z * kGridY + blockIdx.y;
     if (iw >= items * cv.Hkv || pair >= n_pairs) return;
     const int lane = threadIdx.x & 63;
@@ -1121,14 +1125,14 @@ extern "C" int kvq_append(kvq_cache *cache, int32_t layer, const void *k, const 
         // chain of dependent reads wins (measured at 32 sequences: 256 tokens 31 against 37 us, 512 tokens 53 against 48)
         const int block_min_T = tn.append_block_min_T;
         const int items = tiles + 7;                               // upper bound of the blocks one sequence's call touches
-        const long long pairs = nl * n_seq, gx = ((long long)items * d.n_kv_heads + 3) / 4;
+        const long long pairs = nl * n_seq, gx = ((long long)items * d.n_kv_heads + kBlkWaves - 1) / kBlkWaves;
         if (T >= block_min_T && gx * pairs <= (1LL << 24)) {       // (a launch beyond that size goes tile by tile)
             const dim3 grid((unsigned)gx, (unsigned)(pairs < kGridY ? pairs : kGridY), (unsigned)((pairs + kGridY - 1) / kGridY));
             if (cache->view.k_channel)
-                hipLaunchKernelGGL(k_append_blocks<true>, grid, dim3(256), 0, st, cache->view, layer,
+                hipLaunchKernelGGL(k_append_blocks<true>, grid, dim3(64 * kBlkWaves), 0, st, cache->view, layer,
                                    (const __half *)k, (const __half *)v, seq_ids, n_seq, (int)pairs, T, items, stream_min);
             else
-                hipLaunchKernelGGL(k_append_blocks<false>, grid, dim3(256), 0, st, cache->view, layer,
+                hipLaunchKernelGGL(k_append_blocks<false>, grid, dim3(64 * kBlkWaves), 0, st, cache->view, layer,
                                    (const __half *)k, (const __half *)v, seq_ids, n_seq, (int)pairs, T, items, stream_min);
         } else if (cache->view.k_channel)
             hipLaunchKernelGGL(k_append_bulk<true>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer,
