@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+STATIC_WIDTH = {"static2": 2, "static4": 4, "static8": 8, "fp16": 16}     # caches that store every token at one width
 EVENT_STEPS = 5        # timed steps whose launches are bracketed by events (spread evenly over the run)
 
 
@@ -35,7 +36,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (4 = SmolLM-1.7B-shaped, the metric's config)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (profiling runs only)")
-    ap.add_argument("--variant", default="mixed", choices=["mixed", "static4", "fp16", "kchannel"],
+    ap.add_argument("--variant", default="mixed", choices=["mixed", "static2", "static4", "static8", "fp16", "kchannel"],
                     help="cache the timed loops run on (profiling runs: the same config stored as static 4-bit, FP16, or with "
                          "per-channel keys); anything but 'mixed' is not the metric and is named in config.variant")
     ap.add_argument("--no-compare", action="store_true", help="skip the static-4-bit, FP16, rule-policy and per-channel-key caches")
@@ -88,10 +89,8 @@ def main():
 
     def prefill_bits(variant):
         T = int(lens0.max())
-        if variant == "static4":
-            return np.full((B, T), 4, np.uint8)
-        if variant == "fp16":
-            return np.full((B, T), 16, np.uint8)
+        if variant in STATIC_WIDTH:
+            return np.full((B, T), STATIC_WIDTH[variant], np.uint8)
         if variant == "rule":
             f = torch.from_numpy(np.concatenate([wl.bulk_features(cfg, T, chunk=100 + s) for s in range(B)])).to(dev)
             b = torch.empty(B * T, dtype=torch.uint8, device=dev)
@@ -178,8 +177,8 @@ def main():
         counts_d = torch.from_numpy(counts_np).to(dev)
         totals_d = torch.tensor([N, Vobs], dtype=torch.int64, device=dev)
         fixed = None
-        if variant in ("static4", "fp16"):
-            fixed = torch.full((B, 1), 4 if variant == "static4" else 16, dtype=torch.uint8, device=dev)
+        if variant in STATIC_WIDTH:
+            fixed = torch.full((B, 1), STATIC_WIDTH[variant], dtype=torch.uint8, device=dev)
         ev_pairs, stage_ev = [], []
         base_step = done_steps.get(id(cache), 0)
         done_steps[id(cache)] = base_step + warm_steps + timed_steps + (1 if graph else 0)

@@ -104,6 +104,13 @@ int kvq_cache_reset(kvq_cache *cache, void *stream);
 /* Empties the listed sequences and returns their pages.  seq_ids: device int32[n_seq], distinct. */
 int kvq_cache_free_seqs(kvq_cache *cache, const int32_t *seq_ids, int32_t n_seq, void *stream);
 
+/* Launch-shape hint (never changes a result).  The library shapes an attention launch (waves per head, splits) for the
+ * longest sequence the cache may hold.  It cannot see the lengths without a device round trip, so it keeps a host-side
+ * high-water mark: every append raises it by the tokens appended, kvq_cache_reset clears it, kvq_cache_free_seqs does
+ * not lower it (the host does not know which sequences remain).  A server that recycles sequences tells the library
+ * the longest live length here; the mark continues to grow from that value. */
+int kvq_cache_set_length_hint(kvq_cache *cache, int64_t longest_live_length);
+
 /* Synchronizes `stream` and reports the sticky flags (KVQ_FLAG_*) and, if free_pages != NULL, the
  * number of free pages left in each class (host int64[4]). */
 int kvq_cache_status(kvq_cache *cache, uint32_t *flags, int64_t *free_pages, void *stream);
@@ -149,7 +156,8 @@ int kvq_cache_export(const kvq_cache *cache, int32_t layer, int32_t seq, uint8_t
  * values outside [m_c, m_c + r_c] clamp, and no per-token scale or minimum is stored for K (the export shows 0 for
  * them).  Values, the 16-bit class, and every entry point's signature are unchanged; the attention kernel folds the
  * steps into q once per class instead of reading a scale and a minimum per token.  Choose the quantizer while the
- * cache is empty (after create or reset); kmin == krange == NULL returns to the per-token quantizer.  Appends with
+ * cache is empty (after kvq_cache_create or kvq_cache_reset: a cache emptied by kvq_cache_free_seqs does not count,
+ * call kvq_cache_reset first); kmin == krange == NULL returns to the per-token quantizer.  Appends with
  * many tokens per call take the wave-per-vector kernel in this mode. */
 int kvq_cache_set_k_channel_quant(kvq_cache *cache, const void *kmin, const void *krange, void *stream);
 

@@ -24,7 +24,7 @@ EXPORT_REC = 128
 
 EXPORTED_SYMBOLS = (
     "kvq_version", "kvq_last_error", "kvq_cache_arena_bytes", "kvq_cache_create", "kvq_cache_destroy",
-    "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export", "kvq_cache_import", "kvq_cache_set_k_channel_quant",
+    "kvq_cache_reset", "kvq_cache_free_seqs", "kvq_cache_set_length_hint", "kvq_cache_status", "kvq_cache_counts", "kvq_cache_usage_of", "kvq_cache_export", "kvq_cache_import", "kvq_cache_set_k_channel_quant",
     "kvq_features_workspace", "kvq_features", "kvq_features_typed", "kvq_controller", "kvq_features_controller", "kvq_features_controller_typed", "kvq_rule_policy", "kvq_controller_param_count", "kvq_controller_train_workspace",
     "kvq_controller_train_step", "kvq_append", "kvq_decode_attn_workspace",
     "kvq_decode_attn", "kvq_decode_attn_static_capacity", "kvq_decode_attn_static", "kvq_append_decode_attn", "kvq_tuning_set", "kvq_tuning_get",
@@ -87,6 +87,7 @@ def load_library() -> ctypes.CDLL:
     lib.kvq_cache_destroy.argtypes = [vp]
     lib.kvq_cache_reset.argtypes = [vp, vp]
     lib.kvq_cache_free_seqs.argtypes = [vp, vp, i32, vp]
+    lib.kvq_cache_set_length_hint.argtypes = [vp, i64]
     lib.kvq_cache_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(i64), vp]
     lib.kvq_cache_counts.argtypes = [vp, vp, vp]
     lib.kvq_cache_usage_of.argtypes = [vp, ctypes.POINTER(CacheUsage), vp]
@@ -198,6 +199,9 @@ class Cache:
 
     def free_seqs(self, seq_ids: Optional[torch.Tensor], n_seq: int, stream=None) -> None:
         _check(load_library().kvq_cache_free_seqs(self.handle, _ptr(seq_ids, torch.int32, "seq_ids"), n_seq, _stream(stream)))
+
+    def set_length_hint(self, longest_live_length: int) -> None:
+        _check(load_library().kvq_cache_set_length_hint(self.handle, int(longest_live_length)))
 
     def status(self, stream=None):
         flags = ctypes.c_uint32(0)

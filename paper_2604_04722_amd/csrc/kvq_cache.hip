@@ -925,6 +925,7 @@ extern "C" int kvq_cache_create(const kvq_cache_desc *desc, kvq_cache **out)
     c->arena_bytes = need;
     c->own_arena = own;
     c->len_bound = 0;
+    c->touched = false;
     (void)hipGetDevice(&c->device);
     plan_arena(*desc, &c->view, (uint8_t *)arena);
     // Pages hold finite data from the start: lanes past the end of a bucket read in-bounds bytes and
@@ -959,6 +960,7 @@ extern "C" int kvq_cache_reset(kvq_cache *cache, void *stream)
     hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, (hipStream_t)stream, cache->view);
     KVQ_HIP(hipGetLastError());
     cache->len_bound = 0;
+    cache->touched = false;
     return KVQ_OK;
 }
 
@@ -969,6 +971,14 @@ extern "C" int kvq_cache_free_seqs(kvq_cache *cache, const int32_t *seq_ids, int
     if (n_seq == 0) return KVQ_OK;
     hipLaunchKernelGGL(k_free_seqs, dim3(n_seq), dim3(256), 0, (hipStream_t)stream, cache->view, seq_ids, n_seq);
     KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+}
+
+extern "C" int kvq_cache_set_length_hint(kvq_cache *cache, int64_t longest_live_length)
+{
+    if (!cache) { set_error("cache is NULL"); return KVQ_ERR_INVALID_ARG; }
+    if (longest_live_length < 0) { set_error("length hint is negative"); return KVQ_ERR_INVALID_ARG; }
+    cache->len_bound = longest_live_length < cache->desc.max_context ? longest_live_length : cache->desc.max_context;
     return KVQ_OK;
 }
 
@@ -1062,6 +1072,7 @@ extern "C" int kvq_cache_import(kvq_cache *cache, int32_t layer, int32_t seq, co
         KVQ_HIP(hipGetLastError());
         cache->len_bound += n_tokens;
         if (cache->len_bound > d.max_context) cache->len_bound = d.max_context;
+        cache->touched = true;
     }
     const long long waves = (long long)n_tokens * d.n_kv_heads;
     hipLaunchKernelGGL(k_import, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, cache->view, layer, seq, codes, meta,
@@ -1074,7 +1085,7 @@ extern "C" int kvq_cache_set_k_channel_quant(kvq_cache *cache, const void *kmin,
 {
     if (!cache) { set_error("cache is NULL"); return KVQ_ERR_INVALID_ARG; }
     if ((kmin == nullptr) != (krange == nullptr)) { set_error("kmin and krange must both be given or both be NULL"); return KVQ_ERR_INVALID_ARG; }
-    if (cache->len_bound != 0) { set_error("the key quantizer can only be chosen while the cache is empty (create or reset it first)"); return KVQ_ERR_INVALID_ARG; }
+    if (cache->touched) { set_error("the key quantizer can only be chosen while the cache is empty (create or reset it first)"); return KVQ_ERR_INVALID_ARG; }
     if (!kmin) { cache->view.k_channel = 0; return KVQ_OK; }
     const long long n = (long long)cache->desc.n_layers * cache->desc.n_kv_heads * kD;
     hipLaunchKernelGGL(k_set_kch, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, cache->view,
@@ -1093,6 +1104,7 @@ int kvq_append_bookkeeping(kvq_cache *cache, const uint8_t *bits, const int32_t 
     KVQ_HIP(hipGetLastError());
     cache->len_bound += T;
     if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;
+    cache->touched = true;
     return KVQ_OK;
 }
 

@@ -593,6 +593,7 @@ extern "C" int kvq_features_controller_typed(const void *logits, int32_t logits_
     if (cache) {                                                   // host-side length bound: the launch is queued
         cache->len_bound += 1;
         if (cache->len_bound > cache->desc.max_context) cache->len_bound = cache->desc.max_context;
+        cache->touched = true;
     }
     return KVQ_OK;
 }

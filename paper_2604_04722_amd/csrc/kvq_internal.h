@@ -83,7 +83,9 @@ struct kvq_cache {
     size_t arena_bytes;
     bool own_arena;
     int device;
-    int64_t len_bound;                 // host-side upper bound of any sequence's length (split heuristic only)
+    int64_t len_bound;                 // host-side upper bound of any sequence's length (split heuristic only): a high-water
+                                       // mark that grows with every append and falls only by reset or the caller's hint
+    bool touched;                      // something was appended or imported since create / reset
 };
 
 int kvq_append_bookkeeping(kvq_cache *cache, const uint8_t *bits, const int32_t *seq_ids, int n_seq, int T, void *stream);

@@ -104,6 +104,7 @@ def test_null_and_range_checks_fire_before_any_launch(lib):
     assert lib.kvq_controller(None, -1, ctypes.byref(m), None, None, None) == 1
     assert lib.kvq_features(None, 1, 100, None, None, None, 0, None, None, None, 1, 0, None, None, 0, None) == 1
     assert lib.kvq_features(None, 0, 100, None, None, None, 0, None, None, None, 1, 0, None, None, 0, None) == 0   # n = 0
+    assert lib.kvq_cache_set_length_hint(None, 5) == 1
     assert lib.kvq_tuning_set(b"no_such_entry", 1) == 1
     assert lib.kvq_tuning_set(b"attn_splits", 65) == 1
     assert lib.kvq_tuning_set(None, 1) == 1

@@ -53,6 +53,9 @@ def test_sequences_come_and_go_in_a_tight_pool():
         act = sorted(running)
         if not act:
             continue
+        # the launch-shape hint: the longest live sequence (on every other step a deliberately wrong value: results
+        # must not depend on it)
+        cache.set_length_hint(max(running.values()) + 1 if step % 2 else int(rng.integers(0, 3 * MAXC)))
         n = len(act)
         ids = torch.tensor(act, dtype=torch.int32, device=dev())
         sb = rng.choice([2, 4, 8, 16], (n, 1), p=mix).astype(np.uint8)
