@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (4 = SmolLM-1.7B-shaped, the metric's config)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (profiling runs only)")
-    ap.add_argument("--variant", default="mixed", choices=["mixed", "static2", "static4", "static8", "fp16", "kchannel"],
+    ap.add_argument("--variant", default="mixed", choices=["mixed", "static2", "static4", "static8", "fp16", "rule", "kchannel"],
                     help="cache the timed loops run on (profiling runs: the same config stored as static 4-bit, FP16, or with "
                          "per-channel keys); anything but 'mixed' is not the metric and is named in config.variant")
     ap.add_argument("--no-compare", action="store_true", help="skip the static-4-bit, FP16, rule-policy and per-channel-key caches")
@@ -61,6 +61,37 @@ def main():
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported (sequences and kv-heads are "
               "independent units, so a larger job shards over GPUs without any exchange inside this path)" % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    # ---------------- comparison caches built by the same library ------------------------------------
+    # Each comparison cache (static 4-bit, FP16, the rule policy's, per-channel keys) is built and timed by a child process
+    # of its own (this script with --variant), one after the other, BEFORE this process touches the device: a cache is
+    # then measured exactly as the headline is, as the first cache of a process that has the GPU to itself.  Device memory
+    # that is released (hipFree, torch emptying its cache when a graph is captured, a process that exits) is wiped by
+    # the driver in the background, and until that is done every bandwidth-bound launch on the device runs 3-5 % slow
+    # (launch-bound ones do not change; measured: 58 GB released -> the next process's first 50 ms of launches), so
+    # this process waits a few seconds after every child before the next measurement starts.
+    compare = {}
+    if not args.no_compare:
+        import subprocess
+        import workloads as wl0
+        variants = ("static4", "fp16") + (("rule",) if wl0.CONFIGS[args.config].bits_kind == "controller" else ()) + ("kchannel",)
+        for variant in variants:
+            cmd = [sys.executable, os.path.abspath(__file__), "--config", str(args.config), "--variant", variant,
+                   "--steps", str(args.steps), "--warmup", str(args.warmup), "--layers", str(args.layers),
+                   "--no-compare", "--no-cpu", "--no-fused", "--no-prefill", "--no-rotate"]
+            try:
+                r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+                sub = json.loads(r.stdout.strip().splitlines()[-1]) if r.returncode == 0 and r.stdout.strip() else None
+            except (subprocess.TimeoutExpired, ValueError):
+                sub = None
+            time.sleep(3.0)
+            if sub is None:
+                compare[variant] = {"skipped": "the child run of this variant failed (a cache that does not fit the device, most likely)"}
+                continue
+            log("[bench] %s cache (child process): %.1f us per attention launch" % (variant, sub["stages_us"]["attn_per_layer"]))
+            compare[variant] = {"us_per_step": sub["value"], "attn_us_per_layer": sub["stages_us"]["attn_per_layer"],
+                                "attn_GBps": sub["roofline"]["achieved"], "attn_bytes_per_layer": sub["roofline"]["bytes_per_launch"],
+                                "frac_of_hbm_peak": sub["roofline"]["frac"]}
 
     import numpy as np
     import torch
@@ -525,27 +556,6 @@ def main():
                          "threads), scaled by tokens to the batch and by %d layers = %.2f s; plus, timed once: features of the "
                          "batch %.3f s, controller %.4f s, quantize-and-append of one token per sequence x %d layers %.3f s "
                          "(features and append spread over %d threads by rows / sequences, the controller's %d rows on one)" % (ns, B, best, nthr, L, best * scale, t_feat, t_ctrl, L, t_app, nw, B)}
-    # ---------------- comparison caches built by the same library ------------------------------------
-    # (the mixed cache stays alive next to them: see `graveyard` above; config 5's caches are too large for that, and it
-    # has no comparison variants worth the memory: static 4-bit, FP16 and per-channel keys are quoted on config 4)
-    if cfg.index == 5:
-        cache.destroy()
-        del cache
-        torch.cuda.empty_cache()
-    compare = {}
-    if not args.no_compare:
-        for variant in ("static4", "fp16") + (("rule",) if rule is not None else ()) + ("kchannel",):
-            try:
-                c2, r2 = run_variant(variant, max(5, args.steps // 2), max(2, args.warmup), not args.no_events)
-            except kvq.KvqError as e:
-                if e.code != kvq.KVQ_ERR_OOM:
-                    raise
-                compare[variant] = {"skipped": "this cache does not fit next to the ones already built"}
-                continue
-            graveyard.append(c2)
-            compare[variant] = {"us_per_step": r2["ms_per_step"] * 1e3, "attn_us_per_layer": r2.get("attn_us_per_layer"),
-                                "attn_GBps": r2.get("attn_GBps"), "attn_bytes_per_layer": r2["attn_bytes_per_layer"]}
-
     tok = mixed["tokens_per_class"]
     tot = sum(tok) or 1.0
     result = {
