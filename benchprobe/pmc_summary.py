@@ -10,8 +10,8 @@ dispatch), each scaled by what the same counter reads for the benchmark's plain 
 1 GiB written), plus the hash of the kernel's sources so that a summary taken before a kernel change is not printed
 after it.
 
-    python3 benchprobe/pmc_summary.py --kernel k_decode_split --dirs gpurun_out/prof/trace gpurun_out/prof/fetch \\
-        gpurun_out/prof/write --traffic-kernel "k_decode_split<2, false>" --traffic-out profiles/..._traffic.txt
+    python3 benchprobe/pmc_summary.py --kernel k_decode_split --dirs out/prof/trace out/prof/fetch \\
+        out/prof/write --traffic-kernel "k_decode_split<2, false>" --traffic-out profiles/..._traffic.txt
 """
 from __future__ import annotations
 
