@@ -112,6 +112,31 @@ def test_null_and_range_checks_fire_before_any_launch(lib):
     assert b"kvq" in lib.kvq_version()
 
 
+def test_launch_shape_table_round_trips_and_starts_from_the_environment(lib):
+    """kvq_tuning_set / kvq_tuning_get on the host: defaults, a round trip, range checks that change nothing, and the
+    KVQ_* environment variables as the table's starting values (read once, in a process of its own)."""
+    import subprocess
+    import sys
+    v = ctypes.c_int32(-99)
+    lib.kvq_tuning_get.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int32)]
+    lib.kvq_tuning_set.argtypes = [ctypes.c_char_p, ctypes.c_int32]
+    defaults = {b"attn_splits": 0, b"attn_waves": 0, b"attn_longest_first": -1, b"attn_by_class": 12, b"append_bulk_min_T": 32,
+                b"append_stream_min": 16, b"append_block_min_T": 512, b"controller_no_mfma": 0, b"train_no_mfma": 0}
+    for name, want in defaults.items():
+        assert lib.kvq_tuning_get(name, ctypes.byref(v)) == 0 and v.value == want, name
+    assert lib.kvq_tuning_set(b"attn_splits", 7) == 0
+    assert lib.kvq_tuning_get(b"attn_splits", ctypes.byref(v)) == 0 and v.value == 7
+    assert lib.kvq_tuning_set(b"attn_splits", 65) == 1                       # out of range: refused, nothing changes
+    assert lib.kvq_tuning_get(b"attn_splits", ctypes.byref(v)) == 0 and v.value == 7
+    assert lib.kvq_tuning_set(b"attn_splits", 0) == 0
+    assert lib.kvq_tuning_get(b"nope", ctypes.byref(v)) == 1 and lib.kvq_tuning_get(b"attn_splits", None) == 1
+    code = ("import ctypes; l = ctypes.CDLL(%r); v = ctypes.c_int32(0); l.kvq_tuning_get(b'attn_splits', ctypes.byref(v)); a = v.value; "
+            "l.kvq_tuning_get(b'attn_waves', ctypes.byref(v)); print(a, v.value)" % os.path.join(ROOT, "paper_2604_04722_amd", "libkvq.so"))
+    env = dict(os.environ, KVQ_ATTN_SPLITS="3", KVQ_ATTN_WAVES="99")           # 99 is outside the entry's range: the default stays
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0 and r.stdout.split() == ["3", "0"], (r.stdout, r.stderr)
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     from paper_2604_04722_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
