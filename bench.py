@@ -378,7 +378,7 @@ def main():
                                                               Hq, feats, fws, sum_p2=sum_p2),
                                               kvq.kvq_controller(feats, mlp, step_bits.view(-1)))),
         "note": "kvq_features_controller (two launches) against kvq_features + kvq_controller (four launches), 100 calls back "
-                "to back without event records or cache bookkeeping; a launch costs about 7 us on this stream whatever it does"}
+                "to back without event records or cache bookkeeping; a call that launches one small kernel costs about 7 us of host time whatever the kernel does"}
 
     # measured streaming-read rate of a trivial kernel on this device (context for the 8 TB/s nominal peak)
     probe = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
