@@ -416,7 +416,7 @@ def test_fused_front_end_advances_the_cache_like_a_layer0_append():
         for l in range(L):
             kvq.kvq_append(cache_a, l, K[l], V[l], bits_a if l == 0 else None, seq_ids, B, 1)
             kvq.kvq_decode_attn(cache_a, l, q[l], seq_ids, B, out_a, aws, None, p2_a if l == L - 1 else None)
-        # path b: one front-end launch, then one launch per layer
+        # path b: the fused front end (two launches), then one launch per layer
         # (the variance feature of both paths comes from path a's attention: the two attention entry points agree
         # within the attention tolerance, not bit for bit, and this test compares bookkeeping exactly)
         kvq.kvq_features_controller(logits, ids, c_b, tot_b, True, p2_prev, lens, Hq, mlp, feats_b, bits_b.view(-1),
