@@ -82,3 +82,38 @@ def test_static_scratch_entry_point_rejects_launches_beyond_its_array():
     torch.cuda.synchronize()
     assert bool((out == 0.0).all())                           # empty sequences give zeros
     cache.destroy()
+
+
+def test_static_scratch_entry_point_under_graph_capture_replays_like_the_eager_call():
+    """What the entry point is for: a split launch (two kernels, the partial results in the library's own array) captured
+    into a HIP graph and replayed several times, with eager work and synchronizations in between, every replay compared
+    with the eager result on the inputs of that moment."""
+    say("kvq_decode_attn_static captured in a graph: 3 sequences x 900 tokens, 4 splits, 4 replays on changing queries")
+    B, T, Hq, Hkv = 3, 900, 8, 2
+    cache, oc = _build(B, T, Hq, Hkv, 53)
+    d = dev()
+    q_dev = torch.zeros((B, Hq, 64), dtype=torch.float16, device=d)
+    out_g = torch.zeros((B, Hq, 64), dtype=torch.float32, device=d)
+    lse_g = torch.zeros((B, Hq), dtype=torch.float32, device=d)
+    with tuning(attn_splits=4):
+        kvq.kvq_decode_attn_static(cache, 0, q_dev, None, B, out_g, lse_g)       # warm-up outside the capture (first-use set-up)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            kvq.kvq_decode_attn_static(cache, 0, q_dev, None, B, out_g, lse_g)
+        for rep in range(4):
+            q = make_kv((B, Hq, 64), 600 + rep, outlier=False)
+            q_dev.copy_(gpu_f16(q))
+            g.replay()
+            torch.cuda.synchronize()
+            got, got_lse = out_g.cpu().numpy().copy(), lse_g.cpu().numpy().copy()
+            out_e = torch.full((B, Hq, 64), float("nan"), dtype=torch.float32, device=d)
+            lse_e = torch.zeros((B, Hq), dtype=torch.float32, device=d)
+            kvq.kvq_decode_attn_static(cache, 0, q_dev, None, B, out_e, lse_e)   # eager work between the replays
+            torch.cuda.synchronize()
+            assert np.array_equal(got, out_e.cpu().numpy()) and np.array_equal(got_lse, lse_e.cpu().numpy()), "replay %d differs from the eager call" % rep
+            for b in range(B):
+                want, _, _ = oc.attn(b, q[b], Hq)
+                assert_attn_close(got[b], want, "graph replay %d, seq %d" % (rep, b))
+    cache.destroy()
+
