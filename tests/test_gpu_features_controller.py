@@ -214,6 +214,45 @@ def test_controller_row_and_bulk_launch_shapes_agree():
         check_controller(feats[:100], Wo, bo)
 
 
+@pytest.mark.parametrize("widths", [(50, 33), (7,), (256, 200), (129, 3)])
+def test_per_step_controller_widths_off_the_vector_path_and_the_fused_call_above_256_rows(widths):
+    say("per-step controller, hidden widths %s: no multiple of 4 (scalar weight loads), several passes over the work items" % (widths,))
+    d = dev()
+    rng = np.random.default_rng(900 + sum(widths))
+    dims = (4,) + tuple(widths) + (4,)
+    Ws = [rng.uniform(-1, 1, (dims[i + 1], dims[i])).astype(np.float32) * np.float32(np.sqrt(3.0 / dims[i])) for i in range(len(dims) - 1)]
+    bs = [rng.uniform(-0.3, 0.3, dims[i + 1]).astype(np.float32) for i in range(len(dims) - 1)]
+    feats = rng.standard_normal((2048, 4)).astype(np.float32) * np.array([3.0, 4.0, 1e-3, 0.5], np.float32)
+    for n in (1, 7, 256, 257, 2048):                              # 1024 threads a row up to 256 rows, 256 threads beyond
+        check_controller(feats[:n], Ws, bs)
+    # the fused call takes the same two workgroup sizes; its decision equals the separate calls' bit for bit
+    mlp = kvq.MlpWeights([torch.from_numpy(w).to(d) for w in Ws], [torch.from_numpy(b).to(d) for b in bs])
+    Hq, vocab = 6, 3001
+    for n in (9, 300):
+        logits, ids, counts, N, Vobs, lens, p2 = _front_inputs(n, vocab, Hq, 77 + n)
+        t = lambda a: torch.from_numpy(a).to(d)
+        t_logits, t_ids, t_len, t_p2 = t(logits), t(ids), t(lens), t(p2)
+        c_a, tot_a = t(counts), torch.tensor([N, Vobs], dtype=torch.int64, device=d)
+        f_a = torch.zeros((n, 4), dtype=torch.float32, device=d)
+        b_a = torch.zeros(n, dtype=torch.uint8, device=d)
+        l_a = torch.zeros((n, 4), dtype=torch.float32, device=d)
+        kvq.kvq_features(t_logits, t_ids, c_a, tot_a, True, t_len, Hq, f_a, front_ws(n, vocab), sum_p2=t_p2)
+        kvq.kvq_controller(f_a, mlp, b_a, l_a)
+        c_b, tot_b = t(counts), torch.tensor([N, Vobs], dtype=torch.int64, device=d)
+        f_b = torch.full((n, 4), float("nan"), dtype=torch.float32, device=d)
+        b_b = torch.zeros(n, dtype=torch.uint8, device=d)
+        l_b = torch.zeros((n, 4), dtype=torch.float32, device=d)
+        kvq.kvq_features_controller(t_logits, t_ids, c_b, tot_b, True, t_p2, t_len, Hq, mlp, f_b, b_b, front_ws(n, vocab), logits_out=l_b)
+        torch.cuda.synchronize()
+        assert np.array_equal(f_b.cpu().numpy().view(np.uint32), f_a.cpu().numpy().view(np.uint32))
+        assert np.array_equal(l_b.cpu().numpy().view(np.uint32), l_a.cpu().numpy().view(np.uint32))
+        assert np.array_equal(b_b.cpu().numpy(), b_a.cpu().numpy())
+        assert np.array_equal(c_b.cpu().numpy(), c_a.cpu().numpy()) and np.array_equal(tot_b.cpu().numpy(), tot_a.cpu().numpy())
+        want_bits, want_logits = oracle.controller(f_a.cpu().numpy(), Ws, bs)
+        srt = np.sort(want_logits, axis=1)
+        assert not np.any((b_b.cpu().numpy() != want_bits) & (srt[:, -1] - srt[:, -2] > 1e-5))
+
+
 @pytest.mark.parametrize("dims", [(4, 32, 4), (4, 64, 4), (4, 128, 4), (4, 32, 32, 4), (4, 64, 128, 4), (4, 128, 32, 4), (4, 128, 64, 4)])
 @pytest.mark.parametrize("n", [2049, 4097, 33333])
 def test_controller_matrix_core_shape_all_width_combinations(dims, n):
