@@ -47,6 +47,11 @@ template <> struct Cls<1> { static constexpr int U = 1, NCH = 2, NT = 2; };
 template <> struct Cls<2> { static constexpr int U = 1, NCH = 4, NT = 1; };
 template <> struct Cls<3> { static constexpr int U = 1, NCH = 8, NT = 1; };
 
+// Relative cost of one unit of each class (2 bit: 128 tokens, 5 KiB; 4 bit: 64 tokens, 4.5 KiB; 8 bit: 8.5 KiB;
+// FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost vector-ALU time for unpacking, and
+// these ratios are the ones that equalise the finishing times of a workgroup's waves (measured).
+constexpr int kUnitCost[4] = {14, 11, 17, 32};
+
 // target multipliers M: h = 1 + c/M
 #define KVQ_M0_0 4.f      /* 2-bit codes at mantissa bits [8,10) */
 #define KVQ_M0_1 16.f     /*                              [6,8)  */
@@ -89,6 +94,9 @@ template <int CTRL> __device__ __forceinline__ float dpp_mov(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
 }
 
+template <int CTRL> __device__ __forceinline__ int quad_mov_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
+template <int CTRL> __device__ __forceinline__ float quad_mov_f(float v) { return dpp_mov<CTRL>(v); }
+
 __device__ __forceinline__ float lane_bcast(float v, int lane)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
@@ -129,7 +137,6 @@ struct QConst {
 
 struct AttnParams {
     CacheView cv;
-    int32_t wgt[4];
     int32_t by_class;        // whole waves per class when a wave has at most this many units on average (0: never)
     const uint32_t *q;          // [n_seq][Hq][32] fp16 pairs
     const __half *k_new, *v_new; // fused append: the new token's K/V [n_seq][Hkv][64], or nullptr
@@ -439,19 +446,37 @@ struct ClassWalk {
     const int32_t *pt;          // page-table row of (seq, class)
     const uint8_t *pool;        // class pool at this layer
     int Hkv, kvh, bpp, bpp_log2, cnt;
+    int pi0, page0;             // the page-table entry of the range's first unit (index, page id), fetched by the prologue
 };
 
 // The page table is read through the constant address space: with a wave-uniform index this is a scalar
 // load, which does not queue behind (or force a wait on) the vector loads of the stage pipeline.
 typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
 
-template <int C> __device__ __forceinline__ const uint8_t *unit_base(const ClassWalk &w, int ui)
+template <int C> __device__ __forceinline__ int units_per_page_log2(int bpp_log2) { return bpp_log2 - (Cls<C>::U == 2 ? 1 : 0); }
+
+template <int C> __device__ __forceinline__ const uint8_t *unit_base_in(const ClassWalk &w, int ui, int page)
 {
     constexpr int U = Cls<C>::U;
-    const int sh = w.bpp_log2 - (U == 2 ? 1 : 0);   // log2(units per page); page_tokens is a power of two
-    const int page = ((const_i32_ptr)(uintptr_t)w.pt)[ui >> sh];
+    const int sh = units_per_page_log2<C>(w.bpp_log2);   // page_tokens is a power of two
     const int blk = (ui & ((1 << sh) - 1)) * U;
     return w.pool + (((size_t)page * w.Hkv + w.kvh) * w.bpp + blk) * (size_t)class_block_bytes(C);
+}
+
+// (No "same page as last time?" shortcut here: a branch inside the pipelined loops makes the compiler's wait-count
+// bookkeeping give up, and it then drains every outstanding stage load at the top of each iteration.)
+template <int C> __device__ __forceinline__ const uint8_t *unit_base(const ClassWalk &w, int ui)
+{
+    const int sh = units_per_page_log2<C>(w.bpp_log2);
+    return unit_base_in<C>(w, ui, ((const_i32_ptr)(uintptr_t)w.pt)[ui >> sh]);
+}
+
+// Outside the loops: a unit of the range's first page needs no look at the table.
+template <int C> __device__ __forceinline__ const uint8_t *unit_base_start(const ClassWalk &w, int ui)
+{
+    const int sh = units_per_page_log2<C>(w.bpp_log2);
+    if ((ui >> sh) == w.pi0) return unit_base_in<C>(w, ui, w.page0);
+    return unit_base<C>(w, ui);
 }
 
 template <int C> __device__ __forceinline__ int unit_ntok(const ClassWalk &w, int ui)
@@ -477,18 +502,27 @@ __device__ __forceinline__ void run_low(const ClassWalk &w, int k0, int k1, int 
     constexpr int U = Cls<C>::U, NT = Cls<C>::NT;
     Stage b0, b1, b2, b3;
     uint2 m0[U], m1[U];
-    const uint8_t *safe = unit_base<C>(w, k0);
+    const uint8_t *safe = unit_base_start<C>(w, k0);
     {
+        // (fenced like the loop body: the loop's wait counts assume that the buffers were asked for in the order in
+        // which they are used, and the compiler takes the stricter of what the loop's two entries need; left to
+        // itself it may ask for the first buffer last, and the loop then waits for ALL loads in every iteration)
         const int na = unit_ntok<C>(w, k0);
+        KVQ_FENCE();
         issue_stage<C, false, 0>(b0, safe, na, lane);
         issue_meta<C>(m0, safe, na, lane);
+        KVQ_FENCE();
         issue_stage<C, true, 0>(b1, safe, na, lane);
+        KVQ_FENCE();
         const bool two = k0 + step < k1;
-        const uint8_t *bb = two ? unit_base<C>(w, k0 + step) : safe;
+        const uint8_t *bb = two ? unit_base_start<C>(w, k0 + step) : safe;
         const int nb = two ? unit_ntok<C>(w, k0 + step) : 0;
+        KVQ_FENCE();
         issue_stage<C, false, 0>(b2, bb, nb, lane);
         issue_meta<C>(m1, bb, nb, lane);
+        KVQ_FENCE();
         issue_stage<C, true, 0>(b3, bb, nb, lane);
+        KVQ_FENCE();
     }
     auto k_stage = [&](const Stage &b, const uint2 (&m)[U], int ntok, float (&a)[U][NT]) {
         float dot[U];
@@ -539,14 +573,20 @@ __device__ __forceinline__ void run_8bit(const ClassWalk &w, int k0, int k1, int
     if (k0 >= k1) return;
     Stage b0, b1, b2, b3;
     uint2 m0[1];
-    const uint8_t *safe = unit_base<2>(w, k0);
+    const uint8_t *safe = unit_base_start<2>(w, k0);
     {
         const int na = unit_ntok<2>(w, k0);
+        KVQ_FENCE();
         issue_stage<2, false, 0>(b0, safe, na, lane);
-        issue_meta<2>(m0, safe, na, lane);
+        KVQ_FENCE();
         issue_stage<2, false, 1>(b1, safe, na, lane);
+        KVQ_FENCE();
+        issue_meta<2>(m0, safe, na, lane);
+        KVQ_FENCE();
         issue_stage<2, true, 0>(b2, safe, na, lane);
+        KVQ_FENCE();
         issue_stage<2, true, 1>(b3, safe, na, lane);
+        KVQ_FENCE();
     }
     for (int ui = k0; ui < k1; ui += step) {
         const bool more = ui + step < k1;
@@ -582,13 +622,18 @@ __device__ __forceinline__ void run_fp16(const ClassWalk &w, int k0, int k1, int
 {
     if (k0 >= k1) return;
     Stage b0, b1, b2, b3;
-    const uint8_t *safe = unit_base<3>(w, k0);
+    const uint8_t *safe = unit_base_start<3>(w, k0);
     {
         const int na = unit_ntok<3>(w, k0);
+        KVQ_FENCE();
         issue_stage<3, false, 0>(b0, safe, na, lane);
+        KVQ_FENCE();
         issue_stage<3, false, 1>(b1, safe, na, lane);
+        KVQ_FENCE();
         issue_stage<3, false, 2>(b2, safe, na, lane);
+        KVQ_FENCE();
         issue_stage<3, false, 3>(b3, safe, na, lane);
+        KVQ_FENCE();
     }
     const uint8_t *bc = safe;
     for (int ui = k0; ui < k1; ui += step) {
@@ -684,83 +729,106 @@ template <int NW, bool KCH>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAVES_PER_EU, KVQ_WAVES_PER_EU))) void k_decode_split(AttnParams P)
 {
     const CacheView &cv = P.cv;
-    // The arguments live in memory and the compiler would fetch each where it is first used: a dozen scalar loads,
-    // each waited for on its own, before the first byte of the cache is asked for.  Asking for them here makes them
-    // one batch behind a single wait.
-#define KVQ_FETCH_NOW(x) asm volatile("" : : "s"(x))
-    KVQ_FETCH_NOW(P.S); KVQ_FETCH_NOW(P.n_seq); KVQ_FETCH_NOW(P.longest_first); KVQ_FETCH_NOW(P.seq_ids); KVQ_FETCH_NOW(P.q);
-    KVQ_FETCH_NOW(P.k_new); KVQ_FETCH_NOW(P.layer); KVQ_FETCH_NOW(P.by_class);
-    KVQ_FETCH_NOW(P.wgt[0]); KVQ_FETCH_NOW(P.wgt[1]); KVQ_FETCH_NOW(P.wgt[2]); KVQ_FETCH_NOW(P.wgt[3]);
-    KVQ_FETCH_NOW(cv.Hq); KVQ_FETCH_NOW(cv.Hkv); KVQ_FETCH_NOW(cv.max_seqs); KVQ_FETCH_NOW(cv.counts); KVQ_FETCH_NOW(cv.last_rec);
-    KVQ_FETCH_NOW(cv.page_table); KVQ_FETCH_NOW(cv.max_pages_per_seq); KVQ_FETCH_NOW(cv.blocks_per_page);
-#undef KVQ_FETCH_NOW
-    const int G = cv.Hq / cv.Hkv;
-    const int S = P.S;
-    const int nunits = P.n_seq * cv.Hq * S;
+    // Every memory round trip before the first cache byte is asked for costs a launch of a few units per wave more than
+    // the units themselves, so the prologue is three batches of loads, each behind ONE wait:
+    //   1. the arguments (the compiler would fetch each where it is first used, and wait for each on its own);
+    //   2. everything that hangs on the sequence and head alone: the class counts, the newest-token record, the query
+    //      and entry 0 of the four page-table rows (one vector load, a word per lane: scalar loads that miss their
+    //      cache are answered one line after the other, these travel side by side);
+    //   3. only for a wave whose range starts beyond a class's first page: the entries it starts at.
+    int S = P.S, n_seq = P.n_seq, Hq = cv.Hq, Hkv = cv.Hkv;
+    const int longest_first = P.longest_first, layer = P.layer, by_class = P.by_class;
+    const int max_seqs = cv.max_seqs, mpps = cv.max_pages_per_seq, bpp = cv.blocks_per_page;
+    const int32_t *const seq_ids = P.seq_ids;
+    const uint32_t *const q_all = P.q;
+    const __half *const k_new = P.k_new;
+    const int32_t *const counts = cv.counts, *const last_rec = cv.last_rec, *const page_table = cv.page_table;
+    const uint8_t *const pool0 = cv.pool[0];     // (the pools and layer strides share one 64-byte line of the argument block:
+                                                 // asking for one of them now makes the later reads of the others short)
+    // (the four that the work-item arithmetic starts from are outputs as well: nothing can then be scheduled ahead of
+    // this point, behind a wait of its own for part of the loads)
+    asm volatile("" : "+s"(S), "+s"(n_seq), "+s"(Hq), "+s"(Hkv)
+                 : "s"(longest_first), "s"(layer), "s"(by_class), "s"(max_seqs), "s"(mpps), "s"(bpp), "s"(seq_ids), "s"(q_all),
+                   "s"(k_new), "s"(counts), "s"(last_rec), "s"(page_table), "s"(pool0));
+    const uint32_t G = (uint32_t)Hq / (uint32_t)Hkv;
+    const uint32_t nunits = (uint32_t)n_seq * (uint32_t)Hq * (uint32_t)S;
     // Workgroups are dealt to the 8 XCDs round-robin by id.  Give each XCD a contiguous range of work
     // items instead, so that the G query heads that share one kv-head's bytes also share one L2.
-    const int per_xcd = (nunits + 7) >> 3;
-    const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const uint32_t per_xcd = (nunits + 7u) >> 3;
+    const uint32_t unit = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
     if ((blockIdx.x >> 3) >= per_xcd || unit >= nunits) return;
     // unit = ((si*Hkv + kvh)*S + s)*G + g
-    int r = unit;
-    const int g = r % G; r /= G;
-    const int s = r % S; r /= S;
-    const int kvh = r % cv.Hkv;
-    int si = r / cv.Hkv;
-    const int qh = kvh * G + g;
+    uint32_t r = unit;
+    const int g = (int)(r % G); r /= G;
+    int s = 0;
+    if (S != 1) { s = (int)(r % (uint32_t)S); r /= (uint32_t)S; }
+    const int kvh = (int)(r % (uint32_t)Hkv);
+    int si = (int)(r / (uint32_t)Hkv);
+    const int qh = kvh * (int)G + g;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (P.longest_first) {
+    if (longest_first) {
         // A launch with more workgroups than fit at once is list scheduling in workgroup order: with the sequences in
         // arbitrary order the last round may start a long one (ragged batch: makespan up to 1.3x the mean).  So the
         // position si in the launch order takes the sequence of that RANK by length, longest first, dealt to the XCDs
         // in turn (an XCD's k-th position has rank 8k + xcd).  Every workgroup ranks the (at most 64) lengths itself:
         // lane = sequence, 64 lane reads.
-        const int q8 = P.n_seq >> 3;
+        const int q8 = n_seq >> 3;
         const int want = (si % q8) * 8 + si / q8;
         int my_len = -1;
-        if (lane < P.n_seq) {
-            const int sq = P.seq_ids ? P.seq_ids[lane] : lane;
-            my_len = (sq >= 0 && sq < cv.max_seqs) ? cv.counts[(size_t)sq * 5 + 4] : 0;
+        if (lane < n_seq) {
+            const int sq = seq_ids ? seq_ids[lane] : lane;
+            my_len = (sq >= 0 && sq < max_seqs) ? counts[(size_t)sq * 5 + 4] : 0;
         }
         int rank = 0;
-        for (int j = 0; j < P.n_seq; ++j) {
+        for (int j = 0; j < n_seq; ++j) {
             const int lj = __builtin_amdgcn_readlane(my_len, j);
             rank += (lj > my_len || (lj == my_len && j < lane)) ? 1 : 0;
         }
-        const unsigned long long hit = __ballot(lane < P.n_seq && rank == want);
+        const unsigned long long hit = __ballot(lane < n_seq && rank == want);
         si = (int)__builtin_ctzll(hit);
     }
-    int seq = P.seq_ids ? P.seq_ids[si] : si;
-    const bool seq_ok = seq >= 0 && seq < cv.max_seqs;
-    if (!seq_ok) seq = 0;
+    int seq = si;
+    if (seq_ids) seq = ((const_i32_ptr)(uintptr_t)seq_ids)[si];
+    const bool seq_ok = seq >= 0 && seq < max_seqs;
+    if (!seq_ok) seq = 0;                                                    // row 0 exists: the loads below stay in bounds
 
-    // the sequence's class counts and newest-token record are asked for before the query, so that the three answers
-    // travel together: what follows the query (ranges, first page, first block) hangs on the counts
-    int cnt[kClasses];
-#pragma unroll
-    for (int c = 0; c < kClasses; ++c) cnt[c] = seq_ok ? cv.counts[(size_t)seq * 5 + c] : 0;
-    int4 rec = make_int4(0, 0, 0, 0);                                        // {last_T, bits, slot, page} of the newest token
-    if (P.k_new != nullptr && seq_ok) rec = *(const int4 *)(cv.last_rec + (size_t)seq * 4);
-
-    // the query as 32 fp16 pairs (wave-uniform), sum(q), and the per-class target sums
+    // ---- batch 2: ONE vector load instruction, a different address per lane, then lane reads into scalars ----
+    //   lanes 0..31 the query's fp16 pairs, 32..35 the class counts, 40..43 the newest-token record,
+    //   48..51 entry 0 of the four page-table rows; the other lanes repeat lane 0's word
+    const int32_t *const pt_seq = page_table + (size_t)seq * kClasses * mpps;
+    const uint32_t *b2 = q_all + ((size_t)si * Hq + qh) * 32 + (lane < 32 ? lane : 0);
+    if (lane >= 32 && lane < 36) b2 = (const uint32_t *)(counts + (size_t)seq * 5 + (lane - 32));
+    if (lane >= 40 && lane < 44) b2 = (const uint32_t *)(last_rec + (size_t)seq * 4 + (lane - 40));
+    if (lane >= 48 && lane < 52) b2 = (const uint32_t *)(pt_seq + (size_t)(lane - 48) * mpps);
+    const int b2v = (int)*b2;
     uint32_t q2[32];
-    const uint32_t *qp = P.q + ((size_t)si * cv.Hq + qh) * 32;
-    float qsum = 0.f, t0[3] = {0.f, 0.f, 0.f}, t1[2] = {0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-        q2[i] = qp[i];
-        const float v = half_lo(q2[i]) + half_hi(q2[i]);
-        qsum += v;
-        t0[target0(i % 8)] += v;
-        t1[target1(i % 4)] += v;
-    }
+    for (int i = 0; i < 32; ++i) q2[i] = (uint32_t)__builtin_amdgcn_readlane(b2v, i);
+    int cnt[kClasses] = {__builtin_amdgcn_readlane(b2v, 32), __builtin_amdgcn_readlane(b2v, 33), __builtin_amdgcn_readlane(b2v, 34),
+                         __builtin_amdgcn_readlane(b2v, 35)};
+    int4 rec = make_int4(__builtin_amdgcn_readlane(b2v, 40), __builtin_amdgcn_readlane(b2v, 41), __builtin_amdgcn_readlane(b2v, 42),
+                         __builtin_amdgcn_readlane(b2v, 43));         // {last_T, bits, slot, page} of the newest token
+    const int sp0 = __builtin_amdgcn_readlane(b2v, 48), sp1 = __builtin_amdgcn_readlane(b2v, 49),
+              sp2 = __builtin_amdgcn_readlane(b2v, 50), sp3 = __builtin_amdgcn_readlane(b2v, 51);
+    if (!seq_ok) cnt[0] = cnt[1] = cnt[2] = cnt[3] = 0;
+    if (k_new == nullptr || !seq_ok) rec = make_int4(0, 0, 0, 0);
+
+    // sum(q) and, per class, sum_t M_t sum(q over target t): lane = pair while the load's answer still lies across the
+    // lanes (32 pairs at once and three reductions, instead of a chain of a hundred dependent scalar-operand additions
+    // that every wave would walk through before its first load).  M is a power of two: 2^e with e from the pair's
+    // position in its word (2 bit: pairs 1,4,7 -> 4, 0,3,6 -> 16, 2,5 -> 64; 4 bit: odd -> 16, even -> 256).
     QConst qc;
-    qc.qs = qsum * kScoreScale;
-    qc.qm[0] = (KVQ_M0_0 * t0[0] + KVQ_M0_1 * t0[1] + KVQ_M0_2 * t0[2]) * kScoreScale;
-    qc.qm[1] = (KVQ_M1_0 * t1[0] + KVQ_M1_1 * t1[1]) * kScoreScale;
-    qc.qm[2] = KVQ_OFF2 * qsum * kScoreScale;
+    {
+        const float v = lane < 32 ? half_lo((uint32_t)b2v) + half_hi((uint32_t)b2v) : 0.f;
+        const int e0 = (int)((0x24624624u >> (4 * (lane & 7))) & 15u);
+        const int e1 = (lane & 1) ? 4 : 8;
+        const float qsum = wave_sum(v);
+        qc.qs = qsum * kScoreScale;
+        qc.qm[0] = wave_sum(__builtin_ldexpf(v, e0)) * kScoreScale;
+        qc.qm[1] = wave_sum(__builtin_ldexpf(v, e1)) * kScoreScale;
+        qc.qm[2] = KVQ_OFF2 * qsum * kScoreScale;
+    }
     const Consts cs = make_consts();
 
     WaveState st;
@@ -774,16 +842,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     // weighted by their cost; the S workgroups x NW waves cut the list into S*NW contiguous ranges of
     // equal weight (a unit belongs to the range that holds its start), so a wave meets one or two classes.
     int nu[kClasses];
-    const int *env_w = P.wgt;
-    const int wgt[kClasses] = {env_w[0], env_w[1], env_w[2], env_w[3]};
+    constexpr int wgt[kClasses] = {kUnitCost[0], kUnitCost[1], kUnitCost[2], kUnitCost[3]};
     uint32_t wtot = 0;                                       // below 2^31: the host checks units x weight before the launch
     // Fused append: the newest token of the sequence (logged by the bookkeeping kernel, slot = last of its class)
     // is not read from the cache.  It is quantized in registers from k_new / v_new, joins the softmax as one extra
     // partial result, and the workgroup with s == 0, g == 0 stores it for later steps.
     bool has_new = false;
     int new_bits = 16, new_cls = 3, new_slot = 0, new_page = 0;
-    if (P.k_new != nullptr && seq_ok) {
-        if (rec.x == 1) {
+    {
+        if (rec.x == 1) {                                     // (zeroed above when there is no new token to take)
             new_bits = rec.y;
             new_slot = rec.z;
             new_page = rec.w;
@@ -796,10 +863,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     const bool does_new = has_new && s == 0 && wave == 0;
     __half new_kx = __ushort_as_half((unsigned short)0), new_vx = new_kx, new_qx = new_kx;
     if (does_new) {
-        const size_t src = ((size_t)si * cv.Hkv + kvh) * kD + lane;
-        new_kx = P.k_new[src];
+        const size_t src = ((size_t)si * Hkv + kvh) * kD + lane;
+        new_kx = k_new[src];
         new_vx = P.v_new[src];
-        new_qx = ((const __half *)P.q)[((size_t)si * cv.Hq + qh) * kD + lane];
+        new_qx = ((const __half *)q_all)[((size_t)si * Hq + qh) * kD + lane];
     }
 #pragma unroll
     for (int c = 0; c < kClasses; ++c) {
@@ -820,46 +887,50 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     const uint32_t nu_tot = (uint32_t)(nu[0] + nu[1] + nu[2] + nu[3]);
     const int nonempty = (nu[0] > 0) + (nu[1] > 0) + (nu[2] > 0) + (nu[3] > 0);
     bool ranged = false;
-    if (S == 1 && nonempty > 1 && J >= 2 * nonempty && nu_tot <= (uint32_t)P.by_class * (uint32_t)J) {
-        uint32_t wc[kClasses];
-        int nwc[kClasses], used = 0;
+    if (S == 1 && nonempty > 1 && J >= 2 * nonempty && nu_tot <= (uint32_t)by_class * (uint32_t)J) {
+        // lane = class (the lane's low two bits; every quad computes the same): four classes per instruction, and the
+        // cross-class steps are moves inside a quad
+        const int c4 = lane & 3;
+        const int v_nu = c4 == 0 ? nu[0] : c4 == 1 ? nu[1] : c4 == 2 ? nu[2] : nu[3];
+        const int v_wgt = c4 == 0 ? wgt[0] : c4 == 1 ? wgt[1] : c4 == 2 ? wgt[2] : wgt[3];
+        const float v_wc = (float)(v_nu * v_wgt);                  // exact: below 2^24 here (at most a dozen units per wave)
         const float per_weight = (float)J * __builtin_amdgcn_rcpf((float)wtot);
-#pragma unroll
-        for (int c = 0; c < kClasses; ++c) {
-            wc[c] = (uint32_t)nu[c] * (uint32_t)wgt[c];
-            nwc[c] = wc[c] ? max(1, (int)((float)wc[c] * per_weight)) : 0;
-            used += nwc[c];
+        int v_n = v_nu > 0 ? max(1, (int)(v_wc * per_weight)) : 0;
+        int used;
+        {
+            int t = v_n + quad_mov_i<0xB1>(v_n);                   // [1,0,3,2]
+            t += quad_mov_i<0x4E>(t);                              // [2,3,0,1]
+            used = __builtin_amdgcn_readfirstlane(t);
         }
         for (int it = 0; it < 2 * kClasses && used != J; ++it) {
+            // too few waves handed out: the class with the largest load per wave gets one more; too many: the class
+            // whose load per wave rises least gives one back (ties: the lowest class)
             const bool more = used < J;
-            int pick = -1;
-            uint32_t pw = 0, pn = 1;                                // the picked class's weight and wave count (less one when taking away)
-#pragma unroll
-            for (int c = 0; c < kClasses; ++c) {
-                const uint32_t n = (uint32_t)(more ? nwc[c] : nwc[c] - 1);
-                // more: the class with the largest load per wave gets one more; else: the class whose load per wave
-                // rises least (smallest weight per remaining wave) gives one back
-                const bool ok = more ? nwc[c] > 0 : nwc[c] > 1;
-                const bool better = pick < 0 || (more ? wc[c] * pn > pw * n : wc[c] * pn < pw * n);
-                if (ok && better) { pick = c; pw = wc[c]; pn = n; }
-            }
-            if (pick < 0) break;
+            const int n = more ? v_n : v_n - 1;
+            const bool ok = n > 0;
+            const float load = v_wc * __builtin_amdgcn_rcpf((float)max(n, 1));
+            const float key = ok ? (more ? load : -load) : -INFINITY;
+            float best = fmaxf(key, quad_mov_f<0xB1>(key));
+            best = fmaxf(best, quad_mov_f<0x4E>(best));
+            const unsigned long long hit = __builtin_amdgcn_ballot_w64(ok && key == best) & 0xFull;
+            if (hit == 0ull) break;
+            const int pick = (int)__builtin_ctzll(hit);
             const int d = more ? 1 : -1;
-#pragma unroll
-            for (int c = 0; c < kClasses; ++c)
-                if (c == pick) nwc[c] += d;
+            v_n += c4 == pick ? d : 0;
             used += d;
         }
         if (used == J) {
-            int jc = j;
+            const int n0 = quad_mov_i<0x00>(v_n), n1 = quad_mov_i<0x55>(v_n), n2 = quad_mov_i<0xAA>(v_n);     // class 0, 1, 2 to all
+            const int before = (c4 > 0 ? n0 : 0) + (c4 > 1 ? n1 : 0) + (c4 > 2 ? n2 : 0);
+            const int jc = j - before;
+            const bool mine = jc >= 0 && jc < v_n;
+            const float per_wave = (float)v_nu * __builtin_amdgcn_rcpf((float)max(v_n, 1));
+            const int v_first = mine ? min((int)((float)jc * per_wave), v_nu) : 0;
+            const int v_last = mine ? (jc + 1 == v_n ? v_nu : min((int)((float)(jc + 1) * per_wave), v_nu)) : 0;
 #pragma unroll
             for (int c = 0; c < kClasses; ++c) {
-                if (jc >= 0 && jc < nwc[c]) {
-                    const float per_wave = (float)nu[c] * __builtin_amdgcn_rcpf((float)nwc[c]);
-                    first[c] = min((int)((float)jc * per_wave), nu[c]);
-                    last[c] = jc + 1 == nwc[c] ? nu[c] : min((int)((float)(jc + 1) * per_wave), nu[c]);
-                }
-                jc -= nwc[c];
+                first[c] = __builtin_amdgcn_readlane(v_first, c);
+                last[c] = __builtin_amdgcn_readlane(v_last, c);
             }
             ranged = true;
         }
@@ -868,7 +939,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         // 64-bit division is a long emulated routine, and this runs before a wave's first load: 32 bits whenever
         // wtot * J fits (it does unless a context has millions of tokens)
         uint32_t lo_w, hi_w;
-        if (((unsigned long long)wtot * (uint32_t)J) >> 32 == 0) {
+        if (S == 1) {                                        // the usual case: divisions by a constant
+            if (((unsigned long long)wtot * (uint32_t)NW) >> 32 == 0) {
+                lo_w = wtot * (uint32_t)wave / (uint32_t)NW;
+                hi_w = wtot * (uint32_t)(wave + 1) / (uint32_t)NW;
+            } else {
+                lo_w = (uint32_t)((unsigned long long)wtot * (uint32_t)wave / (uint32_t)NW);
+                hi_w = (uint32_t)((unsigned long long)wtot * (uint32_t)(wave + 1) / (uint32_t)NW);
+            }
+        } else if (((unsigned long long)wtot * (uint32_t)J) >> 32 == 0) {
             lo_w = wtot * (uint32_t)j / (uint32_t)J;
             hi_w = wtot * (uint32_t)(j + 1) / (uint32_t)J;
         } else {
@@ -886,11 +965,25 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         }
     }
     ClassWalk w;
-    w.Hkv = cv.Hkv; w.kvh = kvh; w.bpp = cv.blocks_per_page; w.bpp_log2 = 31 - __builtin_clz(cv.blocks_per_page);
+    w.Hkv = Hkv; w.kvh = kvh; w.bpp = bpp; w.bpp_log2 = 31 - __builtin_clz(bpp);
+    // ---- batch 3: the page-table entry that each class's range starts in, when it is not entry 0 ----
+#define KVQ_PI0(C) (first[C] < last[C] ? first[C] >> units_per_page_log2<C>(w.bpp_log2) : 0)
+    const int pi0_0 = KVQ_PI0(0), pi0_1 = KVQ_PI0(1), pi0_2 = KVQ_PI0(2), pi0_3 = KVQ_PI0(3);
+    int pg0_0 = sp0, pg0_1 = sp1, pg0_2 = sp2, pg0_3 = sp3;
+    if ((pi0_0 | pi0_1 | pi0_2 | pi0_3) != 0) {
+        // (a range's first unit exists, so its page index is below max_pages_per_seq; the four loads travel together)
+        const int c4 = lane & 3;
+        const int pi_l = c4 == 0 ? pi0_0 : c4 == 1 ? pi0_1 : c4 == 2 ? pi0_2 : pi0_3;
+        const int b3v = pt_seq[(size_t)c4 * mpps + pi_l];
+        pg0_0 = __builtin_amdgcn_readlane(b3v, 0); pg0_1 = __builtin_amdgcn_readlane(b3v, 1);
+        pg0_2 = __builtin_amdgcn_readlane(b3v, 2); pg0_3 = __builtin_amdgcn_readlane(b3v, 3);
+    }
 #define KVQ_WALK(C)                                                                              \
-    w.pt = cv.page_table + ((size_t)seq * kClasses + (C)) * cv.max_pages_per_seq;                \
-    w.pool = cv.pool[C] + (size_t)P.layer * cv.layer_stride[C];                                  \
-    w.cnt = cnt[C];
+    w.pt = page_table + ((size_t)seq * kClasses + (C)) * mpps;                                   \
+    w.pool = cv.pool[C] + (size_t)layer * cv.layer_stride[C];                                    \
+    w.cnt = cnt[C];                                                                              \
+    w.pi0 = KVQ_PI0(C);                                                                          \
+    w.page0 = pg0_##C;
     if constexpr (!KCH) {
         KVQ_WALK(0) run_low<0>(w, first[0], last[0], step, lane, q2, q2, qc, cs, st);
         KVQ_WALK(1) run_low<1>(w, first[1], last[1], step, lane, q2, q2, qc, cs, st);
@@ -906,6 +999,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         if (first[2] < last[2]) { kch_prepare<2>(P, si, qh, kvh, lane, q2, q2l, qc); KVQ_WALK(2) run_8bit<true>(w, first[2], last[2], step, lane, q2, q2l, qc, st); }
     }
 #undef KVQ_WALK
+#undef KVQ_PI0
 
     // ---- the fused new token: quantized in registers, stored for later steps, one more partial result -----------
     float new_score = -INFINITY, new_v = 0.f;
@@ -1122,10 +1216,6 @@ static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t lay
     P.S = (int)S;
     const Tuning &tn = tuning();
     P.by_class = tn.attn_by_class;
-    // Relative cost of one unit of each class (2 bit: 128 tokens, 5 KiB; 4 bit: 64 tokens, 4.5 KiB; 8 bit: 8.5 KiB;
-    // FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost VALU time for unpacking,
-    // and the ratios below are the ones that equalise the finishing times of a workgroup's waves (measured).
-    P.wgt[0] = 14; P.wgt[1] = 11; P.wgt[2] = 17; P.wgt[3] = 32;
     const int nunits = (int)(heads * S);
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
