@@ -733,9 +733,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     // the units themselves, so the prologue is three batches of loads, each behind ONE wait:
     //   1. the arguments (the compiler would fetch each where it is first used, and wait for each on its own);
     //   2. everything that hangs on the sequence and head alone: the class counts, the newest-token record, the query
-    //      and entry 0 of the four page-table rows (one vector load, a word per lane: scalar loads that miss their
+    //      and the first six entries of the four page-table rows (one vector load, a word per lane: scalar loads that miss their
     //      cache are answered one line after the other, these travel side by side);
-    //   3. only for a wave whose range starts beyond a class's first page: the entries it starts at.
+    //   3. only for a wave whose range starts beyond a class's first six pages: the entries it starts at.
     int S = P.S, n_seq = P.n_seq, Hq = cv.Hq, Hkv = cv.Hkv;
     const int longest_first = P.longest_first, layer = P.layer, by_class = P.by_class;
     const int max_seqs = cv.max_seqs, mpps = cv.max_pages_per_seq, bpp = cv.blocks_per_page;
@@ -794,23 +794,25 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     if (!seq_ok) seq = 0;                                                    // row 0 exists: the loads below stay in bounds
 
     // ---- batch 2: ONE vector load instruction, a different address per lane, then lane reads into scalars ----
-    //   lanes 0..31 the query's fp16 pairs, 32..35 the class counts, 40..43 the newest-token record,
-    //   48..51 entry 0 of the four page-table rows; the other lanes repeat lane 0's word
+    //   lanes 0..31 the query's fp16 pairs, 32..35 the class counts, 36..39 the newest-token record,
+    //   40 + 6 c + e entry e < 6 of class c's page-table row (indices past the row's end repeat its last entry)
+    constexpr int kSpecLane = 40, kSpecPages = 6;
     const int32_t *const pt_seq = page_table + (size_t)seq * kClasses * mpps;
     const uint32_t *b2 = q_all + ((size_t)si * Hq + qh) * 32 + (lane < 32 ? lane : 0);
     if (lane >= 32 && lane < 36) b2 = (const uint32_t *)(counts + (size_t)seq * 5 + (lane - 32));
-    if (lane >= 40 && lane < 44) b2 = (const uint32_t *)(last_rec + (size_t)seq * 4 + (lane - 40));
-    if (lane >= 48 && lane < 52) b2 = (const uint32_t *)(pt_seq + (size_t)(lane - 48) * mpps);
+    if (lane >= 36 && lane < 40) b2 = (const uint32_t *)(last_rec + (size_t)seq * 4 + (lane - 36));
+    if (lane >= kSpecLane) {
+        const int sc = (lane - kSpecLane) / kSpecPages, se = (lane - kSpecLane) - sc * kSpecPages;
+        b2 = (const uint32_t *)(pt_seq + (size_t)sc * mpps + min(se, mpps - 1));
+    }
     const int b2v = (int)*b2;
     uint32_t q2[32];
 #pragma unroll
     for (int i = 0; i < 32; ++i) q2[i] = (uint32_t)__builtin_amdgcn_readlane(b2v, i);
     int cnt[kClasses] = {__builtin_amdgcn_readlane(b2v, 32), __builtin_amdgcn_readlane(b2v, 33), __builtin_amdgcn_readlane(b2v, 34),
                          __builtin_amdgcn_readlane(b2v, 35)};
-    int4 rec = make_int4(__builtin_amdgcn_readlane(b2v, 40), __builtin_amdgcn_readlane(b2v, 41), __builtin_amdgcn_readlane(b2v, 42),
-                         __builtin_amdgcn_readlane(b2v, 43));         // {last_T, bits, slot, page} of the newest token
-    const int sp0 = __builtin_amdgcn_readlane(b2v, 48), sp1 = __builtin_amdgcn_readlane(b2v, 49),
-              sp2 = __builtin_amdgcn_readlane(b2v, 50), sp3 = __builtin_amdgcn_readlane(b2v, 51);
+    int4 rec = make_int4(__builtin_amdgcn_readlane(b2v, 36), __builtin_amdgcn_readlane(b2v, 37), __builtin_amdgcn_readlane(b2v, 38),
+                         __builtin_amdgcn_readlane(b2v, 39));         // {last_T, bits, slot, page} of the newest token
     if (!seq_ok) cnt[0] = cnt[1] = cnt[2] = cnt[3] = 0;
     if (k_new == nullptr || !seq_ok) rec = make_int4(0, 0, 0, 0);
 
@@ -966,11 +968,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     }
     ClassWalk w;
     w.Hkv = Hkv; w.kvh = kvh; w.bpp = bpp; w.bpp_log2 = 31 - __builtin_clz(bpp);
-    // ---- batch 3: the page-table entry that each class's range starts in, when it is not entry 0 ----
+    // ---- batch 3: the page-table entry that each class's range starts in, when batch 2 has not brought it ----
 #define KVQ_PI0(C) (first[C] < last[C] ? first[C] >> units_per_page_log2<C>(w.bpp_log2) : 0)
     const int pi0_0 = KVQ_PI0(0), pi0_1 = KVQ_PI0(1), pi0_2 = KVQ_PI0(2), pi0_3 = KVQ_PI0(3);
-    int pg0_0 = sp0, pg0_1 = sp1, pg0_2 = sp2, pg0_3 = sp3;
-    if ((pi0_0 | pi0_1 | pi0_2 | pi0_3) != 0) {
+    int pg0_0, pg0_1, pg0_2, pg0_3;
+    if (max(max(pi0_0, pi0_1), max(pi0_2, pi0_3)) < kSpecPages) {
+        pg0_0 = __builtin_amdgcn_readlane(b2v, kSpecLane + pi0_0);
+        pg0_1 = __builtin_amdgcn_readlane(b2v, kSpecLane + kSpecPages + pi0_1);
+        pg0_2 = __builtin_amdgcn_readlane(b2v, kSpecLane + 2 * kSpecPages + pi0_2);
+        pg0_3 = __builtin_amdgcn_readlane(b2v, kSpecLane + 3 * kSpecPages + pi0_3);
+    } else {
         // (a range's first unit exists, so its page index is below max_pages_per_seq; the four loads travel together)
         const int c4 = lane & 3;
         const int pi_l = c4 == 0 ? pi0_0 : c4 == 1 ? pi0_1 : c4 == 2 ? pi0_2 : pi0_3;
