@@ -922,8 +922,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
             used += d;
         }
         if (used == J) {
-            const int n0 = quad_mov_i<0x00>(v_n), n1 = quad_mov_i<0x55>(v_n), n2 = quad_mov_i<0xAA>(v_n);     // class 0, 1, 2 to all
-            const int before = (c4 > 0 ? n0 : 0) + (c4 > 1 ? n1 : 0) + (c4 > 2 ? n2 : 0);
+            // The waves take the classes in the order 2 bit, 4 bit, FP16, 8 bit: waves i and i + 4 of an eight-wave workgroup
+            // share a SIMD, and this order pairs the class with the most unpacking arithmetic with the one that has none.
+            const int n0 = quad_mov_i<0x00>(v_n), n1 = quad_mov_i<0x55>(v_n), n3 = quad_mov_i<0xFF>(v_n);     // class 0, 1, 3 to all
+            const int before = (c4 > 0 ? n0 : 0) + (c4 > 1 ? n1 : 0) + (c4 == 2 ? n3 : 0);
             const int jc = j - before;
             const bool mine = jc >= 0 && jc < v_n;
             const float per_wave = (float)v_nu * __builtin_amdgcn_rcpf((float)max(v_n, 1));
