@@ -397,6 +397,17 @@ def main():
     half = probe.numel() // 2
     benchprobe.copy(probe[half:], probe[:half])
     torch.cuda.synchronize()
+    # what a trivial kernel reaches when it writes a byte for every three it reads (the prefill append's ratio): the
+    # last quarter of the buffer is written from the three quarters before it
+    quarter = probe.numel() // 4
+    for _ in range(2):
+        benchprobe.mix3(probe[3 * quarter:], probe[:3 * quarter])
+    p0.record()
+    for _ in range(5):
+        benchprobe.mix3(probe[3 * quarter:], probe[:3 * quarter])
+    p1.record()
+    torch.cuda.synchronize()
+    mix3_gbps = 5 * 4 * quarter / (p0.elapsed_time(p1) * 1e-3) / 1e9
     del probe
 
     # ---------------- prefill-stage kernels at this config's shape --------------------------------------
@@ -451,7 +462,8 @@ def main():
             "controller": {"rows": n_rows, "us": ctrl_us, "rows_per_s": n_rows / (ctrl_us * 1e-6),
                            "TFLOPs": 2 * macs * n_rows / (ctrl_us * 1e-6) / 1e12, "frac_of_fp32_mfma_peak": 2 * macs * n_rows / (ctrl_us * 1e-6) / 1e12 / 157.3},
             "append": {"tokens_per_seq_per_call": Tc, "bytes_per_call": app_bytes, "us_layer0_with_bookkeeping": us0, "us_other_layers": us1,
-                       "GBps_other_layers": app_bytes / (us1 * 1e-6) / 1e9, "frac_of_hbm_peak": app_bytes / (us1 * 1e-6) / 1e9 / HBM_PEAK_GBPS},
+                       "GBps_other_layers": app_bytes / (us1 * 1e-6) / 1e9, "frac_of_hbm_peak": app_bytes / (us1 * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                       "frac_of_stream_mix3": app_bytes / (us1 * 1e-6) / 1e9 / mix3_gbps},
             "note": "bulk controller (fp32 MFMA) on batch x context rows in one call; bulk append in 2048-token chunks, five layers "
                     "back to back per chunk with K/V of their own (median over the layers after the first); "
                     "algorithmic bytes = 256 B read + the class's bytes written per (token, kv-head)"}
@@ -580,6 +592,7 @@ def main():
                       "attn_per_layer": mixed.get("attn_us_per_layer"), "attn_per_layer_median": mixed.get("attn_us_median"),
                       "attn_per_layer_min": mixed.get("attn_us_min"), "attn_launches_timed": mixed.get("attn_launches_timed")},
         "stream_read_GBps": stream_gbps,
+        "stream_mix3_GBps": mix3_gbps,
         "fused_path": None if fused is None else {
             "us_per_step": fused["ms_per_step"] * 1e3, "launch_us_per_layer": fused.get("attn_us_per_layer"),
             "front_us": fused.get("front_us"),

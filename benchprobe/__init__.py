@@ -1,4 +1,4 @@
-"""Loader of ``libbenchprobe.so``: the benchmark's two measurement kernels (a streaming read and a plain copy).
+"""Loader of ``libbenchprobe.so``: the benchmark's measurement kernels (a streaming read, a plain copy, a 3:1 read/write mix).
 
 They are no part of the method and live outside the product library; ``bench.py`` times them next to the library's own
 kernels and uses the copy to calibrate hardware byte counters.
@@ -41,6 +41,7 @@ def load() -> ctypes.CDLL:
         vp, sz = ctypes.c_void_p, ctypes.c_size_t
         lib.benchprobe_read.argtypes = [vp, sz, vp, vp]
         lib.benchprobe_copy.argtypes = [vp, vp, sz, vp]
+        lib.benchprobe_mix3.argtypes = [vp, vp, sz, vp]
         _lib = lib
     return _lib
 
@@ -59,3 +60,13 @@ def copy(dst: torch.Tensor, src: torch.Tensor) -> None:
     rc = load().benchprobe_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), _stream())
     if rc:
         raise RuntimeError("benchprobe_copy failed (%d)" % rc)
+
+
+def mix3(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """dst = a ^ b ^ c, the three sources back to back in src (three times dst's size)"""
+    nbytes = dst.numel() * dst.element_size()
+    if src.numel() * src.element_size() < 3 * nbytes:
+        raise ValueError("src must hold three times dst's bytes")
+    rc = load().benchprobe_mix3(dst.data_ptr(), src.data_ptr(), nbytes, _stream())
+    if rc:
+        raise RuntimeError("benchprobe_mix3 failed (%d)" % rc)

@@ -1,6 +1,6 @@
 // Measurement helpers of the benchmark (a library of its own, libbenchprobe.so; no part of the method and not linked
-// into libkvq.so): a streaming read-reduce and a plain copy, used to find the HBM rate a trivial kernel attains on the
-// same device and to calibrate hardware byte counters against a transfer of known size.
+// into libkvq.so): a streaming read-reduce, a plain copy and a three-reads-per-write mix, used to find the HBM rate a
+// trivial kernel attains on the same device and to calibrate hardware byte counters against a transfer of known size.
 #include "benchprobe.h"
 
 #include <hip/hip_runtime.h>
@@ -65,6 +65,30 @@ __global__ __launch_bounds__(256) void k_probe_copy(uint4 *dst, const uint4 *src
     for (; i < end; i += 256) __builtin_nontemporal_store(__builtin_nontemporal_load((const u32x4 *)(src + i)), (u32x4 *)(dst + i));
 }
 
+// Three streams read for one written (dst[i] = a[i] ^ b[i] ^ c[i], the three sources back to back in src): the
+// read-to-write ratio of the prefill append (256 bytes in, 84 out per token and head on the benchmark's mix).
+__global__ __launch_bounds__(256) void k_probe_mix3(uint4 *dst, const uint4 *src, size_t n16)
+{
+    constexpr int U = 4;
+    size_t i, end;
+    probe_region(n16, &i, &end);
+    i += threadIdx.x;
+    for (; i + (U - 1) * 256 < end; i += U * 256) {
+        u32x4 v[U][3];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int r = 0; r < 3; ++r) v[u][r] = __builtin_nontemporal_load((const u32x4 *)(src + (size_t)r * n16 + i + u * 256));
+#pragma unroll
+        for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u][0] ^ v[u][1] ^ v[u][2], (u32x4 *)(dst + i + u * 256));
+    }
+    for (; i < end; i += 256) {
+        const u32x4 a = __builtin_nontemporal_load((const u32x4 *)(src + i)), b = __builtin_nontemporal_load((const u32x4 *)(src + n16 + i)),
+                    c = __builtin_nontemporal_load((const u32x4 *)(src + 2 * n16 + i));
+        __builtin_nontemporal_store(a ^ b ^ c, (u32x4 *)(dst + i));
+    }
+}
+
 }  // namespace benchprobe
 
 using namespace benchprobe;
@@ -88,5 +112,16 @@ extern "C" int benchprobe_copy(void *dst, const void *src, size_t bytes, void *s
     size_t blocks = (n16 + 256 * 8 - 1) / (256 * 8);
     if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (uint4 *)dst, (const uint4 *)src, n16);
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+extern "C" int benchprobe_mix3(void *dst, const void *src, size_t dst_bytes, void *stream)
+{
+    if (!src || !dst || (dst_bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return 1;
+    if (dst_bytes == 0) return 0;
+    const size_t n16 = dst_bytes / 16;
+    size_t blocks = (n16 + 256 * 4 - 1) / (256 * 4);
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(k_probe_mix3, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (uint4 *)dst, (const uint4 *)src, n16);
     return hipGetLastError() == hipSuccess ? 0 : 2;
 }

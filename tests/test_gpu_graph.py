@@ -101,3 +101,11 @@ def test_measurement_probes_copy_every_byte_and_read_in_bounds(n16):
     torch.cuda.synchronize()
     assert torch.equal(dst[:n16 * 4], src[:n16 * 4])
     assert bool((dst[n16 * 4:] == -7).all())
+    # three reads per write: dst = a ^ b ^ c, the sources back to back
+    src3 = torch.randint(0, 2 ** 31 - 1, (3 * n16 * 4,), dtype=torch.int32, generator=g).to(dev())
+    dst3 = torch.full((n16 * 4 + 8,), -7, dtype=torch.int32, device=dev())
+    benchprobe.mix3(dst3[:n16 * 4], src3)
+    torch.cuda.synchronize()
+    a, b, c = src3[:n16 * 4], src3[n16 * 4:2 * n16 * 4], src3[2 * n16 * 4:]
+    assert torch.equal(dst3[:n16 * 4], a ^ b ^ c)
+    assert bool((dst3[n16 * 4:] == -7).all())
