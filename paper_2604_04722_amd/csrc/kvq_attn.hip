@@ -771,10 +771,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         // A launch with more workgroups than fit at once is list scheduling in workgroup order: with the sequences in
         // arbitrary order the last round may start a long one (ragged batch: makespan up to 1.3x the mean).  So the
         // position si in the launch order takes the sequence of that RANK by length, longest first, dealt to the XCDs
-        // in turn (an XCD's k-th position has rank 8k + xcd).  Every workgroup ranks the (at most 64) lengths itself:
-        // lane = sequence, 64 lane reads.
+        // eight at a time, every other eight the other way round (an XCD's k-th position has rank 8k + xcd for even k,
+        // 8k + 7 - xcd for odd k: always in the same direction, XCD 0 would get the longest of every eight and 13 % more
+        // tokens than XCD 7 on lengths spread evenly over a 1:4 range).  Every workgroup ranks the (at most 64) lengths
+        // itself: lane = sequence, 64 lane reads.
         const int q8 = n_seq >> 3;
-        const int want = (si % q8) * 8 + si / q8;
+        const int lf_k = si % q8, lf_x = si / q8;
+        const int want = lf_k * 8 + ((lf_k & 1) ? 7 - lf_x : lf_x);
         int my_len = -1;
         if (lane < n_seq) {
             const int sq = seq_ids ? seq_ids[lane] : lane;
