@@ -48,9 +48,15 @@ template <> struct Cls<2> { static constexpr int U = 1, NCH = 4, NT = 1; };
 template <> struct Cls<3> { static constexpr int U = 1, NCH = 8, NT = 1; };
 
 // Relative cost of one unit of each class (2 bit: 128 tokens, 5 KiB; 4 bit: 64 tokens, 4.5 KiB; 8 bit: 8.5 KiB;
-// FP16: 16 KiB).  Bytes alone would give 10:9:17:32; the low-bit units also cost vector-ALU time for unpacking, and
-// these ratios are the ones that equalise the finishing times of a workgroup's waves (measured).
+// FP16: 16 KiB), by which a (sequence, head)'s units are cut into ranges for its waves.  Bytes alone would give
+// 10:9:17:32; the low-bit units also cost vector-ALU time for unpacking.  Two sets, both measured:
+//   kUnitCost       every wave of the launch resident at once: the kernel's length is what the memory system gives all
+//                   waves together, and these ratios (each class's time per unit when streamed alone) are the fastest;
+//   kUnitCostRounds more workgroups than places (several rounds): a workgroup keeps its place until its slower wave is
+//                   done, so the ratios that make a workgroup's waves END together win (time stamps on a ragged batch of
+//                   64: 171 / 142 us per wave with the first set, 162 / 159 us with this one, the kernel 430 -> 416 us).
 constexpr int kUnitCost[4] = {14, 11, 17, 32};
+constexpr int kUnitCostRounds[4] = {26, 16, 17, 32};
 
 // target multipliers M: h = 1 + c/M
 #define KVQ_M0_0 4.f      /* 2-bit codes at mantissa bits [8,10) */
@@ -144,6 +150,7 @@ struct AttnParams {
     float *out, *lse, *p2, *ws;
     int32_t layer, n_seq, S;
     int32_t longest_first;      // ragged batches over more than one round of workgroups: see k_decode_split
+    int32_t rounds;             // more workgroups than places: unit costs kUnitCostRounds
 };
 
 // Register budget: two waves per SIMD (256 VGPRs each).  The four-buffer ring, 64 accumulators and the per-class
@@ -737,7 +744,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     //      cache are answered one line after the other, these travel side by side);
     //   3. only for a wave whose range starts beyond a class's first six pages: the entries it starts at.
     int S = P.S, n_seq = P.n_seq, Hq = cv.Hq, Hkv = cv.Hkv;
-    const int longest_first = P.longest_first, layer = P.layer, by_class = P.by_class;
+    const int longest_first = P.longest_first, layer = P.layer, by_class = P.by_class, rounds_arg = P.rounds;
     const int max_seqs = cv.max_seqs, mpps = cv.max_pages_per_seq, bpp = cv.blocks_per_page;
     const int32_t *const seq_ids = P.seq_ids;
     const uint32_t *const q_all = P.q;
@@ -748,7 +755,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     // (the four that the work-item arithmetic starts from are outputs as well: nothing can then be scheduled ahead of
     // this point, behind a wait of its own for part of the loads)
     asm volatile("" : "+s"(S), "+s"(n_seq), "+s"(Hq), "+s"(Hkv)
-                 : "s"(longest_first), "s"(layer), "s"(by_class), "s"(max_seqs), "s"(mpps), "s"(bpp), "s"(seq_ids), "s"(q_all),
+                 : "s"(longest_first), "s"(layer), "s"(by_class), "s"(rounds_arg), "s"(max_seqs), "s"(mpps), "s"(bpp), "s"(seq_ids), "s"(q_all),
                    "s"(k_new), "s"(counts), "s"(last_rec), "s"(page_table), "s"(pool0));
     const uint32_t G = (uint32_t)Hq / (uint32_t)Hkv;
     const uint32_t nunits = (uint32_t)n_seq * (uint32_t)Hq * (uint32_t)S;
@@ -847,7 +854,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
     // weighted by their cost; the S workgroups x NW waves cut the list into S*NW contiguous ranges of
     // equal weight (a unit belongs to the range that holds its start), so a wave meets one or two classes.
     int nu[kClasses];
-    constexpr int wgt[kClasses] = {kUnitCost[0], kUnitCost[1], kUnitCost[2], kUnitCost[3]};
+    static_assert(kUnitCost[2] == kUnitCostRounds[2] && kUnitCost[3] == kUnitCostRounds[3], "the two sets differ in the low-bit classes only");
+    const bool rounds = rounds_arg != 0;
+    const int wgt[kClasses] = {rounds ? kUnitCostRounds[0] : kUnitCost[0], rounds ? kUnitCostRounds[1] : kUnitCost[1], kUnitCost[2], kUnitCost[3]};
     uint32_t wtot = 0;                                       // below 2^31: the host checks units x weight before the launch
     // Fused append: the newest token of the sequence (logged by the bookkeeping kernel, slot = last of its class)
     // is not read from the cache.  It is quantized in registers from k_new / v_new, joins the softmax as one extra
@@ -964,8 +973,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(KVQ_WAV
         uint32_t wbase = 0;
 #pragma unroll
         for (int c = 0; c < kClasses; ++c) {
-            const int klo = min(lo_w <= wbase ? 0 : ceil_div_pos(lo_w - wbase, (uint32_t)wgt[c]), nu[c]);
-            const int khi = min(hi_w <= wbase ? 0 : ceil_div_pos(hi_w - wbase, (uint32_t)wgt[c]), nu[c]);
+            // (divisions by constants: both sets' quotients and a select, no division instruction sequence)
+            const uint32_t dl = lo_w <= wbase ? 0u : lo_w - wbase, dh = hi_w <= wbase ? 0u : hi_w - wbase;
+            const int ql = rounds ? ceil_div_pos(dl, (uint32_t)kUnitCostRounds[c]) : ceil_div_pos(dl, (uint32_t)kUnitCost[c]);
+            const int qh_ = rounds ? ceil_div_pos(dh, (uint32_t)kUnitCostRounds[c]) : ceil_div_pos(dh, (uint32_t)kUnitCost[c]);
+            const int klo = min(ql, nu[c]);
+            const int khi = min(qh_, nu[c]);
             first[c] = klo;
             last[c] = khi;
             wbase += (uint32_t)nu[c] * (uint32_t)wgt[c];
@@ -1232,6 +1245,7 @@ static int launch_attn(const kvq_cache *cache, const AttnPlan &plan, int32_t lay
     const unsigned grid = (unsigned)(((nunits + 7) / 8) * 8);
     hipStream_t st = (hipStream_t)stream;
     P.longest_first = tn.attn_longest_first >= 0 ? tn.attn_longest_first : (n_seq <= 64 && n_seq % 8 == 0 && heads * S * nw > 2048) ? 1 : 0;
+    P.rounds = heads * S * nw > 2048 ? 1 : 0;
     if (n_seq > 64 || n_seq % 8 != 0) P.longest_first = 0;
     if (S > 1) P.longest_first = 0;                               // the merging kernel looks partial results up by output row
     if (!cache->view.k_channel) {
