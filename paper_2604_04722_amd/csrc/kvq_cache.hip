@@ -253,24 +253,46 @@ __global__ __launch_bounds__(64 * kAdvanceMaxWaves) void k_advance(CacheView cv,
 __global__ __launch_bounds__(256) void k_append_write(CacheView cv, int layer, const __half *k, const __half *v,
                                                       const int32_t *seq_ids, int n_seq, int T, long long total_vecs)
 {
-    const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
+    // This kernel runs once per layer and decode step and lives on latency: its arguments come in one batch of scalar
+    // loads behind one wait (the compiler would fetch each where it is first used and wait for each), and the wave's
+    // place in the launch is taken apart in 32-bit scalar arithmetic whenever the launch is small enough for that (the
+    // emulated 64-bit divisions were a third of the kernel's instructions).
+    int Hkv = cv.Hkv;
+    const int max_seqs = cv.max_seqs;
+    const int32_t *const last_rec_p = cv.last_rec;
+    const uint8_t *const pool0 = cv.pool[0];
+    asm volatile("" : "+s"(Hkv) : "s"(layer), "s"(k), "s"(v), "s"(seq_ids), "s"(n_seq), "s"(T), "s"(total_vecs), "s"(max_seqs),
+                 "s"(last_rec_p), "s"(pool0));
     const int lane = threadIdx.x & 63;
-    if (wave >= total_vecs) return;
-    long long r = wave;
-    const int h = (int)(r % cv.Hkv); r /= cv.Hkv;
-    const int t = (int)(r % T); r /= T;
-    const int si = (int)(r % n_seq);
-    const int li = (int)(r / n_seq);
+    int h, t, si, li;
+    if (total_vecs <= 0x7fffffffLL) {
+        const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)((blockIdx.x * 256u + threadIdx.x) >> 6));
+        if (wave >= (uint32_t)total_vecs) return;
+        uint32_t r = wave;
+        h = (int)(r % (uint32_t)Hkv); r /= (uint32_t)Hkv;
+        t = 0;
+        if (T != 1) { t = (int)(r % (uint32_t)T); r /= (uint32_t)T; }
+        si = (int)(r % (uint32_t)n_seq);
+        li = (int)(r / (uint32_t)n_seq);
+    } else {
+        const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
+        if (wave >= total_vecs) return;
+        long long r = wave;
+        h = (int)(r % Hkv); r /= Hkv;
+        t = (int)(r % T); r /= T;
+        si = (int)(r % n_seq);
+        li = (int)(r / n_seq);
+    }
     const int L = layer < 0 ? li : layer;
     const int seq = seq_ids ? seq_ids[si] : si;
-    if (seq < 0 || seq >= cv.max_seqs) return;
+    if (seq < 0 || seq >= max_seqs) return;
     // the vectors themselves do not depend on where they go: asked for first, they travel with the slot lookup
-    const size_t src = ((((size_t)li * n_seq + si) * T + t) * cv.Hkv + h) * kD + lane;
+    const size_t src = ((((size_t)li * n_seq + si) * T + t) * Hkv + h) * kD + lane;
     const __half kx = k[src], vx = v[src];
     int b, slot, page;
     if (T == 1) {
         // the decode step: everything about the new token in one 16-byte read
-        const int4 rec = *(const int4 *)(cv.last_rec + (size_t)seq * 4);
+        const int4 rec = *(const int4 *)(last_rec_p + (size_t)seq * 4);
         if (rec.x != 1) return;                                    // the bookkeeping call skipped this sequence
         b = rec.y; slot = rec.z; page = rec.w;
     } else {
