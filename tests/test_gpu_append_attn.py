@@ -237,6 +237,34 @@ def test_longest_first_launch_order_on_a_ragged_batch(B, fused):
             assert_export_equals(cache, 0, s_, oc)
 
 
+@pytest.mark.parametrize("waves", [0, 2, 8])
+def test_launch_of_several_rounds_ragged_batch_both_range_rules(waves):
+    """More workgroups than the device has places for (40 sequences x 32 query heads): the launch runs in rounds, takes its
+    sequences longest first (ranks dealt to the XCDs in alternating direction) and cuts the units by the second set of unit
+    costs; with 8 waves per workgroup and these short contexts the classes get whole waves, with 2 one cost range per wave."""
+    say("several rounds, ragged batch of 40, %d waves per workgroup" % waves)
+    B, Hq, Hkv, max_ctx = 40, 32, 4, 1024
+    rng = np.random.default_rng(4200 + waves)
+    lens = rng.integers(60, 700, B)
+    lens[3] = lens[17] = 333
+    cache = kvq.Cache(1, B, Hq, Hkv, max_ctx)
+    oc = OracleCache(B, Hkv)
+    for s_, n in enumerate(lens):
+        bits = rng.choice([2, 4, 8, 16], (1, n), p=[0.7, 0.2, 0.08, 0.02]).astype(np.uint8)
+        K, V = make_kv((1, n, Hkv, 64), 1700 + s_), make_kv((1, n, Hkv, 64), 1800 + s_)
+        ids = torch.tensor([s_], dtype=torch.int32, device=dev())
+        kvq.kvq_append(cache, 0, gpu_f16(K), gpu_f16(V), torch.from_numpy(bits).to(dev()), ids, 1, n)
+        oc.append(s_, K[0], V[0], bits[0])
+    q = make_kv((B, Hq, 64), 1900, outlier=False)
+    with tuning(attn_waves=waves):
+        out, lse, _ = run_attn(cache, 0, q, B, Hq)
+    for s_ in rng.choice(B, 10, replace=False):
+        want, want_lse, _ = oc.attn(int(s_), q[s_], Hq)
+        assert_attn_close(out[s_], want, "seq %d (%d tokens)" % (s_, lens[s_]))
+        np.testing.assert_allclose(lse[s_], want_lse, rtol=1e-4, atol=1e-4)
+    assert np.all(np.isfinite(out))
+
+
 def test_degenerate_vectors_constant_tiny_huge_and_signed_zero():
     say("degenerate vectors: constant, sub-resolution, +-65504, signed zeros")
     B, T, Hq, Hkv = 1, 8, 2, 2
