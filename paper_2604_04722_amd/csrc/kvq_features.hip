@@ -103,7 +103,9 @@ __device__ __forceinline__ Lse3 thread_partial(const T *logits, long long vocab,
 {
     constexpr int kPer = 16 / (int)sizeof(T);             // logits per 16-byte load
     const T *z = logits + row * vocab;
-    const long long per = (vocab + slices - 1) / slices;
+    // (a 64-bit division is a long emulated routine that would stand in front of the slice's first load)
+    const long long per = vocab <= 0x7fffffffLL ? (long long)(((uint32_t)vocab + (uint32_t)slices - 1u) / (uint32_t)slices)
+                                                : (vocab + slices - 1) / slices;
     long long lo = per * slice, hi = lo + per;
     if (hi > vocab) hi = vocab;
     Lse3 a = {-INFINITY, 0.f, 0.f};
@@ -211,12 +213,20 @@ __global__ __launch_bounds__(kFeatThreads) void k_lse_partial(const T *logits, l
     __shared__ Lse3 sm[kFeatThreads];
     const long long row = blockIdx.y;
     const int slice = blockIdx.x;
-    if (gather != nullptr && slice == 0 && threadIdx.x == 0) {
-        const long long id = token_ids[row];
-        gather[row * 2] = (id >= 0 && id < vocab) ? counts[id] : 0;       // an id outside the table counts as unseen
-        gather[row * 2 + 1] = totals[0] + totals[1];
+    // The copy is a chain of dependent reads (token id -> its count): the id is asked for ahead of the logits and the
+    // rest follows them, by a thread of the workgroup's last wavefront, which has the least to do in the merge -- in
+    // front of the slice's loads the chain made slice 0, and with it the launch, two memory round trips longer.
+    const bool copies = gather != nullptr && slice == 0 && threadIdx.x == kFeatThreads - 64;
+    long long id = -1, seen = 0;
+    if (copies) {
+        id = token_ids[row];
+        seen = totals[0] + totals[1];
     }
     sm[threadIdx.x] = thread_partial<T, Stream>(logits, vocab, slices, row, slice, threadIdx.x);
+    if (copies) {
+        gather[row * 2] = (id >= 0 && id < vocab) ? counts[id] : 0;       // an id outside the table counts as unseen
+        gather[row * 2 + 1] = seen;
+    }
     group_merge(sm, threadIdx.x);
     if (threadIdx.x == 0) {
         float *w = ws + (row * slices + slice) * 4;
